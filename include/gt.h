@@ -1,0 +1,234 @@
+/*
+ * gt.h -- C ABI of the MI355X (gfx950) GNN aggregation / combination library.
+ *
+ * The library implements the GPU hot path of GraphTensor (arXiv 2305.17469):
+ *   - `Pull`, the destination-centric, feature-wise neighbour aggregation  Y = A X  over an
+ *     in-edge CSR (paper: Preliminaries "Data representation"; Frontend section, the Pull
+ *     primitive), and its derivative, an aggregation whose outputs live on the source vertices
+ *     (paper: "Training for GNNs"), run over the transposed structure,
+ *   - `Apply`, the dense combination  act(M W + b)  and its derivatives (same sections),
+ *   - the kernel orchestrator's run-time choice between aggregation-first
+ *     act(A X W + b) = sigma(W f(h(X)) + b)  and combination-first  sigma(f(h(W X)) + b)
+ *     (paper: GNN Kernel Orchestrator, "Dynamic kernel placement" and the DKP cost model table).
+ *
+ * Conventions (hold for every entry point unless it says otherwise)
+ *   Layout     matrices are row-major, nodes x features; `ld*` is the row stride in ELEMENTS
+ *              (>= the logical width).  Rows whose stride in bytes and base address are
+ *              multiples of 16 take the vectorised kernels; anything else takes a slower
+ *              element-wise path with identical results up to summation order.
+ *   Pointers   every data pointer is a DEVICE pointer unless marked "host".  The caller owns
+ *              all device memory (inputs, outputs, workspaces); the library never allocates or
+ *              frees device memory and never keeps a pointer beyond what is stated.
+ *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute
+ *              calls only enqueue work and return; gt_graph_create synchronises the stream once.
+ *   dtype      GT_F32: fp32 storage and arithmetic.  GT_BF16: bf16 storage (round-to-nearest-
+ *              even on store), fp32 accumulation.
+ *   Errors     every call returns a gt_status; nothing throws, aborts or prints.  Arguments
+ *              are validated on the host (null pointers, negative sizes, ld < width, workspace
+ *              too small, unsupported combinations) BEFORE anything is launched; device array
+ *              CONTENTS are trusted (use gt_graph_validate to check them).
+ *              gt_last_error() gives a thread-local message for the last failing call.
+ *   Results    no floating-point atomics anywhere: results are bit-wise reproducible from run
+ *              to run for the same inputs and the same plan.
+ */
+#ifndef GT_H
+#define GT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GT_OK = 0,
+    GT_ERR_INVALID_ARG = 1,  /* null pointer, negative size, ld < width, aliasing in == out */
+    GT_ERR_UNSUPPORTED = 2,  /* e.g. symmetric norm on a non-square graph, E >= 2^31        */
+    GT_ERR_WORKSPACE = 3,    /* workspace pointer null / misaligned / too small             */
+    GT_ERR_HIP = 4,          /* a HIP runtime call failed (message in gt_last_error)        */
+    GT_ERR_INTERNAL = 5
+} gt_status;
+
+typedef enum { GT_F32 = 0, GT_BF16 = 1 } gt_dtype;
+
+/* Aggregation function f (paper: "Algorithm model", e.g. arithmetic mean; the `mode` string
+ * of Pull).  For destination v with in-edges e = (u -> v), per-edge scalar weight w_e (1 if
+ * the graph has none; the weighting function h of the paper restricted to scalars):
+ *   GT_SUM      Y[v] = sum_e w_e X[u]
+ *   GT_MEAN     Y[v] = (sum_e w_e X[u]) / indeg(v)           (0 for an empty row)
+ *   GT_SYMNORM  Y[v] = d(v)^-1/2 sum_e w_e d(u)^-1/2 X[u],   d = in-degree of the given CSR for
+ *               both ends, d^-1/2 := 0 where d = 0; square graphs (n_src == n_dst) only.
+ * GT_SYMNORM is not in the paper (its GCN is mean based); it is the usual GCN normalisation. */
+typedef enum { GT_SUM = 0, GT_MEAN = 1, GT_SYMNORM = 2 } gt_reduce;
+
+/* Kernel placement (paper: "Dynamic kernel placement").  For the backward pass the value names
+ * the derivative of that forward composition: GT_AGG_FIRST runs the transposed aggregation at
+ * width in_dim (dM = dZ W^T, then A^T dM), GT_COMB_FIRST at width out_dim (A^T dZ, then ... W^T). */
+typedef enum { GT_AUTO = 0, GT_AGG_FIRST = 1, GT_COMB_FIRST = 2 } gt_order;
+
+typedef enum { GT_ACT_NONE = 0, GT_ACT_RELU = 1 } gt_act;
+
+typedef struct gt_graph gt_graph; /* opaque HOST handle; borrows the caller's device arrays */
+
+/* ------------------------------------------------------------------------------------------
+ * Graph plan (once per graph / per sampled block).
+ * The paper keeps the forward structure in CSR and states that CSC suits the backward pass
+ * ("Training for GNNs"); it does not say how CSC is obtained.  Here it is built once per graph:
+ * degrees, the transposed structure (rows by source, entries ordered by position in the given
+ * CSR, i.e. a stable sort), and the degree-binned work lists that split long rows.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Bytes of device workspace gt_graph_create needs (host out-pointer).  */
+gt_status gt_graph_plan_size(int64_t n_dst, int64_t n_src, int64_t n_edges, int has_edge_weight,
+                             size_t *ws_bytes /* host */);
+
+/* rowptr[n_dst+1], colidx[n_edges] (source ids in [0, n_src)), edge_weight[n_edges] or NULL:
+ * device, int32/fp32, borrowed until gt_graph_destroy.  ws: device, 256-byte aligned, at
+ * least gt_graph_plan_size bytes, borrowed likewise (it holds the plan).  Enqueues the plan
+ * kernels on `stream` and synchronises it once to read back the work-list sizes.
+ * Errors: INVALID_ARG (null/negative), UNSUPPORTED (n_edges or n_* >= 2^31 - 1), WORKSPACE, HIP. */
+gt_status gt_graph_create(gt_graph **g /* host out */, int64_t n_dst, int64_t n_src, int64_t n_edges,
+                          const int32_t *rowptr, const int32_t *colidx, const float *edge_weight,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/* Frees the host handle only. */
+gt_status gt_graph_destroy(gt_graph *g);
+
+/* Device pointers into the plan (any out-pointer may be NULL): in_deg[n_dst], out_deg[n_src],
+ * rowptr_t[n_src+1], colidx_t[n_edges] (destination of each transposed entry), perm[n_edges]
+ * (position of that entry in the given CSR).  All int32 and exactly defined (bit-exact). */
+gt_status gt_graph_outputs(const gt_graph *g, const int32_t **in_deg, const int32_t **out_deg,
+                           const int32_t **rowptr_t, const int32_t **colidx_t, const int32_t **perm);
+
+/* Host-side sizes of the plan: n_dst, n_src, n_edges, and the number of work items / split
+ * rows of the forward and transposed schedules (any out-pointer may be NULL). */
+gt_status gt_graph_info(const gt_graph *g, int64_t *n_dst, int64_t *n_src, int64_t *n_edges,
+                        int64_t *fwd_items, int64_t *fwd_split_rows, int64_t *bwd_items,
+                        int64_t *bwd_split_rows);
+
+/* Debug check of the borrowed arrays: counts rowptr[0] != 0, rowptr[n_dst] != n_edges,
+ * decreasing rowptr, colidx outside [0, n_src).  Synchronises; *n_violations is a host int64. */
+gt_status gt_graph_validate(const gt_graph *g, int64_t *n_violations /* host */, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Aggregation (Pull) and its derivative.
+ * ------------------------------------------------------------------------------------------ */
+
+/* Bytes of scratch an aggregation at width F needs on this graph (fp32 partial rows of the
+ * split long rows; 0 if no row is split).  Covers both directions. */
+gt_status gt_aggregate_ws_size(const gt_graph *g, int64_t F, size_t *ws_bytes /* host */);
+
+/* Y[n_dst, F] = A X,  X[n_src, F];  see gt_reduce.  X and Y must not overlap.  ws: device
+ * scratch of at least gt_aggregate_ws_size bytes (may be NULL when that is 0), 256-byte aligned;
+ * its contents are overwritten.  Errors: INVALID_ARG, UNSUPPORTED (SYMNORM on a non-square
+ * graph), WORKSPACE.  n_dst == 0 or F == 0 is a valid no-op; empty rows give zeros. */
+gt_status gt_aggregate_fwd(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, int64_t F,
+                           const void *X, int64_t ldx, void *Y, int64_t ldy,
+                           void *ws, size_t ws_bytes, void *stream);
+
+/* dX[n_src, F] = A^T dY,  dY[n_dst, F]: the derivative of gt_aggregate_fwd with the same
+ * per-edge coefficients (edge weights are constants: no gradient is produced for them). */
+gt_status gt_aggregate_bwd(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, int64_t F,
+                           const void *dY, int64_t lddy, void *dX, int64_t lddx,
+                           void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Combination (Apply): C[M,N] = act(op(A) op(B) + bias), op(A) is M x K, op(B) is K x N.
+ *   transA = 0: A stored M x K (lda >= K);  transA = 1: A stored K x M (lda >= M).
+ *   transB = 0: B stored K x N (ldb >= N);  transB = 1: B stored N x K (ldb >= K).
+ * A and B have type `dtype`; C has type `c_dtype` (fp32 accumulation in MFMA either way; fp32
+ * data uses fp32 MFMA, bf16 data bf16 MFMA).  bias[N] fp32 or NULL.  transA = 1 is the weight
+ * gradient shape (reduction over the long node dimension): it is split over workgroups and
+ * summed in a fixed order from `ws` (size from gt_combine_ws_size; 0 otherwise).
+ * ------------------------------------------------------------------------------------------ */
+gt_status gt_combine_ws_size(gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                             size_t *ws_bytes /* host */);
+
+gt_status gt_combine(gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                     const void *A, int64_t lda, const void *B, int64_t ldb,
+                     const float *bias, gt_act act, void *C, int64_t ldc, gt_dtype c_dtype,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
+ * One GNN layer with dynamic kernel placement:
+ *   H'[n_dst, out_dim] = act( A X W  (+ X[0:n_dst] W_root)  + b ),   X[n_src, in_dim].
+ * has_root = 1 adds the root (self) linear of a GraphSAGE-style layer: the destinations are the
+ * first n_dst source ids of the block.  need_dx = 0 marks the first layer of a model: only
+ * parameter gradients are wanted, so an aggregation-first backward needs no transposed
+ * aggregation at all (paper: cost-model paragraph on the first GNN layer).
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+    gt_reduce reduce;
+    gt_dtype dtype;
+    gt_act act;
+    int64_t in_dim, out_dim;
+    int has_root;
+    int need_dx;
+} gt_layer_desc;
+
+/* Coefficients of the kernel-time model behind the placement decision (paper: "DKP cost model
+ * and parameters"): combination of `rows` rows takes rows*(alpha*in*out + beta*width) and an
+ * aggregation at width F takes F*(gamma*n_edge + delta*n_out); separate sets for the forward
+ * (FWP) and backward (BWP) pass.  Differences of these times are exactly the four "benefit"
+ * formulas of the paper's table.  Units: seconds.  The paper's own constants were fitted on
+ * another GPU and are NOT the defaults; gt_calibrate refits them on this device. */
+typedef struct {
+    double alpha_fwd, beta_fwd, gamma_fwd, delta_fwd;
+    double alpha_bwd, beta_bwd, gamma_bwd, delta_bwd;
+} gt_cost_coeffs;
+
+gt_status gt_cost_get(gt_cost_coeffs *c /* host */);
+gt_status gt_cost_set(const gt_cost_coeffs *c /* host */);
+
+/* The four benefit values of the paper's cost-model table for the given sizes and coefficients
+ * (pure host arithmetic): aggr-first FWP/BWP, comb-first FWP/BWP.  first_layer != 0 uses n_src
+ * as the BWP reduction factor of aggr-first, as the paper prescribes for the first layer. */
+gt_status gt_cost_benefits(const gt_cost_coeffs *c, int64_t n_src, int64_t n_dst, int64_t n_edge,
+                           int64_t n_feat, int64_t n_hid, int first_layer,
+                           double *aggr_fwd, double *aggr_bwd, double *comb_fwd, double *comb_bwd);
+
+/* Placement for this layer on this graph (pure host, deterministic): comb-first iff its benefit
+ * is strictly larger; a tie keeps the original aggregation-first order.  With need_dx = 0 the
+ * forward and backward are decided together (the backward can only skip the aggregation if the
+ * forward ran aggregation-first and saved A X). */
+gt_status gt_layer_decide(const gt_graph *g, const gt_layer_desc *d, gt_order *fwd, gt_order *bwd);
+
+/* Device bytes for `saved` (activations the backward needs, written by gt_layer_fwd) and for
+ * `scratch` (temporaries of either call), for any order. */
+gt_status gt_layer_ws_size(const gt_graph *g, const gt_layer_desc *d,
+                           size_t *saved_bytes /* host */, size_t *scratch_bytes /* host */);
+
+/* X[n_src,in_dim] (ldx), W[in_dim,out_dim] and W_root (dense, ld = out_dim; NULL iff !has_root)
+ * in d->dtype, b[out_dim] fp32 or NULL, Y[n_dst,out_dim] (ldy) in d->dtype.  `req` forces an
+ * order or GT_AUTO; *used (host, may be NULL) receives the order that ran. */
+gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_order req,
+                       const void *X, int64_t ldx, const void *W, const void *W_root, const float *b,
+                       void *Y, int64_t ldy, void *saved, void *scratch, gt_order *used, void *stream);
+
+/* dY[n_dst,out_dim] in d->dtype; X, W, W_root, Y, saved as given to / produced by gt_layer_fwd
+ * with forward order `fwd_used`.  Outputs: dX[n_src,in_dim] in d->dtype (NULL iff !need_dx),
+ * dW[in_dim,out_dim], dW_root (NULL iff !has_root), db[out_dim] (may be NULL): always fp32,
+ * overwritten (not accumulated).  `req` forces the backward order or GT_AUTO. */
+gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_order fwd_used, gt_order req,
+                       const void *dY, int64_t lddy, const void *X, int64_t ldx,
+                       const void *W, const void *W_root, const void *Y, int64_t ldy,
+                       const void *saved, void *scratch,
+                       void *dX, int64_t lddx, float *dW, float *dW_root, float *db,
+                       gt_order *used, void *stream);
+
+/* Refit the cost coefficients by least squares from kernel times measured on this device
+ * (paper: coefficients are fitted from measured kernel times at the start of training).  Runs
+ * synthetic aggregations and combinations inside `ws` (device, >= gt_calibrate_ws_size bytes);
+ * synchronises.  The fitted values are installed (as by gt_cost_set) and returned in *fitted. */
+gt_status gt_calibrate_ws_size(size_t *ws_bytes /* host */);
+gt_status gt_calibrate(void *ws, size_t ws_bytes, gt_cost_coeffs *fitted /* host, may be NULL */, void *stream);
+
+const char *gt_status_string(gt_status s);
+const char *gt_last_error(void);
+const char *gt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GT_H */

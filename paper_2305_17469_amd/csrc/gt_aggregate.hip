@@ -1,0 +1,364 @@
+// Neighbour aggregation (the paper's Pull primitive) and its derivative, as one gather-reduce
+// kernel family over a work list.
+//
+// Prior art kept from the paper (Frontend section, "GNN graph aware scheduling" and the Pull
+// description): traversal is destination-centric, all features of one output row are handled by
+// one group of lanes spread over the feature columns, the running sum stays in registers and the
+// row is written once, so no atomics or locks are needed.  What differs for CDNA4 and for full
+// power-law graphs: a "group" is G = 4..64 lanes of a 64-wide wavefront, each lane moving
+// 16 bytes per gathered row, so narrow rows still issue full-width memory instructions; rows
+// longer than GT_SPLIT_MIN entries are cut into GT_CHUNK-entry work items whose fp32 partial rows
+// are added by a second kernel in chunk order (deterministic, no floating-point atomics); work
+// items are ordered longest first so the groups of a wavefront see similar trip counts.
+//
+// The same kernels serve the backward pass on the transposed structure: the derivative of the
+// aggregation is an aggregation whose outputs are the source vertices (paper, "Training for
+// GNNs").
+#include "gt_internal.h"
+
+namespace {
+
+struct AggArgs {
+    const gt_item *items;
+    int64_t n_items;
+    const int32_t *rowptr;   // of the output rows (for the mean's divisor)
+    const int32_t *nbr;
+    const float *wt;         // per-entry weight or null
+    const float *pre;        // per-neighbour scale or null
+    const float *post;       // per-output-row scale (post_mode 1) or null
+    int post_mode;           // 0 none, 1 multiply by post[row], 2 divide by the row's entry count
+    const float *bias;       // per-column bias added after scaling, or null
+    int relu;
+    const void *X;
+    int64_t ldx;
+    void *Y;
+    int64_t ldy;
+    int64_t F;
+    float *partials;         // [n_partials][ldp]
+    int64_t ldp;
+    const gt_split *splits;
+    int64_t n_splits;
+};
+
+typedef uint16_t bf16_t;
+
+__device__ inline float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+__device__ inline uint32_t f32_to_bf16(float f) {   // round to nearest even; NaN stays NaN
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+// V consecutive elements starting at p (p is 16-byte aligned when V > 1) -> fp32
+template <typename T, int V>
+__device__ inline void load_vec(const T *p, float (&out)[V]);
+
+template <>
+__device__ inline void load_vec<float, 4>(const float *p, float (&out)[4]) {
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+template <>
+__device__ inline void load_vec<float, 1>(const float *p, float (&out)[1]) { out[0] = *p; }
+template <>
+__device__ inline void load_vec<bf16_t, 8>(const bf16_t *p, float (&out)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+    out[0] = __uint_as_float(v.x << 16); out[1] = __uint_as_float(v.x & 0xffff0000u);
+    out[2] = __uint_as_float(v.y << 16); out[3] = __uint_as_float(v.y & 0xffff0000u);
+    out[4] = __uint_as_float(v.z << 16); out[5] = __uint_as_float(v.z & 0xffff0000u);
+    out[6] = __uint_as_float(v.w << 16); out[7] = __uint_as_float(v.w & 0xffff0000u);
+}
+template <>
+__device__ inline void load_vec<bf16_t, 1>(const bf16_t *p, float (&out)[1]) { out[0] = bf16_to_f32(*p); }
+
+// store the first `n` (<= V) of V values; full vectors go out as 16-byte stores
+template <typename T, int V>
+__device__ inline void store_vec(T *p, const float (&v)[V], int n);
+
+template <>
+__device__ inline void store_vec<float, 4>(float *p, const float (&v)[4], int n) {
+    if (n >= 4) {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+        for (int i = 0; i < n; ++i) p[i] = v[i];
+    }
+}
+template <>
+__device__ inline void store_vec<float, 1>(float *p, const float (&v)[1], int n) { if (n > 0) p[0] = v[0]; }
+template <>
+__device__ inline void store_vec<bf16_t, 8>(bf16_t *p, const float (&v)[8], int n) {
+    if (n >= 8) {
+        uint4 o;
+        o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+        o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+        o.z = f32_to_bf16(v[4]) | (f32_to_bf16(v[5]) << 16);
+        o.w = f32_to_bf16(v[6]) | (f32_to_bf16(v[7]) << 16);
+        *reinterpret_cast<uint4 *>(p) = o;
+    } else {
+        for (int i = 0; i < n; ++i) p[i] = (bf16_t)f32_to_bf16(v[i]);
+    }
+}
+template <>
+__device__ inline void store_vec<bf16_t, 1>(bf16_t *p, const float (&v)[1], int n) {
+    if (n > 0) p[0] = (bf16_t)f32_to_bf16(v[0]);
+}
+
+// scale, bias, activation and store of one finished output row segment
+template <typename T, int V, int G, int NP>
+__device__ inline void finish_row(const AggArgs &a, int row, int gl, int64_t col0, float (&acc)[NP][V]) {
+    float mul = 1.0f;
+    bool zero = false;
+    float div = 1.0f;
+    if (a.post_mode == 1) {
+        mul = a.post[row];
+    } else if (a.post_mode == 2) {
+        const int d = a.rowptr[row + 1] - a.rowptr[row];
+        zero = d <= 0;
+        div = (float)(d > 0 ? d : 1);
+    }
+    T *y = static_cast<T *>(a.Y) + (int64_t)row * a.ldy;
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int64_t col = col0 + (int64_t)(p * G + gl) * V;
+        if (col >= a.F) continue;
+        const int n = (int)((a.F - col) < V ? (a.F - col) : V);
+        float o[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            float x = acc[p][i];
+            if (a.post_mode == 1) x *= mul;
+            if (a.post_mode == 2) x = zero ? 0.0f : x / div;
+            if (a.bias && i < n) x += a.bias[col + i];
+            if (a.relu) x = x > 0.0f ? x : 0.0f;
+            o[i] = x;
+        }
+        store_vec<T, V>(y + col, o, n);
+    }
+}
+
+// One group of G lanes per work item; 64/G items per wavefront; 4 wavefronts per workgroup.
+// blockIdx.y selects a column tile of G*V*NP columns.
+template <typename T, int V, int G, int NP, int U>
+__global__ void __launch_bounds__(256) k_aggregate(const AggArgs a) {
+    constexpr int NG = 64 / G;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int gl = lane & (G - 1);
+    const int grp = lane / G;
+    const int64_t item_id = ((int64_t)blockIdx.x * 4 + wave) * NG + grp;
+    if (item_id >= a.n_items) return;   // whole groups leave together; no barriers are used below
+    const int4 raw = reinterpret_cast<const int4 *>(a.items)[item_id];
+    const int row = raw.x, e0 = raw.y, e1 = raw.z, slot = raw.w;
+    const int64_t col0 = (int64_t)blockIdx.y * (G * V * NP);
+    const T *X = static_cast<const T *>(a.X);
+
+    float acc[NP][V];
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[p][i] = 0.0f;
+
+    for (int base = e0; base < e1; base += G) {
+        // the group fetches G neighbour ids and coefficients at once, then walks them
+        const int e = base + gl;
+        int idx = 0;
+        float c = 0.0f;
+        if (e < e1) {
+            idx = a.nbr[e];
+            c = a.wt ? a.wt[e] : 1.0f;
+            if (a.pre) c *= a.pre[idx];
+        }
+        const int cnt = (e1 - base) < G ? (e1 - base) : G;
+        for (int j = 0; j < cnt; j += U) {
+            float v[U][NP][V];
+            float cj[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int jj = j + u;
+                const int src = __shfl(idx, jj & (G - 1), G);
+                cj[u] = __shfl(c, jj & (G - 1), G);
+                const bool live = jj < cnt;
+                if (!live) cj[u] = 0.0f;
+                const T *xr = X + (int64_t)src * a.ldx;
+#pragma unroll
+                for (int p = 0; p < NP; ++p) {
+                    const int64_t col = col0 + (int64_t)(p * G + gl) * V;
+                    if (live && col < a.F) {
+                        load_vec<T, V>(xr + col, v[u][p]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < V; ++i) v[u][p][i] = 0.0f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int p = 0; p < NP; ++p)
+#pragma unroll
+                    for (int i = 0; i < V; ++i) acc[p][i] = fmaf(cj[u], v[u][p][i], acc[p][i]);
+        }
+    }
+
+    if (slot >= 0) {
+        float *P = a.partials + (int64_t)slot * a.ldp;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int64_t col = col0 + (int64_t)(p * G + gl) * V;
+            if (col >= a.F) continue;
+#pragma unroll
+            for (int i = 0; i < V; ++i)
+                if (col + i < a.F) P[col + i] = acc[p][i];
+        }
+    } else {
+        finish_row<T, V, G, NP>(a, row, gl, col0, acc);
+    }
+}
+
+// Second pass for split rows: add the row's partial rows in chunk order.
+template <typename T, int V, int G, int NP>
+__global__ void __launch_bounds__(256) k_reduce_partials(const AggArgs a) {
+    constexpr int NG = 64 / G;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int gl = lane & (G - 1);
+    const int grp = lane / G;
+    const int64_t sid = ((int64_t)blockIdx.x * 4 + wave) * NG + grp;
+    if (sid >= a.n_splits) return;
+    const gt_split s = a.splits[sid];
+    const int64_t col0 = (int64_t)blockIdx.y * (G * V * NP);
+    float acc[NP][V];
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[p][i] = 0.0f;
+    for (int k = 0; k < s.count; ++k) {
+        const float *P = a.partials + (int64_t)(s.first + k) * a.ldp;
+#pragma unroll
+        for (int p = 0; p < NP; ++p) {
+            const int64_t col = col0 + (int64_t)(p * G + gl) * V;
+#pragma unroll
+            for (int i = 0; i < V; ++i)
+                if (col + i < a.F) acc[p][i] += P[col + i];
+        }
+    }
+    finish_row<T, V, G, NP>(a, s.row, gl, col0, acc);
+}
+
+template <typename T, int V, int G, int NP, int U>
+gt_status launch(const AggArgs &a, hipStream_t st) {
+    constexpr int NG = 64 / G;
+    const int64_t tile = (int64_t)G * V * NP;
+    const unsigned gy = (unsigned)((a.F + tile - 1) / tile);
+    if (a.n_items > 0) {
+        const int64_t gx = (a.n_items + 4 * NG - 1) / (4 * NG);
+        k_aggregate<T, V, G, NP, U><<<dim3((unsigned)gx, gy), 256, 0, st>>>(a);
+        GT_LAUNCH_CHECK("k_aggregate");
+    }
+    if (a.n_splits > 0) {
+        const int64_t gx = (a.n_splits + 4 * NG - 1) / (4 * NG);
+        k_reduce_partials<T, V, G, NP><<<dim3((unsigned)gx, gy), 256, 0, st>>>(a);
+        GT_LAUNCH_CHECK("k_reduce_partials");
+    }
+    return GT_OK;
+}
+
+template <typename T, int V>
+gt_status dispatch(const AggArgs &a, hipStream_t st) {
+    const int64_t nvec = (a.F + V - 1) / V;   // lanes needed to cover one row
+    if (nvec <= 4) return launch<T, V, 4, 1, 4>(a, st);
+    if (nvec <= 8) return launch<T, V, 8, 1, 4>(a, st);
+    if (nvec <= 16) return launch<T, V, 16, 1, 4>(a, st);
+    if (nvec <= 32) return launch<T, V, 32, 1, 4>(a, st);
+    if (nvec <= 64) return launch<T, V, 64, 1, 4>(a, st);
+    if (nvec <= 128) return launch<T, V, 64, 2, 2>(a, st);
+    if (nvec <= 192) return launch<T, V, 64, 3, 2>(a, st);
+    return launch<T, V, 64, 4, 2>(a, st);   // wider rows take several column tiles (grid.y)
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+size_t gt_aggregate_ws_bytes(const gt_graph *g, int64_t F) {
+    const int64_t ldp = (F + 7) / 8 * 8;
+    const int64_t parts = g->fwd.n_partials > g->bwd.n_partials ? g->fwd.n_partials : g->bwd.n_partials;
+    return gt_align_up((size_t)parts * (size_t)ldp * 4);
+}
+
+gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce, gt_dtype in_dtype, gt_dtype out_dtype,
+                           int64_t F, const void *X, int64_t ldx, void *Y, int64_t ldy, const float *bias, gt_act act,
+                           void *ws, size_t ws_bytes, hipStream_t st) {
+    const char *fn = transposed ? "gt_aggregate_bwd" : "gt_aggregate_fwd";
+    if (!g) return gt_fail(GT_ERR_INVALID_ARG, "%s: g is null", fn);
+    if (F < 0) return gt_fail(GT_ERR_INVALID_ARG, "%s: F < 0", fn);
+    if (reduce != GT_SUM && reduce != GT_MEAN && reduce != GT_SYMNORM)
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown reduce %d", fn, (int)reduce);
+    if (in_dtype != GT_F32 && in_dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown dtype", fn);
+    if (in_dtype != out_dtype) return gt_fail(GT_ERR_UNSUPPORTED, "%s: input and output dtype must match", fn);
+    if (reduce == GT_SYMNORM && g->n_dst != g->n_src)
+        return gt_fail(GT_ERR_UNSUPPORTED, "%s: GT_SYMNORM needs a square graph (n_src == n_dst)", fn);
+    const gt_sched &sc = transposed ? g->bwd : g->fwd;
+    const int64_t n_in = transposed ? g->n_dst : g->n_src;
+    const int64_t n_out = sc.n_rows;
+    if (F == 0 || n_out == 0) return GT_OK;
+    if (!Y) return gt_fail(GT_ERR_INVALID_ARG, "%s: output pointer is null", fn);
+    if (!X && n_in > 0) return gt_fail(GT_ERR_INVALID_ARG, "%s: input pointer is null", fn);
+    if (ldx < F || ldy < F) return gt_fail(GT_ERR_INVALID_ARG, "%s: leading dimension smaller than F", fn);
+    const size_t es = gt_dtype_size(in_dtype);
+    if (((uintptr_t)X % es) || ((uintptr_t)Y % es)) return gt_fail(GT_ERR_INVALID_ARG, "%s: pointer misaligned for dtype", fn);
+    {
+        const char *xb = (const char *)X, *xe = xb + (size_t)n_in * ldx * es;
+        const char *yb = (const char *)Y, *ye = yb + (size_t)n_out * ldy * es;
+        if (X && xb < ye && yb < xe) return gt_fail(GT_ERR_INVALID_ARG, "%s: input and output overlap", fn);
+    }
+    const size_t need = sc.n_partials > 0 ? gt_aggregate_ws_bytes(g, F) : 0;
+    if (need > 0) {
+        if (!ws || ((uintptr_t)ws & 255)) return gt_fail(GT_ERR_WORKSPACE, "%s: ws null or not 256-byte aligned", fn);
+        if (ws_bytes < need) return gt_fail(GT_ERR_WORKSPACE, "%s: ws_bytes %zu < required %zu", fn, ws_bytes, need);
+    }
+
+    AggArgs a{};
+    a.items = sc.items; a.n_items = sc.n_items;
+    a.rowptr = sc.rowptr; a.nbr = sc.nbr; a.wt = sc.wt;
+    a.pre = nullptr; a.post = nullptr; a.post_mode = 0;
+    if (reduce == GT_MEAN) {
+        if (!transposed) a.post_mode = 2;   // divide by the destination's in-degree
+        else a.pre = g->rdeg;               // each term carries 1/indeg of its destination
+    } else if (reduce == GT_SYMNORM) {
+        a.pre = g->dinv; a.post = g->dinv; a.post_mode = 1;
+    }
+    a.bias = bias; a.relu = (act == GT_ACT_RELU);
+    a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy; a.F = F;
+    a.partials = static_cast<float *>(ws); a.ldp = (F + 7) / 8 * 8;
+    a.splits = sc.splits; a.n_splits = sc.n_splits;
+
+    if (in_dtype == GT_F32) {
+        const bool vec = aligned16(X) && aligned16(Y) && (ldx % 4 == 0) && (ldy % 4 == 0);
+        return vec ? dispatch<float, 4>(a, st) : dispatch<float, 1>(a, st);
+    }
+    const bool vec = aligned16(X) && aligned16(Y) && (ldx % 8 == 0) && (ldy % 8 == 0);
+    return vec ? dispatch<bf16_t, 8>(a, st) : dispatch<bf16_t, 1>(a, st);
+}
+
+extern "C" gt_status gt_aggregate_ws_size(const gt_graph *g, int64_t F, size_t *ws_bytes) {
+    if (!g || !ws_bytes) return gt_fail(GT_ERR_INVALID_ARG, "gt_aggregate_ws_size: null argument");
+    if (F < 0) return gt_fail(GT_ERR_INVALID_ARG, "gt_aggregate_ws_size: F < 0");
+    const bool any = g->fwd.n_partials > 0 || g->bwd.n_partials > 0;
+    *ws_bytes = any ? gt_aggregate_ws_bytes(g, F) : 0;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_aggregate_fwd(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, int64_t F, const void *X,
+                                      int64_t ldx, void *Y, int64_t ldy, void *ws, size_t ws_bytes, void *stream) {
+    return gt_aggregate_run(g, false, reduce, dtype, dtype, F, X, ldx, Y, ldy, nullptr, GT_ACT_NONE, ws, ws_bytes,
+                            (hipStream_t)stream);
+}
+
+extern "C" gt_status gt_aggregate_bwd(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, int64_t F, const void *dY,
+                                      int64_t lddy, void *dX, int64_t lddx, void *ws, size_t ws_bytes, void *stream) {
+    return gt_aggregate_run(g, true, reduce, dtype, dtype, F, dY, lddy, dX, lddx, nullptr, GT_ACT_NONE, ws, ws_bytes,
+                            (hipStream_t)stream);
+}

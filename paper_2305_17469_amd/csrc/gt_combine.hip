@@ -1,0 +1,373 @@
+// Combination (the paper's Apply primitive: linear transform, bias, non-linearity) and its
+// derivatives, as one LDS-tiled MFMA GEMM family:  C = act(op(A) op(B) + C_in + bias).
+//
+// The paper delegates this step to a vendor GEMM (Frontend section, Apply); here it is written
+// for CDNA4: 64-lane wavefronts own 64x64 accumulator tiles built from 32x32 MFMA blocks
+// (fp32 MFMA for fp32 data so fp32 accuracy is kept, bf16 MFMA with fp32 accumulation for bf16
+// data), operands are staged through LDS in whichever layout their global layout gives without
+// a transposing store, the next k-tile is prefetched into registers while the current one is
+// multiplied, and the weight-gradient shape (reduction over the node dimension) is split over
+// workgroups and summed in a fixed order, so results are reproducible.
+#include "gt_internal.h"
+#include "gt_combine.h"
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint16_t bf16_t;
+
+constexpr int KT = 32;   // k-tile
+
+__device__ inline uint32_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ inline float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+template <typename T> struct Elem;
+template <> struct Elem<float> { static constexpr int VE = 4; static constexpr int PAD = 4; };
+template <> struct Elem<bf16_t> { static constexpr int VE = 8; static constexpr int PAD = 8; };
+
+struct GemmArgs {
+    const void *A; int64_t lda;
+    const void *B; int64_t ldb;
+    void *C; int64_t ldc;          // output (type c_bf16 ? bf16 : f32), or fp32 partials when splits > 1
+    const void *Cin; int64_t ldcin; // optional addend, same type as C
+    const float *bias;
+    const float *rowscale;         // optional per-row factor applied to the product before addend/bias
+    int relu;
+    int c_bf16;
+    int64_t M, N, K;
+    int64_t k_per_split;           // multiple of KT
+    int vecA, vecB;                // 16-byte loads allowed
+};
+
+// Global -> registers for a ROWS x COLS tile whose COLS direction is contiguous in memory.
+// Element (r, c) sits at p[(r0 + r) * ld + c0 + c]; anything at or beyond (rlim, clim) reads 0.
+template <typename T, int ROWS, int COLS>
+struct TileLoader {
+    static constexpr int VE = Elem<T>::VE;
+    static constexpr int VPR = COLS / VE;                 // vectors per tile row
+    static constexpr int TOTAL = ROWS * VPR;
+    static constexpr int NV = (TOTAL + 255) / 256;        // vectors per thread
+    uint4 reg[NV];
+
+    __device__ inline void load(const T *p, int64_t ld, int64_t r0, int64_t c0, int64_t rlim, int64_t clim, int vec) {
+#pragma unroll
+        for (int it = 0; it < NV; ++it) {
+            const int q = threadIdx.x + 256 * it;
+            const int r = q / VPR, c = (q % VPR) * VE;
+            const int64_t gr = r0 + r, gc = c0 + c;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if ((TOTAL % 256 == 0 || q < TOTAL) && gr < rlim && gc < clim) {
+                const T *src = p + gr * ld + gc;
+                if (vec && gc + VE <= clim) {
+                    v = *reinterpret_cast<const uint4 *>(src);
+                } else {
+                    T tmp[VE];
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) tmp[e] = (gc + e < clim) ? src[e] : (T)0;
+                    v = *reinterpret_cast<const uint4 *>(tmp);
+                }
+            }
+            reg[it] = v;
+        }
+    }
+    template <int STR>
+    __device__ inline void store(T *lds) const {
+#pragma unroll
+        for (int it = 0; it < NV; ++it) {
+            const int q = threadIdx.x + 256 * it;
+            const int r = q / VPR, c = (q % VPR) * VE;
+            if (TOTAL % 256 == 0 || q < TOTAL) *reinterpret_cast<uint4 *>(lds + r * STR + c) = reg[it];
+        }
+    }
+};
+
+// op(A)(i,k): TA ? A[k*lda+i] : A[i*lda+k];   op(B)(k,j): TB ? B[j*ldb+k] : B[k*ldb+j]
+template <typename T, bool TA, bool TB, int WGM, int WGN, int TM, int TN>
+__global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    constexpr int PAD = Elem<T>::PAD;
+    constexpr int ASTR = TA ? BM + PAD : KT + PAD;
+    constexpr int BSTR = TB ? KT + PAD : BN + PAD;
+    constexpr int A_ELEMS = TA ? KT * ASTR : BM * ASTR;
+    constexpr int B_ELEMS = TB ? BN * BSTR : KT * BSTR;
+    __shared__ __attribute__((aligned(16))) T As[A_ELEMS];
+    __shared__ __attribute__((aligned(16))) T Bs[B_ELEMS];
+    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
+    const int64_t kend = (kbeg + g.k_per_split < g.K) ? kbeg + g.k_per_split : g.K;
+    const T *A = static_cast<const T *>(g.A);
+    const T *B = static_cast<const T *>(g.B);
+
+    floatx16 acc[TM][TN];
+#pragma unroll
+    for (int a = 0; a < TM; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+
+    typedef TileLoader<T, TA ? KT : BM, TA ? BM : KT> LoadA;
+    typedef TileLoader<T, TB ? BN : KT, TB ? KT : BN> LoadB;
+    LoadA la;
+    LoadB lb;
+    auto fetch = [&](int64_t k0) {
+        if (TA) la.load(A, g.lda, k0, m0, kend, g.M, g.vecA); else la.load(A, g.lda, m0, k0, g.M, kend, g.vecA);
+        if (TB) lb.load(B, g.ldb, n0, k0, g.N, kend, g.vecB); else lb.load(B, g.ldb, k0, n0, kend, g.N, g.vecB);
+    };
+
+    if (kbeg < kend) fetch(kbeg);
+    for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
+        __syncthreads();                      // previous tile fully consumed
+        la.template store<ASTR>(As);
+        lb.template store<BSTR>(Bs);
+        __syncthreads();
+        if (k0 + KT < kend) fetch(k0 + KT);   // overlaps the MFMA work below
+
+        if constexpr (sizeof(T) == 4) {
+            // fp32: v_mfma_f32_32x32x2f32.  Lane half h owns k = h*16 + t of the tile at step t;
+            // both operands use the same assignment, so the sum over the tile is complete.
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                float af[TM][8], bf[TN][8];
+                const int kk = h * 16 + half * 8;
+#pragma unroll
+                for (int a = 0; a < TM; ++a) {
+                    const int i = (wm * TM + a) * 32 + l32;
+                    if constexpr (!TA) {
+                        const float4 x = *reinterpret_cast<const float4 *>(&As[i * ASTR + kk]);
+                        const float4 y = *reinterpret_cast<const float4 *>(&As[i * ASTR + kk + 4]);
+                        af[a][0] = x.x; af[a][1] = x.y; af[a][2] = x.z; af[a][3] = x.w;
+                        af[a][4] = y.x; af[a][5] = y.y; af[a][6] = y.z; af[a][7] = y.w;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) af[a][q] = As[(kk + q) * ASTR + i];
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    const int j = (wn * TN + b) * 32 + l32;
+                    if constexpr (TB) {
+                        const float4 x = *reinterpret_cast<const float4 *>(&Bs[j * BSTR + kk]);
+                        const float4 y = *reinterpret_cast<const float4 *>(&Bs[j * BSTR + kk + 4]);
+                        bf[b][0] = x.x; bf[b][1] = x.y; bf[b][2] = x.z; bf[b][3] = x.w;
+                        bf[b][4] = y.x; bf[b][5] = y.y; bf[b][6] = y.z; bf[b][7] = y.w;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) bf[b][q] = Bs[(kk + q) * BSTR + j];
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+#pragma unroll
+                    for (int a = 0; a < TM; ++a)
+#pragma unroll
+                        for (int b = 0; b < TN; ++b)
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a][q], bf[b][q], acc[a][b], 0, 0, 0);
+            }
+        } else {
+            // bf16: v_mfma_f32_32x32x16_bf16.  Lane half h supplies k = s*16 + h*8 .. +7.
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                bf16x8 af[TM], bf[TN];
+                const int kk = s * 16 + h * 8;
+#pragma unroll
+                for (int a = 0; a < TM; ++a) {
+                    const int i = (wm * TM + a) * 32 + l32;
+                    if constexpr (!TA) {
+                        af[a] = *reinterpret_cast<const bf16x8 *>(&As[i * ASTR + kk]);
+                    } else {
+                        bf16_t tmp[8];
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) tmp[q] = As[(kk + q) * ASTR + i];
+                        af[a] = *reinterpret_cast<const bf16x8 *>(tmp);
+                    }
+                }
+#pragma unroll
+                for (int b = 0; b < TN; ++b) {
+                    const int j = (wn * TN + b) * 32 + l32;
+                    if constexpr (TB) {
+                        bf[b] = *reinterpret_cast<const bf16x8 *>(&Bs[j * BSTR + kk]);
+                    } else {
+                        bf16_t tmp[8];
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) tmp[q] = Bs[(kk + q) * BSTR + j];
+                        bf[b] = *reinterpret_cast<const bf16x8 *>(tmp);
+                    }
+                }
+#pragma unroll
+                for (int a = 0; a < TM; ++a)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
+            }
+        }
+    }
+
+    // Epilogue.  Accumulator register r of lane (h, l32) holds row 8*(r/4) + 4*h + r%4, column l32.
+    const bool partial = gridDim.z > 1;
+#pragma unroll
+    for (int a = 0; a < TM; ++a) {
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int64_t col = n0 + (wn * TN + b) * 32 + l32;
+            if (col >= g.N) continue;
+            const float bia = (!partial && g.bias) ? g.bias[col] : 0.0f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = m0 + (wm * TM + a) * 32 + 8 * (r / 4) + 4 * h + (r % 4);
+                if (row >= g.M) continue;
+                float v = acc[a][b][r];
+                if (partial) {
+                    static_cast<float *>(g.C)[((int64_t)blockIdx.z * g.M + row) * g.N + col] = v;
+                    continue;
+                }
+                if (g.rowscale) v *= g.rowscale[row];
+                if (g.Cin) {
+                    v += g.c_bf16 ? bf16_to_f32(static_cast<const bf16_t *>(g.Cin)[row * g.ldcin + col])
+                                  : static_cast<const float *>(g.Cin)[row * g.ldcin + col];
+                }
+                v += bia;
+                if (g.relu) v = v > 0.0f ? v : 0.0f;
+                if (g.c_bf16) static_cast<bf16_t *>(g.C)[row * g.ldc + col] = (bf16_t)f32_to_bf16(v);
+                else static_cast<float *>(g.C)[row * g.ldc + col] = v;
+            }
+        }
+    }
+}
+
+// C = act(sum_z P[z] + C_in + bias), partials added in z order
+__global__ void __launch_bounds__(256) k_splitk_reduce(const float *P, int splits, int64_t M, int64_t N, void *C,
+                                                       int64_t ldc, const void *Cin, int64_t ldcin, const float *bias,
+                                                       const float *rowscale, int relu, int c_bf16) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= M * N) return;
+    const int64_t row = idx / N, col = idx % N;
+    float v = 0.0f;
+    for (int z = 0; z < splits; ++z) v += P[(int64_t)z * M * N + idx];
+    if (rowscale) v *= rowscale[row];
+    if (Cin) v += c_bf16 ? bf16_to_f32(static_cast<const bf16_t *>(Cin)[row * ldcin + col])
+                         : static_cast<const float *>(Cin)[row * ldcin + col];
+    if (bias) v += bias[col];
+    if (relu) v = v > 0.0f ? v : 0.0f;
+    if (c_bf16) static_cast<bf16_t *>(C)[row * ldc + col] = (bf16_t)f32_to_bf16(v);
+    else static_cast<float *>(C)[row * ldc + col] = v;
+}
+
+int64_t pick_bn(int64_t N) { return N <= 32 ? 32 : (N <= 64 ? 64 : 128); }
+int64_t pick_bm(int64_t bn) { return bn == 128 ? 128 : 256; }
+
+struct SplitPlan { int splits; int64_t k_per_split; };
+
+SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
+    const int64_t bn = pick_bn(N), bm = pick_bm(bn);
+    const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    SplitPlan p{1, (K + KT - 1) / KT * KT};
+    if (K <= 0) { p.k_per_split = KT; return p; }
+    // the reduction is cut only for the weight-gradient shape: few output tiles, very long K
+    if (!transA || tiles >= 256 || K < 64 * KT) return p;
+    int64_t want = (1024 + tiles - 1) / tiles;                // about four workgroups per CU
+    const int64_t max_by_len = K / (16 * KT);                 // at least 16 k-tiles per split
+    if (want > max_by_len) want = max_by_len;
+    if (want < 1) want = 1;
+    int64_t kps = ((K + want - 1) / want + KT - 1) / KT * KT;
+    p.splits = (int)((K + kps - 1) / kps);
+    p.k_per_split = kps;
+    return p;
+}
+
+template <typename T, bool TA, bool TB>
+gt_status launch_gemm(GemmArgs g, int splits, hipStream_t st) {
+    const int64_t bn = pick_bn(g.N), bm = pick_bm(bn);
+    dim3 grid((unsigned)((g.N + bn - 1) / bn), (unsigned)((g.M + bm - 1) / bm), (unsigned)splits);
+    if (bn == 128) k_gemm<T, TA, TB, 2, 2, 2, 2><<<grid, 256, 0, st>>>(g);
+    else if (bn == 64) k_gemm<T, TA, TB, 4, 1, 2, 2><<<grid, 256, 0, st>>>(g);
+    else k_gemm<T, TA, TB, 4, 1, 2, 1><<<grid, 256, 0, st>>>(g);
+    GT_LAUNCH_CHECK("k_gemm");
+    return GT_OK;
+}
+
+template <typename T>
+gt_status launch_gemm_t(const GemmArgs &g, int transA, int transB, int splits, hipStream_t st) {
+    if (!transA && !transB) return launch_gemm<T, false, false>(g, splits, st);
+    if (!transA && transB) return launch_gemm<T, false, true>(g, splits, st);
+    if (transA && !transB) return launch_gemm<T, true, false>(g, splits, st);
+    return launch_gemm<T, true, true>(g, splits, st);
+}
+
+}  // namespace
+
+size_t gt_gemm_ws_bytes(int transA, int64_t M, int64_t N, int64_t K) {
+    const SplitPlan p = plan_split(transA, M, N, K);
+    return p.splits > 1 ? gt_align_up((size_t)p.splits * (size_t)M * (size_t)N * 4) : 0;
+}
+
+gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                      const void *A, int64_t lda, const void *B, int64_t ldb, const float *bias, const float *rowscale,
+                      gt_act act, const void *Cin, int64_t ldcin, void *C, int64_t ldc, gt_dtype c_dtype, void *ws,
+                      size_t ws_bytes, hipStream_t st) {
+    if (dtype != GT_F32 && dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown dtype", fn);
+    if (c_dtype != GT_F32 && c_dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown c_dtype", fn);
+    if (M < 0 || N < 0 || K < 0) return gt_fail(GT_ERR_INVALID_ARG, "%s: negative size", fn);
+    if (M == 0 || N == 0) return GT_OK;
+    if (!C) return gt_fail(GT_ERR_INVALID_ARG, "%s: C is null", fn);
+    if (K > 0 && (!A || !B)) return gt_fail(GT_ERR_INVALID_ARG, "%s: A or B is null", fn);
+    if (lda < (transA ? M : K) || ldb < (transB ? K : N) || ldc < N || (Cin && ldcin < N))
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: leading dimension too small", fn);
+    const size_t es = gt_dtype_size(dtype), cs = gt_dtype_size(c_dtype);
+    if (((uintptr_t)A % es) || ((uintptr_t)B % es) || ((uintptr_t)C % cs) || ((uintptr_t)Cin % cs))
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: pointer misaligned for dtype", fn);
+    const SplitPlan p = plan_split(transA, M, N, K);
+    const size_t need = p.splits > 1 ? gt_align_up((size_t)p.splits * (size_t)M * (size_t)N * 4) : 0;
+    if (need) {
+        if (!ws || ((uintptr_t)ws & 255)) return gt_fail(GT_ERR_WORKSPACE, "%s: ws null or not 256-byte aligned", fn);
+        if (ws_bytes < need) return gt_fail(GT_ERR_WORKSPACE, "%s: ws_bytes %zu < required %zu", fn, ws_bytes, need);
+    }
+    const int ve = dtype == GT_BF16 ? 8 : 4;
+    GemmArgs g{};
+    g.A = A; g.lda = lda; g.B = B; g.ldb = ldb;
+    g.M = M; g.N = N; g.K = K;
+    g.k_per_split = p.k_per_split;
+    g.vecA = (((uintptr_t)A & 15) == 0 && lda % ve == 0);
+    g.vecB = (((uintptr_t)B & 15) == 0 && ldb % ve == 0);
+    g.bias = bias; g.rowscale = rowscale; g.relu = (act == GT_ACT_RELU); g.c_bf16 = (c_dtype == GT_BF16);
+    g.Cin = Cin; g.ldcin = ldcin;
+    if (p.splits > 1) { g.C = ws; g.ldc = N; } else { g.C = C; g.ldc = ldc; }
+    gt_status s = (dtype == GT_F32) ? launch_gemm_t<float>(g, transA, transB, p.splits, st)
+                                    : launch_gemm_t<bf16_t>(g, transA, transB, p.splits, st);
+    if (s != GT_OK) return s;
+    if (p.splits > 1) {
+        const int64_t n = M * N;
+        k_splitk_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(static_cast<const float *>(ws), p.splits, M, N, C,
+                                                                     ldc, Cin, ldcin, bias, rowscale, g.relu, g.c_bf16);
+        GT_LAUNCH_CHECK("k_splitk_reduce");
+    }
+    return GT_OK;
+}
+
+extern "C" gt_status gt_combine_ws_size(gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                                        size_t *ws_bytes) {
+    (void)dtype; (void)transB;
+    if (!ws_bytes) return gt_fail(GT_ERR_INVALID_ARG, "gt_combine_ws_size: ws_bytes is null");
+    if (M < 0 || N < 0 || K < 0) return gt_fail(GT_ERR_INVALID_ARG, "gt_combine_ws_size: negative size");
+    *ws_bytes = gt_gemm_ws_bytes(transA, M, N, K);
+    return GT_OK;
+}
+
+extern "C" gt_status gt_combine(gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K, const void *A,
+                                int64_t lda, const void *B, int64_t ldb, const float *bias, gt_act act, void *C,
+                                int64_t ldc, gt_dtype c_dtype, void *ws, size_t ws_bytes, void *stream) {
+    if (act != GT_ACT_NONE && act != GT_ACT_RELU) return gt_fail(GT_ERR_INVALID_ARG, "gt_combine: unknown activation");
+    return gt_gemm_run("gt_combine", dtype, transA != 0, transB != 0, M, N, K, A, lda, B, ldb, bias, nullptr, act,
+                       nullptr, 0, C, ldc, c_dtype, ws, ws_bytes, (hipStream_t)stream);
+}

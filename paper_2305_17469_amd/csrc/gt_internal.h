@@ -1,0 +1,77 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "gt.h"
+
+// Work decomposition of one aggregation direction.  A row with more than GT_SPLIT_MIN entries is
+// cut into chunks of GT_CHUNK entries; every chunk becomes a work item that writes an fp32
+// partial row, and a second kernel adds a row's partials in chunk order.  All other rows are
+// one item each and are written directly.  Items are ordered longest first.
+#define GT_CHUNK 512
+#define GT_SPLIT_MIN 768
+
+struct gt_item {   // 16 bytes, loaded as one int4
+    int32_t row;   // output row
+    int32_t e0;    // first entry
+    int32_t e1;    // one past the last entry
+    int32_t slot;  // < 0: write the output row;  >= 0: write partial row `slot`
+};
+
+struct gt_split {  // one per split row
+    int32_t row;
+    int32_t first;  // first partial slot
+    int32_t count;  // number of partial slots
+    int32_t pad;
+};
+
+struct gt_sched {
+    const int32_t *rowptr = nullptr;  // [n_rows + 1]
+    const int32_t *nbr = nullptr;     // [E] neighbour (gathered row) of every entry
+    const float *wt = nullptr;        // [E] per-entry weight or null
+    const gt_item *items = nullptr;
+    const gt_split *splits = nullptr;
+    int64_t n_rows = 0, n_items = 0, n_splits = 0, n_partials = 0;
+};
+
+struct gt_graph {
+    int64_t n_dst = 0, n_src = 0, n_edges = 0;
+    const int32_t *rowptr = nullptr, *colidx = nullptr;
+    const float *ew = nullptr;
+    // plan (device, inside the caller's workspace)
+    int32_t *in_deg = nullptr, *out_deg = nullptr, *rowptr_t = nullptr, *colidx_t = nullptr, *perm = nullptr;
+    float *ew_t = nullptr;
+    float *dinv = nullptr;  // in_deg^-1/2 (square graphs only), 0 where the degree is 0
+    float *rdeg = nullptr;  // 1 / in_deg, 0 where the degree is 0
+    unsigned long long *vcount = nullptr;  // device counter of gt_graph_validate
+    gt_sched fwd, bwd;
+};
+
+void gt_set_error(const char *fmt, ...);
+gt_status gt_fail(gt_status s, const char *fmt, ...);
+gt_status gt_hip_fail(hipError_t e, const char *what);
+
+#define GT_HIP(call)                                                \
+    do {                                                            \
+        hipError_t e__ = (call);                                    \
+        if (e__ != hipSuccess) return gt_hip_fail(e__, #call);      \
+    } while (0)
+
+#define GT_LAUNCH_CHECK(what)                                       \
+    do {                                                            \
+        hipError_t e__ = hipGetLastError();                         \
+        if (e__ != hipSuccess) return gt_hip_fail(e__, what);       \
+    } while (0)
+
+static inline size_t gt_align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+static inline size_t gt_dtype_size(gt_dtype t) { return t == GT_BF16 ? 2 : 4; }
+
+// internal entry points used across translation units
+gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce, gt_dtype in_dtype,
+                           gt_dtype out_dtype, int64_t F, const void *X, int64_t ldx, void *Y, int64_t ldy,
+                           const float *bias, gt_act act, void *ws, size_t ws_bytes, hipStream_t stream);
+
+size_t gt_aggregate_ws_bytes(const gt_graph *g, int64_t F);

@@ -1,0 +1,408 @@
+// One GNN layer with dynamic kernel placement (paper: GNN Kernel Orchestrator).
+//
+//   aggregation-first   H' = act( (A X) W + b )      sigma(W f(h(X)) + b)
+//   combination-first   H' = act( A (X W) + b )      sigma(f(h(W X)) + b)
+//
+// Both are the same function because the aggregation is the linear map A; which one is cheaper
+// depends on how much each kernel shrinks the tensor the other one has to process.  The paper's
+// cost model expresses the gain of either order as (reduction factor) x (kernel execution
+// factor); the two kernel-execution factors are kept here as kernel-time models
+//     t_comb(rows, in, out) = rows * (alpha * in * out + beta * width)
+//     t_aggr(E, n_out, F)   = F * (gamma * E + delta * n_out)
+// whose differences between the two orders are exactly the four benefit formulas of the table
+// "DKP cost model".  Summing kernel times instead of comparing benefits lets the same model
+// cover the cases the table treats by a special rule (first layer: no backward aggregation at
+// all when the forward ran aggregation-first) and the coupling of forward and backward through
+// what was saved.
+#include <math.h>
+
+#include "gt_internal.h"
+#include "gt_combine.h"
+
+namespace {
+
+typedef uint16_t bf16_t;
+
+// Coefficients in seconds.  Defaults are MI355X figures (a gather near 3 TB/s, fp32 MFMA near
+// 60 TFLOP/s sustained); gt_calibrate replaces them with fitted values.
+gt_cost_coeffs g_cost = {3.3e-14, 2.0e-12, 1.3e-12, 1.3e-12, 3.3e-14, 2.0e-12, 1.3e-12, 1.3e-12};
+
+double t_comb(const gt_cost_coeffs &c, bool bwd, double rows, double in, double out) {
+    return bwd ? rows * (c.alpha_bwd * in * out + c.beta_bwd * in) : rows * (c.alpha_fwd * in * out + c.beta_fwd * out);
+}
+double t_aggr(const gt_cost_coeffs &c, bool bwd, double E, double n_out, double F) {
+    return bwd ? F * (c.gamma_bwd * E + c.delta_bwd * n_out) : F * (c.gamma_fwd * E + c.delta_fwd * n_out);
+}
+
+__device__ inline float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ inline uint32_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+template <typename T> __device__ inline float ldf(const T *p);
+template <> __device__ inline float ldf<float>(const float *p) { return *p; }
+template <> __device__ inline float ldf<bf16_t>(const bf16_t *p) { return bf16_to_f32(*p); }
+template <typename T> __device__ inline void stf(T *p, float v);
+template <> __device__ inline void stf<float>(float *p, float v) { *p = v; }
+template <> __device__ inline void stf<bf16_t>(bf16_t *p, float v) { *p = (bf16_t)f32_to_bf16(v); }
+
+constexpr int CS_ROWS = 256;   // rows per workgroup of the column-sum kernels
+
+// dZ = dY * [Y > 0] (or dY when Y is null) and per-workgroup column sums of dZ.
+// One workgroup covers CS_ROWS rows; thread t owns columns t, t+256, ...; sums run down the rows
+// in order, so the result does not depend on scheduling.
+template <typename T>
+__global__ void __launch_bounds__(256) k_mask_colsum(const T *dY, int64_t lddy, const T *Y, int64_t ldy, T *dZ,
+                                                     int64_t lddz, int64_t rows, int64_t cols, float *partial) {
+    const int64_t r0 = (int64_t)blockIdx.x * CS_ROWS;
+    const int64_t r1 = r0 + CS_ROWS < rows ? r0 + CS_ROWS : rows;
+    for (int64_t c = threadIdx.x; c < cols; c += 256) {
+        float s = 0.0f;
+        for (int64_t r = r0; r < r1; ++r) {
+            float g = ldf<T>(dY + r * lddy + c);
+            if (Y) {
+                g = ldf<T>(Y + r * ldy + c) > 0.0f ? g : 0.0f;
+                stf<T>(dZ + r * lddz + c, g);
+            }
+            s += g;
+        }
+        if (partial) partial[(int64_t)blockIdx.x * cols + c] = s;
+    }
+}
+
+__global__ void __launch_bounds__(256) k_colsum_final(const float *partial, int64_t nblk, int64_t cols, float *out) {
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= cols) return;
+    float s = 0.0f;
+    for (int64_t b = 0; b < nblk; ++b) s += partial[b * cols + c];
+    out[c] = s;
+}
+
+int64_t pad_ld(int64_t F, gt_dtype t) {
+    const int64_t v = t == GT_BF16 ? 8 : 4;
+    return (F + v - 1) / v * v;
+}
+
+struct LayerLayout {
+    // scratch regions (bytes offsets); forward and backward use the same buffer at different times
+    size_t T;        // [n_src, ldo]  X W (combination-first forward)
+    size_t dZ;       // [n_dst, ldo]
+    size_t S;        // [n_src, ldo]  A^T dZ
+    size_t dM;       // [n_dst, ldi]  dZ W^T
+    size_t colsum;   // fp32 [ceil(n_dst / CS_ROWS), out]
+    size_t agg_ws;   // aggregation partial rows
+    size_t gemm_ws;  // split-k partials
+    size_t total;
+    size_t saved;    // bytes of `saved`: M = A X, [n_dst, ldi]
+    int64_t ldi, ldo;
+    size_t agg_ws_bytes, gemm_ws_bytes;
+};
+
+LayerLayout layer_layout(const gt_graph *g, const gt_layer_desc *d) {
+    LayerLayout L{};
+    const size_t es = gt_dtype_size(d->dtype);
+    L.ldi = pad_ld(d->in_dim, d->dtype);
+    L.ldo = pad_ld(d->out_dim, d->dtype);
+    size_t off = 0;
+    auto take = [&](size_t b) { size_t o = off; off += gt_align_up(b ? b : 4); return o; };
+    L.T = take((size_t)g->n_src * L.ldo * es);
+    L.dZ = take((size_t)g->n_dst * L.ldo * es);
+    L.S = L.T;   // never live together: T belongs to the forward call, S to the backward call
+    L.dM = take((size_t)g->n_dst * L.ldi * es);
+    L.colsum = take((size_t)((g->n_dst + CS_ROWS - 1) / CS_ROWS + 1) * d->out_dim * 4);
+    const int64_t fmax = d->in_dim > d->out_dim ? d->in_dim : d->out_dim;
+    L.agg_ws_bytes = gt_aggregate_ws_bytes(g, fmax);
+    L.agg_ws = take(L.agg_ws_bytes);
+    const int64_t rows = g->n_src > g->n_dst ? g->n_src : g->n_dst;
+    L.gemm_ws_bytes = gt_gemm_ws_bytes(1, d->in_dim, d->out_dim, rows);
+    const size_t alt = gt_gemm_ws_bytes(1, d->in_dim, d->out_dim, g->n_dst);
+    if (alt > L.gemm_ws_bytes) L.gemm_ws_bytes = alt;
+    L.gemm_ws = take(L.gemm_ws_bytes);
+    L.total = off;
+    L.saved = gt_align_up((size_t)g->n_dst * L.ldi * es);
+    return L;
+}
+
+gt_status check_desc(const char *fn, const gt_graph *g, const gt_layer_desc *d) {
+    if (!g || !d) return gt_fail(GT_ERR_INVALID_ARG, "%s: null graph or descriptor", fn);
+    if (d->in_dim <= 0 || d->out_dim <= 0) return gt_fail(GT_ERR_INVALID_ARG, "%s: in_dim and out_dim must be positive", fn);
+    if (d->dtype != GT_F32 && d->dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown dtype", fn);
+    if (d->reduce != GT_SUM && d->reduce != GT_MEAN && d->reduce != GT_SYMNORM)
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown reduce", fn);
+    if (d->act != GT_ACT_NONE && d->act != GT_ACT_RELU) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown activation", fn);
+    if (d->reduce == GT_SYMNORM && g->n_dst != g->n_src)
+        return gt_fail(GT_ERR_UNSUPPORTED, "%s: GT_SYMNORM needs a square graph", fn);
+    if (d->has_root && g->n_dst > g->n_src)
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: has_root needs the destinations to be the first n_dst sources", fn);
+    return GT_OK;
+}
+
+void *at(void *base, size_t off) { return static_cast<char *>(base) + off; }
+
+void decide(const gt_graph *g, const gt_layer_desc *d, gt_order *fwd, gt_order *bwd) {
+    const gt_cost_coeffs &c = g_cost;
+    const double ns = (double)g->n_src, nd = (double)g->n_dst, E = (double)g->n_edges;
+    const double fi = (double)d->in_dim, fo = (double)d->out_dim;
+    // forward
+    const double f_agg = t_aggr(c, false, E, nd, fi) + t_comb(c, false, nd, fi, fo);
+    const double f_comb = t_comb(c, false, ns, fi, fo) + t_aggr(c, false, E, nd, fo);
+    // backward, by (forward order, backward order).  The weight gradient is (A X)^T dZ over n_dst
+    // rows when A X was saved, else X^T (A^T dZ) over n_src rows, which needs A^T dZ.
+    const double dw_agg = t_comb(c, true, nd, fi, fo), dw_comb = t_comb(c, true, ns, fi, fo);
+    const double s_agg = t_aggr(c, true, E, ns, fo);   // A^T dZ
+    double b[2][2];                                    // [fwd comb?][bwd comb?]
+    if (d->need_dx) {
+        const double dx_agg = t_comb(c, true, nd, fi, fo) + t_aggr(c, true, E, ns, fi);
+        const double dx_comb = s_agg + t_comb(c, true, ns, fi, fo);
+        b[0][0] = dw_agg + dx_agg;
+        b[0][1] = dw_agg + dx_comb;
+        b[1][0] = dw_comb + s_agg + dx_agg;
+        b[1][1] = dw_comb + dx_comb;
+    } else {
+        // first layer: only parameter gradients; the backward order is immaterial but reported
+        // as the forward's
+        b[0][0] = b[0][1] = dw_agg;
+        b[1][0] = b[1][1] = dw_comb + s_agg;
+    }
+    int bf = 0, bb = 0;
+    double best = f_agg + b[0][0];
+    const double cand[4] = {f_agg + b[0][0], f_agg + b[0][1], f_comb + b[1][0], f_comb + b[1][1]};
+    for (int i = 1; i < 4; ++i) {
+        if (cand[i] < best) { best = cand[i]; bf = i >> 1; bb = i & 1; }   // strict: ties keep aggregation-first
+    }
+    if (!d->need_dx) bb = bf;
+    *fwd = bf ? GT_COMB_FIRST : GT_AGG_FIRST;
+    *bwd = bb ? GT_COMB_FIRST : GT_AGG_FIRST;
+}
+
+template <typename T>
+gt_status mask_colsum(const void *dY, int64_t lddy, const void *Y, int64_t ldy, void *dZ, int64_t lddz, int64_t rows,
+                      int64_t cols, float *partial, float *db, hipStream_t st) {
+    if (rows <= 0) {
+        if (db) {   // empty sum: zeros, written by the same final kernel (no memset node)
+            k_colsum_final<<<(unsigned)((cols + 255) / 256), 256, 0, st>>>(partial, 0, cols, db);
+            GT_LAUNCH_CHECK("k_colsum_final");
+        }
+        return GT_OK;
+    }
+    const int64_t nblk = (rows + CS_ROWS - 1) / CS_ROWS;
+    k_mask_colsum<T><<<(unsigned)nblk, 256, 0, st>>>(static_cast<const T *>(dY), lddy, static_cast<const T *>(Y), ldy,
+                                                     static_cast<T *>(dZ), lddz, rows, cols, db ? partial : nullptr);
+    GT_LAUNCH_CHECK("k_mask_colsum");
+    if (db) {
+        k_colsum_final<<<(unsigned)((cols + 255) / 256), 256, 0, st>>>(partial, nblk, cols, db);
+        GT_LAUNCH_CHECK("k_colsum_final");
+    }
+    return GT_OK;
+}
+
+}  // namespace
+
+extern "C" gt_status gt_cost_get(gt_cost_coeffs *c) {
+    if (!c) return gt_fail(GT_ERR_INVALID_ARG, "gt_cost_get: null");
+    *c = g_cost;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_cost_set(const gt_cost_coeffs *c) {
+    if (!c) return gt_fail(GT_ERR_INVALID_ARG, "gt_cost_set: null");
+    const double v[8] = {c->alpha_fwd, c->beta_fwd, c->gamma_fwd, c->delta_fwd,
+                         c->alpha_bwd, c->beta_bwd, c->gamma_bwd, c->delta_bwd};
+    for (double x : v)
+        if (!(x >= 0.0) || !isfinite(x)) return gt_fail(GT_ERR_INVALID_ARG, "gt_cost_set: coefficients must be finite and >= 0");
+    g_cost = *c;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_cost_benefits(const gt_cost_coeffs *c, int64_t n_src, int64_t n_dst, int64_t n_edge,
+                                      int64_t n_feat, int64_t n_hid, int first_layer, double *aggr_fwd,
+                                      double *aggr_bwd, double *comb_fwd, double *comb_bwd) {
+    if (!c) return gt_fail(GT_ERR_INVALID_ARG, "gt_cost_benefits: coefficients are null");
+    const double ns = (double)n_src, nd = (double)n_dst, E = (double)n_edge, F = (double)n_feat, H = (double)n_hid;
+    // table "DKP cost model": reduction factor x kernel execution factor
+    if (aggr_fwd) *aggr_fwd = (ns - nd) * (c->alpha_fwd * H * F + c->beta_fwd * H);
+    if (aggr_bwd) *aggr_bwd = (first_layer ? ns : (ns - nd)) * (c->alpha_bwd * H * F + c->beta_bwd * F);
+    if (comb_fwd) *comb_fwd = (F - H) * (c->gamma_fwd * E + c->delta_fwd * nd);
+    if (comb_bwd) *comb_bwd = (F - H) * (c->gamma_bwd * E + c->delta_bwd * ns);
+    return GT_OK;
+}
+
+extern "C" gt_status gt_layer_decide(const gt_graph *g, const gt_layer_desc *d, gt_order *fwd, gt_order *bwd) {
+    gt_status s = check_desc("gt_layer_decide", g, d);
+    if (s != GT_OK) return s;
+    gt_order f, b;
+    decide(g, d, &f, &b);
+    if (fwd) *fwd = f;
+    if (bwd) *bwd = b;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_layer_ws_size(const gt_graph *g, const gt_layer_desc *d, size_t *saved_bytes,
+                                      size_t *scratch_bytes) {
+    gt_status s = check_desc("gt_layer_ws_size", g, d);
+    if (s != GT_OK) return s;
+    const LayerLayout L = layer_layout(g, d);
+    if (saved_bytes) *saved_bytes = L.saved;
+    if (scratch_bytes) *scratch_bytes = L.total;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_order req, const void *X, int64_t ldx,
+                                  const void *W, const void *W_root, const float *b, void *Y, int64_t ldy, void *saved,
+                                  void *scratch, gt_order *used, void *stream) {
+    const char *fn = "gt_layer_fwd";
+    gt_status s = check_desc(fn, g, d);
+    if (s != GT_OK) return s;
+    if (req != GT_AUTO && req != GT_AGG_FIRST && req != GT_COMB_FIRST) return gt_fail(GT_ERR_INVALID_ARG, "%s: bad order", fn);
+    if (!X || !W || !Y) return gt_fail(GT_ERR_INVALID_ARG, "%s: X, W or Y is null", fn);
+    if ((d->has_root != 0) != (W_root != nullptr)) return gt_fail(GT_ERR_INVALID_ARG, "%s: W_root must be given iff has_root", fn);
+    if (ldx < d->in_dim || ldy < d->out_dim) return gt_fail(GT_ERR_INVALID_ARG, "%s: leading dimension too small", fn);
+    if (!scratch || ((uintptr_t)scratch & 255)) return gt_fail(GT_ERR_WORKSPACE, "%s: scratch null or not 256-byte aligned", fn);
+    hipStream_t st = (hipStream_t)stream;
+    const LayerLayout L = layer_layout(g, d);
+    gt_order order = req;
+    if (order == GT_AUTO) { gt_order bw; decide(g, d, &order, &bw); }
+    if (order == GT_AGG_FIRST && (!saved || ((uintptr_t)saved & 255)))
+        return gt_fail(GT_ERR_WORKSPACE, "%s: saved null or not 256-byte aligned", fn);
+    if (used) *used = order;
+    const gt_dtype t = d->dtype;
+    const int64_t fi = d->in_dim, fo = d->out_dim;
+
+    if (order == GT_AGG_FIRST) {
+        // M = A X (kept for the weight gradient), then the combination on n_dst rows
+        s = gt_aggregate_run(g, false, d->reduce, t, t, fi, X, ldx, saved, L.ldi, nullptr, GT_ACT_NONE,
+                             at(scratch, L.agg_ws), L.agg_ws_bytes, st);
+        if (s != GT_OK) return s;
+        if (!d->has_root)
+            return gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, saved, L.ldi, W, fo, b, nullptr, d->act, nullptr, 0, Y, ldy,
+                               t, nullptr, 0, st);
+        s = gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, saved, L.ldi, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, Y,
+                        ldy, t, nullptr, 0, st);
+        if (s != GT_OK) return s;
+    } else {
+        // T = X W on n_src rows, then the aggregation at width out_dim with bias and activation
+        // applied as the row is written
+        void *T = at(scratch, L.T);
+        s = gt_gemm_run(fn, t, 0, 0, g->n_src, fo, fi, X, ldx, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, T, L.ldo,
+                        t, nullptr, 0, st);
+        if (s != GT_OK) return s;
+        const bool fuse = !d->has_root;
+        s = gt_aggregate_run(g, false, d->reduce, t, t, fo, T, L.ldo, Y, ldy, fuse ? b : nullptr,
+                             fuse ? d->act : GT_ACT_NONE, at(scratch, L.agg_ws), L.agg_ws_bytes, st);
+        if (s != GT_OK || fuse) return s;
+    }
+    // root term: Y = act(Y + X[0:n_dst] W_root + b)
+    return gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, X, ldx, W_root, fo, b, nullptr, d->act, Y, ldy, Y, ldy, t, nullptr,
+                       0, st);
+}
+
+extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_order fwd_used, gt_order req,
+                                  const void *dY, int64_t lddy, const void *X, int64_t ldx, const void *W,
+                                  const void *W_root, const void *Y, int64_t ldy, const void *saved, void *scratch,
+                                  void *dX, int64_t lddx, float *dW, float *dW_root, float *db, gt_order *used,
+                                  void *stream) {
+    const char *fn = "gt_layer_bwd";
+    gt_status s = check_desc(fn, g, d);
+    if (s != GT_OK) return s;
+    if (fwd_used != GT_AGG_FIRST && fwd_used != GT_COMB_FIRST)
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: fwd_used must be the order gt_layer_fwd reported", fn);
+    if (req != GT_AUTO && req != GT_AGG_FIRST && req != GT_COMB_FIRST) return gt_fail(GT_ERR_INVALID_ARG, "%s: bad order", fn);
+    if (!dY || !X || !W || !dW) return gt_fail(GT_ERR_INVALID_ARG, "%s: dY, X, W or dW is null", fn);
+    if (d->act == GT_ACT_RELU && !Y) return gt_fail(GT_ERR_INVALID_ARG, "%s: Y is needed for the ReLU derivative", fn);
+    if ((d->has_root != 0) != (W_root != nullptr) || (d->has_root != 0) != (dW_root != nullptr))
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: W_root and dW_root must be given iff has_root", fn);
+    if ((d->need_dx != 0) != (dX != nullptr)) return gt_fail(GT_ERR_INVALID_ARG, "%s: dX must be given iff need_dx", fn);
+    if (lddy < d->out_dim || ldx < d->in_dim || (Y && ldy < d->out_dim) || (dX && lddx < d->in_dim))
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: leading dimension too small", fn);
+    if (fwd_used == GT_AGG_FIRST && !saved) return gt_fail(GT_ERR_INVALID_ARG, "%s: saved is null", fn);
+    if (!scratch || ((uintptr_t)scratch & 255)) return gt_fail(GT_ERR_WORKSPACE, "%s: scratch null or not 256-byte aligned", fn);
+    hipStream_t st = (hipStream_t)stream;
+    const LayerLayout L = layer_layout(g, d);
+    const gt_dtype t = d->dtype;
+    const int64_t fi = d->in_dim, fo = d->out_dim;
+
+    gt_order order = req;
+    if (order == GT_AUTO) {
+        // best backward order given the forward order that actually ran
+        gt_layer_desc dd = *d;
+        gt_order f2, b2;
+        decide(g, &dd, &f2, &b2);
+        if (f2 == fwd_used) {
+            order = b2;
+        } else {
+            const gt_cost_coeffs &c = g_cost;
+            const double ns = (double)g->n_src, nd = (double)g->n_dst, E = (double)g->n_edges;
+            const double dx_agg = t_comb(c, true, nd, fi, fo) + t_aggr(c, true, E, ns, fi) +
+                                  (fwd_used == GT_COMB_FIRST ? t_aggr(c, true, E, ns, fo) : 0.0);
+            const double dx_comb = t_aggr(c, true, E, ns, fo) + t_comb(c, true, ns, fi, fo);
+            order = dx_comb < dx_agg ? GT_COMB_FIRST : GT_AGG_FIRST;
+        }
+        if (!d->need_dx) order = fwd_used;
+    }
+    if (used) *used = order;
+
+    // dZ = dY * [Y > 0], db = column sums of dZ
+    const void *dZ = dY;
+    int64_t lddz = lddy;
+    float *partial = static_cast<float *>(at(scratch, L.colsum));
+    if (d->act == GT_ACT_RELU) {
+        void *z = at(scratch, L.dZ);
+        s = (t == GT_F32) ? mask_colsum<float>(dY, lddy, Y, ldy, z, L.ldo, g->n_dst, fo, partial, db, st)
+                          : mask_colsum<bf16_t>(dY, lddy, Y, ldy, z, L.ldo, g->n_dst, fo, partial, db, st);
+        dZ = z; lddz = L.ldo;
+    } else if (db) {
+        s = (t == GT_F32) ? mask_colsum<float>(dY, lddy, nullptr, 0, nullptr, 0, g->n_dst, fo, partial, db, st)
+                          : mask_colsum<bf16_t>(dY, lddy, nullptr, 0, nullptr, 0, g->n_dst, fo, partial, db, st);
+    }
+    if (s != GT_OK) return s;
+
+    void *gws = at(scratch, L.gemm_ws);
+    void *aws = at(scratch, L.agg_ws);
+    if (d->has_root) {
+        // dW_root = X[0:n_dst]^T dZ
+        s = gt_gemm_run(fn, t, 1, 0, fi, fo, g->n_dst, X, ldx, dZ, lddz, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dW_root,
+                        fo, GT_F32, gws, L.gemm_ws_bytes, st);
+        if (s != GT_OK) return s;
+    }
+    if (fwd_used == GT_AGG_FIRST) {
+        // dW = (A X)^T dZ with the saved A X
+        s = gt_gemm_run(fn, t, 1, 0, fi, fo, g->n_dst, saved, L.ldi, dZ, lddz, nullptr, nullptr, GT_ACT_NONE, nullptr, 0,
+                        dW, fo, GT_F32, gws, L.gemm_ws_bytes, st);
+        if (s != GT_OK) return s;
+    }
+    const bool need_S = (fwd_used == GT_COMB_FIRST) || (d->need_dx && order == GT_COMB_FIRST);
+    void *S = at(scratch, L.S);
+    if (need_S) {
+        // S = A^T dZ: the aggregation's derivative, outputs on the source vertices, width out_dim
+        s = gt_aggregate_run(g, true, d->reduce, t, t, fo, dZ, lddz, S, L.ldo, nullptr, GT_ACT_NONE, aws, L.agg_ws_bytes, st);
+        if (s != GT_OK) return s;
+    }
+    if (fwd_used == GT_COMB_FIRST) {
+        // dW = X^T (A^T dZ)
+        s = gt_gemm_run(fn, t, 1, 0, fi, fo, g->n_src, X, ldx, S, L.ldo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dW, fo,
+                        GT_F32, gws, L.gemm_ws_bytes, st);
+        if (s != GT_OK) return s;
+    }
+    if (!d->need_dx) return GT_OK;
+    if (order == GT_COMB_FIRST) {
+        // dX = (A^T dZ) W^T
+        s = gt_gemm_run(fn, t, 0, 1, g->n_src, fi, fo, S, L.ldo, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dX, lddx,
+                        t, nullptr, 0, st);
+    } else {
+        // dM = dZ W^T (the combination's derivative uses the transposed weight), dX = A^T dM
+        void *dM = at(scratch, L.dM);
+        s = gt_gemm_run(fn, t, 0, 1, g->n_dst, fi, fo, dZ, lddz, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dM, L.ldi,
+                        t, nullptr, 0, st);
+        if (s != GT_OK) return s;
+        s = gt_aggregate_run(g, true, d->reduce, t, t, fi, dM, L.ldi, dX, lddx, nullptr, GT_ACT_NONE, aws, L.agg_ws_bytes, st);
+    }
+    if (s != GT_OK) return s;
+    if (d->has_root) {
+        // dX[0:n_dst] += dZ W_root^T
+        s = gt_gemm_run(fn, t, 0, 1, g->n_dst, fi, fo, dZ, lddz, W_root, fo, nullptr, nullptr, GT_ACT_NONE, dX, lddx, dX,
+                        lddx, t, nullptr, 0, st);
+    }
+    return s;
+}

@@ -1,0 +1,616 @@
+// Graph plan: degrees, the transposed (by-source) structure as a stable radix sort, and the
+// degree-binned work lists of both aggregation directions.  Integer work only; every output
+// is exactly defined, so it can be compared bit for bit.
+//
+// The paper keeps CSR for the forward pass and observes that CSC suits the backward pass
+// ("Training for GNNs") and that per-batch format translation is pure overhead ("Graph
+// simulation approach" and the kernel breakdown of its evaluation); here the translation is
+// done once per graph and reused by every layer and epoch.
+#include <stdarg.h>
+#include <stdio.h>
+#include <new>
+
+#include "gt_internal.h"
+
+// ---------------------------------------------------------------------------------------------
+// status / error plumbing
+// ---------------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+void gt_set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+gt_status gt_fail(gt_status s, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+gt_status gt_hip_fail(hipError_t e, const char *what) {
+    snprintf(g_err, sizeof(g_err), "HIP error %d (%s) at %s", (int)e, hipGetErrorString(e), what);
+    return GT_ERR_HIP;
+}
+
+extern "C" const char *gt_last_error(void) { return g_err; }
+
+extern "C" const char *gt_status_string(gt_status s) {
+    switch (s) {
+        case GT_OK: return "GT_OK";
+        case GT_ERR_INVALID_ARG: return "GT_ERR_INVALID_ARG";
+        case GT_ERR_UNSUPPORTED: return "GT_ERR_UNSUPPORTED";
+        case GT_ERR_WORKSPACE: return "GT_ERR_WORKSPACE";
+        case GT_ERR_HIP: return "GT_ERR_HIP";
+        case GT_ERR_INTERNAL: return "GT_ERR_INTERNAL";
+    }
+    return "GT_ERR_UNKNOWN";
+}
+
+extern "C" const char *gt_version(void) { return "gt 0.1 (gfx950)"; }
+
+// ---------------------------------------------------------------------------------------------
+// exclusive scan of int32 (reduce-then-scan, recursive over block sums)
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_PER_THREAD = 8;
+constexpr int SCAN_TILE = SCAN_THREADS * SCAN_PER_THREAD;
+
+__device__ inline int32_t block_exclusive_scan(int32_t v, int32_t *total) {
+    // 256 threads; returns exclusive prefix of v over the block, *total = block sum
+    __shared__ int32_t wave_sums[SCAN_THREADS / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int32_t o = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += o;
+    }
+    if (lane == 63) wave_sums[wave] = inc;
+    __syncthreads();
+    int32_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < SCAN_THREADS / 64; ++w) {
+        int32_t s = wave_sums[w];
+        if (w < wave) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS) k_scan_tiles(const int32_t *in, int32_t *out, int64_t n,
+                                                             int32_t *tile_sums) {
+    const int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_PER_THREAD;
+    int32_t v[SCAN_PER_THREAD];
+    int32_t s = 0;
+#pragma unroll
+    for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+        v[i] = (base + i < n) ? in[base + i] : 0;
+        s += v[i];
+    }
+    int32_t total;
+    int32_t ex = block_exclusive_scan(s, &total);
+#pragma unroll
+    for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+        if (base + i < n) out[base + i] = ex;
+        ex += v[i];
+    }
+    if (threadIdx.x == 0 && tile_sums) tile_sums[blockIdx.x] = total;
+}
+
+__global__ void __launch_bounds__(SCAN_THREADS) k_scan_add(int32_t *out, int64_t n, const int32_t *tile_offs) {
+    const int32_t add = tile_offs[blockIdx.x];
+    const int64_t base = (int64_t)blockIdx.x * SCAN_TILE + (int64_t)threadIdx.x * SCAN_PER_THREAD;
+#pragma unroll
+    for (int i = 0; i < SCAN_PER_THREAD; ++i)
+        if (base + i < n) out[base + i] += add;
+}
+
+size_t scan_tmp_ints(int64_t n) {
+    size_t t = 0;
+    while (n > SCAN_TILE) {
+        int64_t tiles = (n + SCAN_TILE - 1) / SCAN_TILE;
+        t += gt_align_up((size_t)tiles * 4) / 4;
+        n = tiles;
+    }
+    return t + 64;
+}
+
+// out[i] = sum_{j<i} in[j] for i < n (in == out allowed).  tmp: scan_tmp_ints(n) int32.
+gt_status scan_exclusive(const int32_t *in, int32_t *out, int64_t n, int32_t *tmp, hipStream_t st) {
+    if (n <= 0) return GT_OK;
+    const int64_t tiles = (n + SCAN_TILE - 1) / SCAN_TILE;
+    if (tiles == 1) {
+        k_scan_tiles<<<1, SCAN_THREADS, 0, st>>>(in, out, n, nullptr);
+        GT_LAUNCH_CHECK("k_scan_tiles");
+        return GT_OK;
+    }
+    k_scan_tiles<<<(unsigned)tiles, SCAN_THREADS, 0, st>>>(in, out, n, tmp);
+    GT_LAUNCH_CHECK("k_scan_tiles");
+    int32_t *next = tmp + gt_align_up((size_t)tiles * 4) / 4;
+    gt_status s = scan_exclusive(tmp, tmp, tiles, next, st);
+    if (s != GT_OK) return s;
+    k_scan_add<<<(unsigned)tiles, SCAN_THREADS, 0, st>>>(out, n, tmp);
+    GT_LAUNCH_CHECK("k_scan_add");
+    return GT_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// stable LSD radix sort of (key, value) pairs, 8 bits per pass
+// ---------------------------------------------------------------------------------------------
+constexpr int RS_THREADS = 256;
+constexpr int RS_WAVES = RS_THREADS / 64;
+constexpr int RS_CHUNKS = 16;                       // 64-item chunks per wave
+constexpr int RS_WAVE_ITEMS = RS_CHUNKS * 64;       // 1024
+constexpr int RS_TILE = RS_WAVES * RS_WAVE_ITEMS;   // 4096 items per block
+
+__global__ void __launch_bounds__(RS_THREADS) k_rs_hist(const uint32_t *keys, int64_t n, int shift,
+                                                        int32_t *hist, int nblk) {
+    __shared__ int32_t h[256];
+    h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * RS_TILE;
+    for (int i = threadIdx.x; i < RS_TILE; i += RS_THREADS) {
+        int64_t p = base + i;
+        if (p < n) atomicAdd(&h[(keys[p] >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
+}
+
+// vals_in == nullptr means value = position (iota).
+__global__ void __launch_bounds__(RS_THREADS) k_rs_scatter(const uint32_t *keys_in, const uint32_t *vals_in,
+                                                           uint32_t *keys_out, uint32_t *vals_out, int64_t n,
+                                                           int shift, const int32_t *offs, int nblk) {
+    __shared__ int32_t cnt[RS_WAVES][256];
+    __shared__ int32_t wbase[RS_WAVES][256];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int i = threadIdx.x; i < RS_WAVES * 256; i += RS_THREADS) (&cnt[0][0])[i] = 0;
+    __syncthreads();
+    const int64_t wstart = (int64_t)blockIdx.x * RS_TILE + (int64_t)wave * RS_WAVE_ITEMS;
+    uint32_t key[RS_CHUNKS];
+    int32_t rank[RS_CHUNKS];
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+#pragma unroll
+    for (int c = 0; c < RS_CHUNKS; ++c) {
+        const int64_t p = wstart + (int64_t)c * 64 + lane;
+        const bool valid = p < n;
+        key[c] = valid ? keys_in[p] : 0u;
+        const uint32_t digit = (key[c] >> shift) & 255u;
+        uint64_t m = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bool bit = (digit >> b) & 1u;
+            const uint64_t bal = __ballot(valid && bit);
+            m &= bit ? bal : ~bal;
+        }
+        // m: valid lanes of this chunk with the same digit (meaningful on valid lanes)
+        const int before = __popcll(m & lt_mask);
+        int32_t prev = 0;
+        if (valid) prev = cnt[wave][digit];
+        rank[c] = prev + before;
+        if (valid && before == 0) cnt[wave][digit] = prev + __popcll(m);
+    }
+    __syncthreads();
+    {
+        const int d = threadIdx.x;   // 256 threads <-> 256 digits
+        int32_t run = offs[(int64_t)d * nblk + blockIdx.x];
+#pragma unroll
+        for (int w = 0; w < RS_WAVES; ++w) {
+            wbase[w][d] = run;
+            run += cnt[w][d];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < RS_CHUNKS; ++c) {
+        const int64_t p = wstart + (int64_t)c * 64 + lane;
+        if (p < n) {
+            const uint32_t digit = (key[c] >> shift) & 255u;
+            const int64_t dst = (int64_t)wbase[wave][digit] + rank[c];
+            keys_out[dst] = key[c];
+            vals_out[dst] = vals_in ? vals_in[p] : (uint32_t)p;
+        }
+    }
+}
+
+struct SortTmp {
+    int32_t *hist;      // 256 * nblk
+    int32_t *scan_tmp;  // scan_tmp_ints(256 * nblk)
+};
+
+int rs_blocks(int64_t n) { return (int)((n + RS_TILE - 1) / RS_TILE); }
+
+gt_status radix_pass(const uint32_t *kin, const uint32_t *vin, uint32_t *kout, uint32_t *vout, int64_t n,
+                     int shift, const SortTmp &t, hipStream_t st) {
+    if (n <= 0) return GT_OK;
+    const int nblk = rs_blocks(n);
+    k_rs_hist<<<nblk, RS_THREADS, 0, st>>>(kin, n, shift, t.hist, nblk);
+    GT_LAUNCH_CHECK("k_rs_hist");
+    gt_status s = scan_exclusive(t.hist, t.hist, (int64_t)256 * nblk, t.scan_tmp, st);
+    if (s != GT_OK) return s;
+    k_rs_scatter<<<nblk, RS_THREADS, 0, st>>>(kin, vin, kout, vout, n, shift, t.hist, nblk);
+    GT_LAUNCH_CHECK("k_rs_scatter");
+    return GT_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// plan kernels
+// ---------------------------------------------------------------------------------------------
+constexpr int PT = 256;
+inline unsigned nblocks(int64_t n, int per = PT) { return (unsigned)((n + per - 1) / per); }
+
+__global__ void k_row_degrees(const int32_t *rowptr, int64_t n_rows, int32_t *deg, float *rdeg, float *dinv) {
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_rows) return;
+    const int32_t d = rowptr[r + 1] - rowptr[r];
+    deg[r] = d;
+    if (rdeg) rdeg[r] = d > 0 ? 1.0f / (float)d : 0.0f;
+    if (dinv) dinv[r] = d > 0 ? 1.0f / sqrtf((float)d) : 0.0f;
+}
+
+// rowptr_t from the sorted source keys: rowptr_t[u] = first position whose key >= u.
+__global__ void k_boundaries(const uint32_t *skeys, int64_t E, int64_t n_src, int32_t *rowptr_t) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k > E) return;
+    // position k closes the gap (key[k-1], key[k]]; k == E closes (key[E-1], n_src]
+    const int64_t lo = (k == 0) ? -1 : (int64_t)skeys[k - 1];
+    const int64_t hi = (k == E) ? n_src : (int64_t)skeys[k];
+    for (int64_t u = lo + 1; u <= hi; ++u) rowptr_t[u] = (int32_t)k;
+}
+
+__global__ void k_transposed_entries(const int32_t *rowptr, int64_t n_dst, const int32_t *perm, int64_t E,
+                                     const float *ew, int32_t *colidx_t, float *ew_t) {
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= E) return;
+    const int32_t e = perm[k];
+    // destination of entry e: the last row v with rowptr[v] <= e
+    int64_t lo = 0, hi = n_dst;   // invariant: rowptr[lo] <= e < rowptr[hi]
+    while (hi - lo > 1) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (rowptr[mid] <= e) lo = mid; else hi = mid;
+    }
+    colidx_t[k] = (int32_t)lo;
+    if (ew_t) ew_t[k] = ew[e];
+}
+
+// per-row item / partial / split counts
+__global__ void k_item_counts(const int32_t *rowptr, int64_t n_rows, int32_t *c_items, int32_t *c_parts,
+                              int32_t *c_splits) {
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_rows) return;
+    const int32_t d = rowptr[r + 1] - rowptr[r];
+    const bool split = d > GT_SPLIT_MIN;
+    const int32_t chunks = (d + GT_CHUNK - 1) / GT_CHUNK;
+    c_items[r] = split ? chunks : 1;
+    c_parts[r] = split ? chunks : 0;
+    c_splits[r] = split ? 1 : 0;
+}
+
+__device__ inline uint32_t length_key(int32_t len) {
+    // descending-length sort key, quarter-octave resolution (exact below 16)
+    uint32_t k;
+    if (len < 16) {
+        k = (uint32_t)len;
+    } else {
+        const int lg = 31 - __clz(len);
+        k = 16u + (uint32_t)(lg - 4) * 4u + (((uint32_t)len >> (lg - 2)) & 3u);
+    }
+    return 255u - k;
+}
+
+__global__ void k_fill_items(const int32_t *rowptr, int64_t n_rows, const int32_t *o_items, const int32_t *o_parts,
+                             const int32_t *o_splits, gt_item *items, uint32_t *keys, gt_split *splits) {
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_rows) return;
+    const int32_t b = rowptr[r], e = rowptr[r + 1], d = e - b;
+    int32_t it = o_items[r];
+    if (d > GT_SPLIT_MIN) {
+        const int32_t chunks = (d + GT_CHUNK - 1) / GT_CHUNK;
+        const int32_t p0 = o_parts[r];
+        gt_split s;
+        s.row = (int32_t)r; s.first = p0; s.count = chunks; s.pad = 0;
+        splits[o_splits[r]] = s;
+        for (int32_t c = 0; c < chunks; ++c) {
+            gt_item x;
+            x.row = (int32_t)r;
+            x.e0 = b + c * GT_CHUNK;
+            x.e1 = min(e, x.e0 + GT_CHUNK);
+            x.slot = p0 + c;
+            items[it + c] = x;
+            keys[it + c] = length_key(x.e1 - x.e0);
+        }
+    } else {
+        gt_item x;
+        x.row = (int32_t)r; x.e0 = b; x.e1 = e; x.slot = -1;
+        items[it] = x;
+        keys[it] = length_key(d);
+    }
+}
+
+__global__ void k_gather_items(const gt_item *src, const uint32_t *idx, int64_t n, gt_item *dst) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = src[idx[i]];
+}
+
+__global__ void k_validate(const int32_t *rowptr, const int32_t *colidx, int64_t n_dst, int64_t n_src, int64_t E,
+                           unsigned long long *bad) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    unsigned long long v = 0;
+    if (i < n_dst && rowptr[i + 1] < rowptr[i]) v++;
+    if (i == 0 && rowptr[0] != 0) v++;
+    if (i == 0 && (int64_t)rowptr[n_dst] != E) v++;
+    if (i < E && (colidx[i] < 0 || (int64_t)colidx[i] >= n_src)) v++;
+    if (v) atomicAdd(bad, v);   // integer atomic: the count does not depend on the order
+}
+
+// ---------------------------------------------------------------------------------------------
+// workspace layout
+// ---------------------------------------------------------------------------------------------
+struct PlanLayout {
+    size_t in_deg, out_deg, rowptr_t, colidx_t, perm, ew_t, dinv, rdeg;
+    size_t items_f, splits_f, items_b, splits_b;
+    size_t counts;                       // 8 int32 read back by the host
+    size_t ca, cb, cc;                   // per-row count arrays (max(n_dst, n_src) + 1 each)
+    size_t items_tmp, item_keys, item_keys2, item_idx;   // unsorted items, sort keys / indices
+    size_t k0, v0, k1, v1;               // sort ping-pong (E each)
+    size_t hist, scan_tmp;
+    size_t total;
+};
+
+int64_t max_items(int64_t n_rows, int64_t E) { return n_rows + E / GT_CHUNK + 1; }
+int64_t max_splits(int64_t E) { return E / GT_SPLIT_MIN + 1; }
+
+PlanLayout plan_layout(int64_t n_dst, int64_t n_src, int64_t E, bool has_ew) {
+    PlanLayout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += gt_align_up(bytes ? bytes : 4); return o; };
+    const int64_t nmax = (n_dst > n_src ? n_dst : n_src);
+    const int64_t imax = max_items(nmax, E);
+    L.in_deg = take((size_t)n_dst * 4);
+    L.out_deg = take((size_t)n_src * 4);
+    L.rowptr_t = take((size_t)(n_src + 1) * 4);
+    L.colidx_t = take((size_t)E * 4);
+    L.perm = take((size_t)E * 4);
+    L.ew_t = take(has_ew ? (size_t)E * 4 : 0);
+    L.dinv = take((size_t)nmax * 4);
+    L.rdeg = take((size_t)n_dst * 4);
+    L.items_f = take((size_t)max_items(n_dst, E) * sizeof(gt_item));
+    L.splits_f = take((size_t)max_splits(E) * sizeof(gt_split));
+    L.items_b = take((size_t)max_items(n_src, E) * sizeof(gt_item));
+    L.splits_b = take((size_t)max_splits(E) * sizeof(gt_split));
+    L.counts = take(128);
+    L.ca = take((size_t)(nmax + 1) * 4);
+    L.cb = take((size_t)(nmax + 1) * 4);
+    L.cc = take((size_t)(nmax + 1) * 4);
+    L.items_tmp = take((size_t)imax * sizeof(gt_item));
+    L.item_keys = take((size_t)imax * 4);
+    L.item_keys2 = take((size_t)imax * 4);
+    L.item_idx = take((size_t)imax * 4);
+    L.k0 = take((size_t)E * 4);
+    L.v0 = take((size_t)E * 4);
+    L.k1 = take((size_t)E * 4);
+    L.v1 = take((size_t)E * 4);
+    const int64_t nsort = E > imax ? E : imax;
+    const int64_t hist_n = (int64_t)256 * (rs_blocks(nsort) + 1);
+    L.hist = take((size_t)hist_n * 4);
+    const int64_t scan_n = hist_n > nmax + 1 ? hist_n : nmax + 1;
+    L.scan_tmp = take(scan_tmp_ints(scan_n) * 4);
+    L.total = off;
+    return L;
+}
+
+template <typename T>
+T *at(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(ws) + off); }
+
+// counts of one direction into cnt[0..2] (items, partials, splits): scans of the per-row counts;
+// the exclusive scan over n_rows + 1 entries (last input 0) leaves the total in element n_rows.
+gt_status count_direction(const int32_t *rowptr, int64_t n_rows, void *ws, const PlanLayout &L, int32_t *cnt3,
+                          hipStream_t st) {
+    int32_t *ca = at<int32_t>(ws, L.ca), *cb = at<int32_t>(ws, L.cb), *cc = at<int32_t>(ws, L.cc);
+    int32_t *stmp = at<int32_t>(ws, L.scan_tmp);
+    GT_HIP(hipMemsetAsync(ca + n_rows, 0, 4, st));
+    GT_HIP(hipMemsetAsync(cb + n_rows, 0, 4, st));
+    GT_HIP(hipMemsetAsync(cc + n_rows, 0, 4, st));
+    if (n_rows > 0) {
+        k_item_counts<<<nblocks(n_rows), PT, 0, st>>>(rowptr, n_rows, ca, cb, cc);
+        GT_LAUNCH_CHECK("k_item_counts");
+    }
+    gt_status s;
+    if ((s = scan_exclusive(ca, ca, n_rows + 1, stmp, st)) != GT_OK) return s;
+    if ((s = scan_exclusive(cb, cb, n_rows + 1, stmp, st)) != GT_OK) return s;
+    if ((s = scan_exclusive(cc, cc, n_rows + 1, stmp, st)) != GT_OK) return s;
+    GT_HIP(hipMemcpyAsync(cnt3 + 0, ca + n_rows, 4, hipMemcpyDeviceToDevice, st));
+    GT_HIP(hipMemcpyAsync(cnt3 + 1, cb + n_rows, 4, hipMemcpyDeviceToDevice, st));
+    GT_HIP(hipMemcpyAsync(cnt3 + 2, cc + n_rows, 4, hipMemcpyDeviceToDevice, st));
+    return GT_OK;
+}
+
+// items of one direction, sorted longest first (stable, so equal lengths keep row order).
+gt_status build_direction(const int32_t *rowptr, int64_t n_rows, int64_t n_items, void *ws, const PlanLayout &L,
+                          gt_item *items_out, gt_split *splits_out, hipStream_t st) {
+    if (n_rows <= 0 || n_items <= 0) return GT_OK;
+    int32_t *ca = at<int32_t>(ws, L.ca), *cb = at<int32_t>(ws, L.cb), *cc = at<int32_t>(ws, L.cc);
+    gt_item *tmp = at<gt_item>(ws, L.items_tmp);
+    uint32_t *keys = at<uint32_t>(ws, L.item_keys), *keys2 = at<uint32_t>(ws, L.item_keys2);
+    uint32_t *idx = at<uint32_t>(ws, L.item_idx);
+    k_fill_items<<<nblocks(n_rows), PT, 0, st>>>(rowptr, n_rows, ca, cb, cc, tmp, keys, splits_out);
+    GT_LAUNCH_CHECK("k_fill_items");
+    SortTmp t{at<int32_t>(ws, L.hist), at<int32_t>(ws, L.scan_tmp)};
+    gt_status s = radix_pass(keys, nullptr, keys2, idx, n_items, 0, t, st);
+    if (s != GT_OK) return s;
+    k_gather_items<<<nblocks(n_items), PT, 0, st>>>(tmp, idx, n_items, items_out);
+    GT_LAUNCH_CHECK("k_gather_items");
+    return GT_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------
+extern "C" gt_status gt_graph_plan_size(int64_t n_dst, int64_t n_src, int64_t n_edges, int has_edge_weight,
+                                        size_t *ws_bytes) {
+    if (!ws_bytes) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_plan_size: ws_bytes is null");
+    if (n_dst < 0 || n_src < 0 || n_edges < 0) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_plan_size: negative size");
+    const int64_t lim = 2147483647LL - 1;
+    if (n_dst >= lim || n_src >= lim || n_edges >= lim)
+        return gt_fail(GT_ERR_UNSUPPORTED, "gt_graph_plan_size: sizes must be below 2^31 - 1 (int32 indices)");
+    *ws_bytes = plan_layout(n_dst, n_src, n_edges, has_edge_weight != 0).total;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_graph_create(gt_graph **out, int64_t n_dst, int64_t n_src, int64_t E, const int32_t *rowptr,
+                                     const int32_t *colidx, const float *ew, void *ws, size_t ws_bytes, void *stream) {
+    if (!out) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_create: g is null");
+    *out = nullptr;
+    size_t need = 0;
+    gt_status s = gt_graph_plan_size(n_dst, n_src, E, ew != nullptr, &need);
+    if (s != GT_OK) return s;
+    if (!rowptr) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_create: rowptr is null");
+    if (E > 0 && !colidx) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_create: colidx is null with n_edges > 0");
+    if (E > 0 && n_src == 0) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_create: edges but n_src == 0");
+    if (E > 0 && n_dst == 0) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_create: edges but n_dst == 0");
+    if (!ws || ((uintptr_t)ws & 255)) return gt_fail(GT_ERR_WORKSPACE, "gt_graph_create: ws null or not 256-byte aligned");
+    if (ws_bytes < need) return gt_fail(GT_ERR_WORKSPACE, "gt_graph_create: ws_bytes %zu < required %zu", ws_bytes, need);
+    hipStream_t st = (hipStream_t)stream;
+    const PlanLayout L = plan_layout(n_dst, n_src, E, ew != nullptr);
+
+    gt_graph *g = new (std::nothrow) gt_graph();
+    if (!g) return gt_fail(GT_ERR_INTERNAL, "gt_graph_create: out of host memory");
+    g->n_dst = n_dst; g->n_src = n_src; g->n_edges = E;
+    g->rowptr = rowptr; g->colidx = colidx; g->ew = ew;
+    g->in_deg = at<int32_t>(ws, L.in_deg);
+    g->out_deg = at<int32_t>(ws, L.out_deg);
+    g->rowptr_t = at<int32_t>(ws, L.rowptr_t);
+    g->colidx_t = at<int32_t>(ws, L.colidx_t);
+    g->perm = at<int32_t>(ws, L.perm);
+    g->ew_t = ew ? at<float>(ws, L.ew_t) : nullptr;
+    g->dinv = (n_dst == n_src) ? at<float>(ws, L.dinv) : nullptr;
+    g->rdeg = at<float>(ws, L.rdeg);
+    g->vcount = at<unsigned long long>(ws, L.counts + 64);
+
+    auto fail = [&](gt_status rc) { delete g; return rc; };
+#define PLAN_HIP(call) do { hipError_t e__ = (call); if (e__ != hipSuccess) return fail(gt_hip_fail(e__, #call)); } while (0)
+#define PLAN_LAUNCH(what) do { hipError_t e__ = hipGetLastError(); if (e__ != hipSuccess) return fail(gt_hip_fail(e__, what)); } while (0)
+
+    // degrees of the given CSR
+    if (n_dst > 0) {
+        k_row_degrees<<<nblocks(n_dst), PT, 0, st>>>(rowptr, n_dst, g->in_deg, g->rdeg, g->dinv);
+        PLAN_LAUNCH("k_row_degrees");
+    }
+    // transposed structure: stable sort of (source, position) pairs by source
+    SortTmp t{at<int32_t>(ws, L.hist), at<int32_t>(ws, L.scan_tmp)};
+    uint32_t *k0 = at<uint32_t>(ws, L.k0), *v0 = at<uint32_t>(ws, L.v0);
+    uint32_t *k1 = at<uint32_t>(ws, L.k1), *v1 = at<uint32_t>(ws, L.v1);
+    const uint32_t *sorted_keys = reinterpret_cast<const uint32_t *>(colidx);
+    if (E > 0) {
+        int bits = 1;
+        while (bits < 32 && ((int64_t)1 << bits) < n_src) ++bits;
+        const int passes = (bits + 7) / 8;
+        const uint32_t *kin = reinterpret_cast<const uint32_t *>(colidx);
+        const uint32_t *vin = nullptr;
+        for (int p = 0; p < passes; ++p) {
+            uint32_t *ko = (p & 1) ? k1 : k0;
+            uint32_t *vo = (p == passes - 1) ? reinterpret_cast<uint32_t *>(g->perm) : ((p & 1) ? v1 : v0);
+            if ((s = radix_pass(kin, vin, ko, vo, E, 8 * p, t, st)) != GT_OK) return fail(s);
+            kin = ko; vin = vo;
+        }
+        sorted_keys = kin;
+    }
+    if (n_src >= 0) {
+        k_boundaries<<<nblocks(E + 1), PT, 0, st>>>(sorted_keys, E, n_src, g->rowptr_t);
+        PLAN_LAUNCH("k_boundaries");
+    }
+    if (n_src > 0) {
+        k_row_degrees<<<nblocks(n_src), PT, 0, st>>>(g->rowptr_t, n_src, g->out_deg, nullptr, nullptr);
+        PLAN_LAUNCH("k_row_degrees(out)");
+    }
+    if (E > 0) {
+        k_transposed_entries<<<nblocks(E), PT, 0, st>>>(rowptr, n_dst, g->perm, E, ew, g->colidx_t, g->ew_t);
+        PLAN_LAUNCH("k_transposed_entries");
+    }
+    // work-list sizes of both directions, read back once
+    int32_t *d_counts = at<int32_t>(ws, L.counts);
+    int32_t h_counts[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    // forward counts are consumed (scanned arrays) before the transposed direction reuses them,
+    // so the forward items are filled between the two counting steps.
+    if ((s = count_direction(rowptr, n_dst, ws, L, d_counts, st)) != GT_OK) return fail(s);
+    PLAN_HIP(hipMemcpyAsync(h_counts, d_counts, 3 * 4, hipMemcpyDeviceToHost, st));
+    PLAN_HIP(hipStreamSynchronize(st));
+    g->fwd.rowptr = rowptr; g->fwd.nbr = colidx; g->fwd.wt = ew; g->fwd.n_rows = n_dst;
+    g->fwd.n_items = h_counts[0]; g->fwd.n_partials = h_counts[1]; g->fwd.n_splits = h_counts[2];
+    g->fwd.items = at<gt_item>(ws, L.items_f); g->fwd.splits = at<gt_split>(ws, L.splits_f);
+    if (g->fwd.n_items > max_items(n_dst, E) || g->fwd.n_splits > max_splits(E))
+        return fail(gt_fail(GT_ERR_INTERNAL, "gt_graph_create: forward work list exceeds its bound (is rowptr valid?)"));
+    if ((s = build_direction(rowptr, n_dst, g->fwd.n_items, ws, L, at<gt_item>(ws, L.items_f),
+                             at<gt_split>(ws, L.splits_f), st)) != GT_OK) return fail(s);
+
+    if ((s = count_direction(g->rowptr_t, n_src, ws, L, d_counts + 4, st)) != GT_OK) return fail(s);
+    PLAN_HIP(hipMemcpyAsync(h_counts + 4, d_counts + 4, 3 * 4, hipMemcpyDeviceToHost, st));
+    PLAN_HIP(hipStreamSynchronize(st));
+    g->bwd.rowptr = g->rowptr_t; g->bwd.nbr = g->colidx_t; g->bwd.wt = g->ew_t; g->bwd.n_rows = n_src;
+    g->bwd.n_items = h_counts[4]; g->bwd.n_partials = h_counts[5]; g->bwd.n_splits = h_counts[6];
+    g->bwd.items = at<gt_item>(ws, L.items_b); g->bwd.splits = at<gt_split>(ws, L.splits_b);
+    if (g->bwd.n_items > max_items(n_src, E) || g->bwd.n_splits > max_splits(E))
+        return fail(gt_fail(GT_ERR_INTERNAL, "gt_graph_create: transposed work list exceeds its bound"));
+    if ((s = build_direction(g->rowptr_t, n_src, g->bwd.n_items, ws, L, at<gt_item>(ws, L.items_b),
+                             at<gt_split>(ws, L.splits_b), st)) != GT_OK) return fail(s);
+    PLAN_HIP(hipStreamSynchronize(st));
+#undef PLAN_HIP
+#undef PLAN_LAUNCH
+    *out = g;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_graph_destroy(gt_graph *g) {
+    delete g;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_graph_outputs(const gt_graph *g, const int32_t **in_deg, const int32_t **out_deg,
+                                      const int32_t **rowptr_t, const int32_t **colidx_t, const int32_t **perm) {
+    if (!g) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_outputs: g is null");
+    if (in_deg) *in_deg = g->in_deg;
+    if (out_deg) *out_deg = g->out_deg;
+    if (rowptr_t) *rowptr_t = g->rowptr_t;
+    if (colidx_t) *colidx_t = g->colidx_t;
+    if (perm) *perm = g->perm;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_graph_info(const gt_graph *g, int64_t *n_dst, int64_t *n_src, int64_t *n_edges,
+                                   int64_t *fwd_items, int64_t *fwd_split_rows, int64_t *bwd_items,
+                                   int64_t *bwd_split_rows) {
+    if (!g) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_info: g is null");
+    if (n_dst) *n_dst = g->n_dst;
+    if (n_src) *n_src = g->n_src;
+    if (n_edges) *n_edges = g->n_edges;
+    if (fwd_items) *fwd_items = g->fwd.n_items;
+    if (fwd_split_rows) *fwd_split_rows = g->fwd.n_splits;
+    if (bwd_items) *bwd_items = g->bwd.n_items;
+    if (bwd_split_rows) *bwd_split_rows = g->bwd.n_splits;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_graph_validate(const gt_graph *g, int64_t *n_violations, void *stream) {
+    if (!g || !n_violations) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_validate: null argument");
+    hipStream_t st = (hipStream_t)stream;
+    GT_HIP(hipMemsetAsync(g->vcount, 0, 8, st));
+    const int64_t n = (g->n_edges > g->n_dst ? g->n_edges : g->n_dst);
+    k_validate<<<nblocks(n > 0 ? n : 1), PT, 0, st>>>(g->rowptr, g->colidx, g->n_dst, g->n_src, g->n_edges, g->vcount);
+    GT_LAUNCH_CHECK("k_validate");
+    unsigned long long h = 0;
+    GT_HIP(hipMemcpyAsync(&h, g->vcount, 8, hipMemcpyDeviceToHost, st));
+    GT_HIP(hipStreamSynchronize(st));
+    *n_violations = (int64_t)h;
+    return GT_OK;
+}

@@ -1,0 +1,157 @@
+"""gt_aggregate_fwd / gt_aggregate_bwd against the oracle, element by element.
+
+Tolerances.  fp32: every output is a sum of at most GT_CHUNK fp32 fused multiply-adds per work
+item plus the ordered sum of its partials, so |gpu - ref| <= 1e-5 * sum_e |c_e x_e| holds with a
+wide margin (worst-case bound of sequential summation: n * 2^-24 per term); the tensor-level
+metric max|gpu - ref| / max|ref| must be <= 1e-5.  bf16: the result is rounded once to bf16
+(relative 2^-8), the oracle's fp64 result is rounded the same way, the two can differ by one
+bf16 step when the fp32 sum sits next to a rounding boundary: |gpu - ref| <= 2^-7 |ref| + the
+fp32 term; tensor-level <= 2e-2.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gt_inputs import configs, graphs, tensors
+from gpu_util import (announce, down, empty_feat, max_rel_err, pad_to, tol_for, up_feat, up_i32)
+
+pytestmark = pytest.mark.gpu
+
+WIDTHS = [1, 3, 16, 41, 47, 64, 100, 128, 256, 602, 1024]
+
+
+def _graph_hubs():
+    """4,096-vertex R-MAT plus two planted hub rows (2,000 and 700 in-edges) and a planted hub
+    source, so split rows, near-threshold rows, empty rows and tiny rows all occur."""
+    rp, ci = graphs.rmat_csr(12, 8, seed=31, self_loops=False)
+    n = rp.size - 1
+    dst = np.repeat(np.arange(n), np.diff(rp))
+    rng = np.random.default_rng(8)
+    extra_s = np.concatenate([rng.choice(n, 2000, replace=False), rng.choice(n, 700, replace=False),
+                              np.full(1500, 5)])
+    extra_d = np.concatenate([np.full(2000, 17), np.full(700, 900), rng.choice(n, 1500, replace=False)])
+    rp, ci = graphs.csr_from_pairs(np.concatenate([ci, extra_s]), np.concatenate([dst, extra_d]), n, n)
+    return rp, ci, n
+
+
+def _check(got, ref, abs_terms, dtype, what):
+    tol = tol_for(dtype)
+    assert max_rel_err(got, ref) <= tol, (what, max_rel_err(got, ref))
+    bound = 1e-5 * abs_terms + 1e-30
+    if dtype == "bf16":
+        bound = bound + 2.0 ** -7 * np.abs(ref)
+    bad = np.abs(got - ref) > bound
+    assert not bad.any(), (what, int(bad.sum()), float(np.abs(got - ref).max()))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("F", WIDTHS)
+def test_aggregate_widths_hub_graph(F, dtype):
+    from paper_2305_17469_amd import binding as B
+    rp, ci, n = _graph_hubs()
+    g = B.Graph(up_i32(rp), up_i32(ci), n)
+    X = tensors.normal((n, F), seed=100 + F)
+    if dtype == "bf16":
+        X = tensors.bf16_values(X)
+    G = tensors.normal((n, F), seed=200 + F)
+    if dtype == "bf16":
+        G = tensors.bf16_values(G)
+    for reduce in ("sum", "mean", "symnorm"):
+        for ld in sorted({F, pad_to(F, dtype) + (8 if F % 2 else 0)}):
+            announce("aggregate", dtype, "F", F, "ld", ld, reduce)
+            Xd = up_feat(X, dtype, ld)
+            Y = empty_feat(n, F, dtype, ld)
+            B.gt_aggregate_fwd(g, reduce, Xd, out=Y)
+            ref = oracle.aggregate_fwd(rp, ci, n, X, reduce)
+            absr = oracle.aggregate_fwd(rp, ci, n, np.abs(X), reduce)
+            if dtype == "bf16":
+                ref = oracle.round_bf16(ref)
+            _check(down(Y), ref, absr, dtype, ("fwd", reduce, F, ld))
+            Gd = up_feat(G, dtype, ld)
+            dX = empty_feat(n, F, dtype, ld)
+            B.gt_aggregate_bwd(g, reduce, Gd, out=dX)
+            ref = oracle.aggregate_bwd(rp, ci, n, G, reduce)
+            absr = oracle.aggregate_bwd(rp, ci, n, np.abs(G), reduce)
+            if dtype == "bf16":
+                ref = oracle.round_bf16(ref)
+            _check(down(dX), ref, absr, dtype, ("bwd", reduce, F, ld))
+            if ld > F:   # padding columns of the outputs are never written
+                assert torch.isnan(Y.as_strided((n, ld - F), (ld, 1), Y.storage_offset() + F)).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_aggregate_edge_weights_and_bipartite(dtype):
+    from paper_2305_17469_amd import binding as B
+    cfg = configs.sage_minibatch(12, 64)
+    for blk in cfg["blocks"]:
+        rp, ci, ns, nd = blk["rowptr"], blk["colidx"], blk["n_src"], blk["n_dst"]
+        ew = np.random.default_rng(5).uniform(0.25, 2.0, ci.size).astype(np.float32)
+        g = B.Graph(up_i32(rp), up_i32(ci), ns, torch.from_numpy(ew).cuda())
+        F = 40
+        X = tensors.normal((ns, F), seed=7)
+        G = tensors.normal((nd, F), seed=8)
+        if dtype == "bf16":
+            X, G = tensors.bf16_values(X), tensors.bf16_values(G)
+        for reduce in ("sum", "mean"):
+            announce("aggregate weighted bipartite", dtype, reduce, nd, ns)
+            Y = B.gt_aggregate_fwd(g, reduce, up_feat(X, dtype))
+            ref = oracle.aggregate_fwd(rp, ci, ns, X, reduce, ew)
+            absr = oracle.aggregate_fwd(rp, ci, ns, np.abs(X), reduce, ew)
+            _check(down(Y), oracle.round_bf16(ref) if dtype == "bf16" else ref, absr, dtype, ("fwd", reduce))
+            dX = B.gt_aggregate_bwd(g, reduce, up_feat(G, dtype))
+            ref = oracle.aggregate_bwd(rp, ci, ns, G, reduce, ew)
+            absr = oracle.aggregate_bwd(rp, ci, ns, np.abs(G), reduce, ew)
+            _check(down(dX), oracle.round_bf16(ref) if dtype == "bf16" else ref, absr, dtype, ("bwd", reduce))
+        with pytest.raises(B.GtError) as e:
+            B.gt_aggregate_fwd(g, "symnorm", up_feat(X, dtype))
+        assert e.value.status == 2   # UNSUPPORTED on a non-square graph
+
+
+def test_exact_invariants_on_the_gpu():
+    """sum of ones = in-degree exactly, mean of ones = 1 exactly (division, not reciprocal)."""
+    from paper_2305_17469_amd import binding as B
+    rp, ci, n = _graph_hubs()
+    announce("aggregate invariants")
+    g = B.Graph(up_i32(rp), up_i32(ci), n)
+    ones = torch.ones((n, 8), dtype=torch.float32, device="cuda")
+    deg = np.diff(rp).astype(np.float64)
+    np.testing.assert_array_equal(down(B.gt_aggregate_fwd(g, "sum", ones)), np.repeat(deg[:, None], 8, 1))
+    np.testing.assert_array_equal(down(B.gt_aggregate_fwd(g, "mean", ones)), np.repeat((deg > 0)[:, None], 8, 1) * 1.0)
+    dout = np.bincount(ci, minlength=n).astype(np.float64)
+    np.testing.assert_array_equal(down(B.gt_aggregate_bwd(g, "sum", ones)), np.repeat(dout[:, None], 8, 1))
+
+
+def test_bitwise_reproducible_and_argument_errors():
+    from paper_2305_17469_amd import binding as B
+    rp, ci, n = _graph_hubs()
+    announce("aggregate determinism + errors")
+    g = B.Graph(up_i32(rp), up_i32(ci), n)
+    X = up_feat(tensors.normal((n, 100), seed=3), "f32", 104)
+    a = B.gt_aggregate_fwd(g, "symnorm", X).clone()
+    b = B.gt_aggregate_fwd(g, "symnorm", X).clone()
+    assert torch.equal(a, b)
+    g2 = B.Graph(up_i32(rp), up_i32(ci), n)       # a second plan of the same graph gives the same bits
+    assert torch.equal(a, B.gt_aggregate_fwd(g2, "symnorm", X))
+    with pytest.raises(B.GtError) as e:           # in-place is rejected
+        B.gt_aggregate_fwd(g, "sum", X, out=X)
+    assert e.value.status == 1
+    st = B.lib.gt_aggregate_fwd(g.handle, 0, 0, 100, X.data_ptr(), 50, a.data_ptr(), 100, None, 0, None)
+    assert st == 1                                # ld < F
+    need = g.aggregate_ws(100).numel()
+    st = B.lib.gt_aggregate_fwd(g.handle, 0, 0, 100, X.data_ptr(), 104, a.data_ptr(), 100, None, 0, None)
+    assert st == 3 and need > 256                 # split rows need the scratch buffer
+    # zero-width and empty-graph calls are no-ops
+    assert B.lib.gt_aggregate_fwd(g.handle, 0, 0, 0, None, 0, None, 0, None, 0, None) == 0
+    g0 = B.Graph(up_i32(np.zeros(1, np.int32)), up_i32(np.zeros(0, np.int32)), 0)
+    assert B.lib.gt_aggregate_fwd(g0.handle, 0, 0, 16, None, 16, None, 16, None, 0, None) == 0
+
+
+def test_empty_rows_only():
+    from paper_2305_17469_amd import binding as B
+    announce("aggregate: graph without edges")
+    g = B.Graph(up_i32(np.zeros(8, np.int32)), up_i32(np.zeros(0, np.int32)), 5)
+    X = up_feat(tensors.normal((5, 12), seed=1), "f32")
+    for reduce in ("sum", "mean"):
+        assert torch.count_nonzero(B.gt_aggregate_fwd(g, reduce, X)) == 0
+        assert torch.count_nonzero(B.gt_aggregate_bwd(g, reduce, up_feat(tensors.normal((7, 12), seed=2), "f32"))) == 0

@@ -1,0 +1,93 @@
+"""gt_combine against the oracle's triple loop.
+
+Tolerance: fp32 MFMA accumulates K products in fp32; |gpu - ref| <= 1e-5 * (|A| |B| + |bias|)
+element-wise (sequential-summation bound is K * 2^-24 per term, far looser in practice) and
+max|gpu - ref| / max|ref| <= 1e-5.  bf16 inputs: products are exact in fp32, the fp32 sum is
+rounded once to bf16 when C is bf16 (2^-8 relative, one step of slack against the oracle's
+rounding); tensor-level <= 2e-2.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gt_inputs import tensors
+from gpu_util import announce, down, max_rel_err, tol_for, up_feat
+
+pytestmark = pytest.mark.gpu
+
+# (M, N, K): several tiles, ragged tails in every dimension, the skinny widths of the workloads
+SHAPES = [(1, 1, 1), (300, 64, 64), (257, 16, 100), (515, 41, 128), (130, 47, 256), (260, 128, 602),
+          (129, 256, 100), (70, 1024, 16), (200, 16, 1024), (33, 130, 37)]
+
+
+def _check(got, ref, absr, dtype, c_bf16, what):
+    assert max_rel_err(got, ref) <= tol_for("bf16" if c_bf16 else dtype), (what, max_rel_err(got, ref))
+    bound = 1e-5 * absr + 1e-30
+    if c_bf16:
+        bound = bound + 2.0 ** -7 * np.abs(ref)
+    bad = np.abs(got - ref) > bound
+    assert not bad.any(), (what, int(bad.sum()), float(np.abs(got - ref).max()))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_combine_all_transposes(shape, dtype):
+    from paper_2305_17469_amd import binding as B
+    M, N, K = shape
+    A = tensors.normal((M, K), seed=M + K)
+    Bm = tensors.normal((K, N), seed=N + K + 1)
+    bias = tensors.normal((N,), seed=5)
+    if dtype == "bf16":
+        A, Bm = tensors.bf16_values(A), tensors.bf16_values(Bm)
+    ref_lin = oracle.combine(A, Bm)
+    absr = oracle.combine(np.abs(A), np.abs(Bm))
+    for tA in (False, True):
+        for tB in (False, True):
+            for padded in (False, True):
+                announce("combine", dtype, shape, "tA", tA, "tB", tB, "padded", padded)
+                a_host = A.T.copy() if tA else A
+                b_host = Bm.T.copy() if tB else Bm
+                v = 8 if dtype == "bf16" else 4
+                lda = (a_host.shape[1] + v - 1) // v * v if padded else a_host.shape[1]
+                ldb = (b_host.shape[1] + v - 1) // v * v if padded else b_host.shape[1]
+                Ad, Bd = up_feat(a_host, dtype, lda), up_feat(b_host, dtype, ldb)
+                C = B.gt_combine(Ad, Bd, transA=tA, transB=tB)
+                ref = oracle.round_bf16(ref_lin) if dtype == "bf16" else ref_lin
+                _check(down(C), ref, absr, dtype, dtype == "bf16", ("lin", tA, tB, padded))
+                if not padded:
+                    continue
+                Cb = B.gt_combine(Ad, Bd, torch.from_numpy(bias).cuda(), relu=True, transA=tA, transB=tB)
+                refb = oracle.combine(A, Bm, bias, relu=True)
+                refb = oracle.round_bf16(refb) if dtype == "bf16" else refb
+                _check(down(Cb), refb, absr + np.abs(bias)[None, :], dtype, dtype == "bf16", ("bias_relu", tA, tB))
+                if dtype == "bf16":   # fp32 output from bf16 operands (the weight-gradient case)
+                    C32 = B.gt_combine(Ad, Bd, transA=tA, transB=tB, out_dtype=torch.float32)
+                    _check(down(C32), ref_lin, absr, dtype, False, ("f32out", tA, tB))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_weight_gradient_shape_split_reduction(dtype):
+    """op(A)^T op(B) with a long reduction (the node dimension): split over workgroups, summed in
+    a fixed order; must be reproducible bit for bit."""
+    from paper_2305_17469_amd import binding as B
+    rows, fi, fo = 40_000, 100, 47
+    A = tensors.normal((rows, fi), seed=11)
+    G = tensors.normal((rows, fo), seed=12)
+    if dtype == "bf16":
+        A, G = tensors.bf16_values(A), tensors.bf16_values(G)
+    announce("combine weight gradient", dtype, rows, fi, fo)
+    v = 8 if dtype == "bf16" else 4
+    Ad = up_feat(A, dtype, (fi + v - 1) // v * v)
+    Gd = up_feat(G, dtype, (fo + v - 1) // v * v)
+    need = B.c_size_t()
+    assert B.lib.gt_combine_ws_size(0, 1, 0, fi, fo, rows, B.byref(need)) == 0 and need.value > 0
+    C1 = B.gt_combine(Ad, Gd, transA=True, out_dtype=torch.float32)
+    C2 = B.gt_combine(Ad, Gd, transA=True, out_dtype=torch.float32)
+    assert torch.equal(C1, C2)
+    ref = oracle.combine(A, G, transA=True)
+    absr = oracle.combine(np.abs(A), np.abs(G), transA=True)
+    _check(down(C1), ref, absr, dtype, False, "dW")
+    st = B.lib.gt_combine(0, 1, 0, fi, fo, rows, Ad.data_ptr(), Ad.stride(0), Gd.data_ptr(), Gd.stride(0), None, 0,
+                          C1.data_ptr(), fo, 0, None, 0, None) if dtype == "f32" else 3
+    assert st == 3   # the split reduction needs its workspace
