@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the GNN hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2]
+
+A step is one forward + backward pass of the whole model of the chosen workload through
+gt_layer_fwd / gt_layer_bwd (aggregation, combination, kernel placement and their derivatives),
+with all inputs resident in HBM.  The graph plan (degrees, transposed structure, work lists) is
+built once per graph before the timed region and its time is reported separately (`plan_ms`).
+Prints ONE JSON line.  Everything runs on one GPU; --gpus above 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E
+
+
+def build_workload(name, scale):
+    from gt_inputs import configs
+    if name == "c1":
+        return configs.tiny(scale or 12)
+    if name == "c2":
+        return configs.reddit_like(scale or 18)
+    if name == "c3":
+        return configs.products_like(scale or 21)
+    if name == "c4":
+        return configs.sage_minibatch(scale or 21)
+    if name == "c5a":
+        return configs.reorder_stress(scale or 20, True, "sum")
+    if name == "c5b":
+        return configs.reorder_stress(scale or 20, False, "sum")
+    raise SystemExit("unknown --config %s" % name)
+
+
+def agg_algorithmic_bytes(E, n_out, F, s, reduce, transposed, has_ew):
+    """Gather-model bytes of one aggregation launch: every edge gathers one row of F elements,
+    every output row is written once, plus the index / coefficient streams."""
+    b = E * F * s + n_out * F * s + E * 4 + (n_out + 1) * 4
+    if has_ew:
+        b += E * 4
+    if reduce == "symnorm" or (reduce == "mean" and transposed):
+        b += E * 4          # per-neighbour scale gathered with the index
+    return b
+
+
+def cpu_baseline(cfg, nominal_ef, budget_rows=1 << 16):
+    """The oracle, as it stands, timed on a bounded sample: every kernel of the definitional
+    (aggregation-first) fwd+bwd step runs on a strided sample of its rows and its time is scaled
+    by the ratio of full to sampled work."""
+    import numpy as np
+    import oracle
+    L = len(cfg["W"])
+    est = 0.0
+    t_cpu = 0.0
+    rng = np.random.default_rng(0)
+    for l in range(L):
+        blk = cfg["blocks"][l]
+        rp, ci, ns, nd = blk["rowptr"], blk["colidx"], blk["n_src"], blk["n_dst"]
+        fi, fo = cfg["dims"][l], cfg["dims"][l + 1]
+        E = ci.size
+        stride = max(1, nd // budget_rows)
+        rows = np.arange(0, nd, stride, dtype=np.int64)
+        Es = int((rp[rows + 1] - rp[rows]).sum())
+        Xl = cfg["X"] if l == 0 else rng.standard_normal((ns, fi)).astype(np.float32)
+        # forward aggregation at width fi on the sampled destinations
+        t0 = time.perf_counter()
+        M = oracle.aggregate_fwd(rp, ci, ns, Xl, cfg["reduce"], rows=rows)
+        t = time.perf_counter() - t0
+        est += t * E / max(Es, 1); t_cpu += t
+        # forward combination on the sampled rows
+        t0 = time.perf_counter()
+        Z = oracle.combine(M, cfg["W"][l], cfg["b"][l], relu=l < L - 1)
+        t = time.perf_counter() - t0
+        est += t * nd / rows.size; t_cpu += t
+        # backward: dW = M^T dZ on the sampled rows
+        dZ = rng.standard_normal(Z.shape)
+        t0 = time.perf_counter()
+        oracle.combine(M, dZ, transA=True)
+        t = time.perf_counter() - t0
+        est += t * nd / rows.size; t_cpu += t
+        if l > 0:
+            # dM = dZ W^T on the sampled rows, then the scatter-form transposed aggregation of
+            # the sampled destination rows (sub-CSR of those rows, plain sum coefficients)
+            t0 = time.perf_counter()
+            dM = oracle.combine(dZ, cfg["W"][l], transB=True)
+            t = time.perf_counter() - t0
+            est += t * nd / rows.size; t_cpu += t
+            sub_rp = np.zeros(rows.size + 1, dtype=np.int64)
+            np.cumsum(rp[rows + 1] - rp[rows], out=sub_rp[1:])
+            sub_ci = np.concatenate([ci[rp[r]:rp[r + 1]] for r in rows]) if Es else np.zeros(0, np.int32)
+            t0 = time.perf_counter()
+            oracle.aggregate_bwd(sub_rp.astype(np.int32), sub_ci, ns, dM, "sum")
+            t = time.perf_counter() - t0
+            est += t * E / max(Es, 1); t_cpu += t
+    return dict(value=nominal_ef / est, unit="edge*feature/s", cores=oracle.num_threads(), kind="oracle",
+                sample="every kernel of the aggregation-first fwd+bwd step on a strided sample of about %d "
+                       "destination rows per layer (%.1f s of CPU time), scaled to the full row / edge counts; "
+                       "backward scatter on the sampled rows' sub-CSR with sum coefficients" % (budget_rows, t_cpu),
+                est_step_seconds=est)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c2")
+    ap.add_argument("--scale", type=int, default=0, help="override the vertex-count exponent (testing)")
+    ap.add_argument("--fwd-order", default="auto")
+    ap.add_argument("--bwd-order", default="auto")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+                         "run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2305_17469_amd import binding as B
+    from paper_2305_17469_amd.stack import LayerStack
+    from gt_inputs import tensors
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
+    dev = torch.device("cuda:0")
+    t0 = time.time()
+    cfg = build_workload(args.config, args.scale)
+    gen_s = time.time() - t0
+    dt = cfg["dtype"]
+    s = 2 if dt == "bf16" else 4
+
+    def up(a, ld=None):
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        n, F = a.shape
+        v = 8 if dt == "bf16" else 4
+        ld = (F + v - 1) // v * v if ld is None else ld
+        host = torch.from_numpy(tensors.to_bf16_bits(a).view(np.int16)).view(torch.bfloat16) if dt == "bf16" \
+            else torch.from_numpy(a)
+        buf = torch.zeros((n, ld), dtype=host.dtype, device=dev)
+        buf[:, :F] = host.to(dev)
+        return buf[:, :F]
+
+    blocks, seen = [], {}
+    for blk in cfg["blocks"]:
+        if id(blk["rowptr"]) not in seen:
+            seen[id(blk["rowptr"])] = dict(rowptr=torch.from_numpy(blk["rowptr"]).to(dev),
+                                           colidx=torch.from_numpy(blk["colidx"]).to(dev),
+                                           n_dst=blk["n_dst"], n_src=blk["n_src"])
+        blocks.append(seen[id(blk["rowptr"])])
+    sage = cfg["model"] == "sage"
+    W = [up(w, w.shape[1]) for w in cfg["W"]]
+    Wr = [up(w, w.shape[1]) for w in cfg["W_root"]] if sage else None
+    bs = [torch.from_numpy(b).to(dev) for b in cfg["b"]]
+    X, G = up(cfg["X"]), up(cfg["G"])
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    model = LayerStack(blocks, cfg["dims"], dt, cfg["reduce"], W, bs, Wr)
+    torch.cuda.synchronize()
+    plan_ms = (time.perf_counter() - t0) * 1e3      # plan build (+ buffer allocation), once per graph
+
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        model.step(X, G, args.fwd_order, args.bwd_order)
+    torch.cuda.synchronize()
+    B.gt_trace_reset()
+    B.gt_trace_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        model.step(X, G, args.fwd_order, args.bwd_order)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    B.gt_trace_enable(False)
+    recs = B.gt_trace_records()
+    B.gt_trace_reset()
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    L = len(cfg["W"])
+    E_l = [b["colidx"].numel() for b in blocks]
+    nominal_ef = sum(E_l[l] * cfg["dims"][l] * (2 if l > 0 else 1) for l in range(L))
+    executed_ef = sum(r[3] * r[1] for r in recs if r[0] in (0, 1)) / args.steps
+    value = nominal_ef / (ms_per_step * 1e-3)
+
+    # per-kernel view of the timed region (HIP events on the launch stream, recorded by the library)
+    groups = {}
+    for kind, width, rows, work, ms in recs:
+        key = (("agg_fwd", "agg_bwd", "combine")[kind], width, rows, work)
+        g = groups.setdefault(key, [0, 0.0])
+        g[0] += 1
+        g[1] += ms
+    kernels = [dict(kernel=k[0], width=k[1], rows=k[2], work=k[3], launches=v[0], avg_ms=v[1] / v[0],
+                    share=v[1] / (ms_per_step * args.steps)) for k, v in sorted(groups.items(), key=lambda kv: -kv[1][1])]
+    # dominant kernel: the aggregation gather kernel instance (same width => same template
+    # instance and kernel name) with the largest total time
+    by_width = {}
+    for kind, width, rows, work, ms in recs:
+        if kind in (0, 1):
+            w = by_width.setdefault(width, dict(n=0, ms=0.0, bytes=0.0))
+            w["n"] += 1
+            w["ms"] += ms
+            w["bytes"] += agg_algorithmic_bytes(work, rows, width, s, cfg["reduce"], kind == 1, False)
+    roofline = None
+    if by_width:
+        wdom, d = max(by_width.items(), key=lambda kv: kv[1]["ms"])
+        avg_ms = d["ms"] / d["n"]
+        achieved = d["bytes"] / d["n"] / (avg_ms * 1e-3) / 1e9
+        traffic = None
+        # byte counters cannot be read from inside the run: the figure measured with rocprofv3 --pmc
+        # for this workload and kernel width is kept beside the other profile summaries
+        tpath = os.path.join(ROOT, "profiles", "k_aggregate_%s_traffic.json" % args.config)
+        if os.path.exists(tpath):
+            tj = json.load(open(tpath))
+            if ("width %d)" % wdom) in tj.get("kernel", ""):
+                traffic = tj.get("hbm_bytes_per_launch")
+        roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
+                        traffic=traffic, kernel="k_aggregate (gather-reduce), width %d" % wdom,
+                        avg_launch_ms=avg_ms, launches=d["n"], algorithmic_bytes_per_launch=d["bytes"] / d["n"])
+
+    out = dict(metric="GNN layer fwd+bwd edge*features/s", value=value, unit="edge*feature/s", n_gpus=1,
+               steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak",
+               vs_baseline=None, dtype="f32" if dt == "f32" else "bf16", data="synthetic",
+               config=dict(workload=cfg["name"], n_nodes=[b["n_src"] for b in blocks][0], n_edges=E_l[0],
+                           dims=cfg["dims"], model=None, reduce=cfg["reduce"], layers=L,
+                           orders_fwd=model.used_fwd, orders_bwd=model.used_bwd,
+                           nominal_edge_features_per_step=nominal_ef, executed_edge_features_per_step=executed_ef,
+                           plan_ms=plan_ms, input_generation_s=gen_s),
+               roofline=roofline, kernels=kernels[:8])
+    del out["config"]["model"]
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, nominal_ef)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -224,6 +224,21 @@ gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_order fwd_u
 gt_status gt_calibrate_ws_size(size_t *ws_bytes /* host */);
 gt_status gt_calibrate(void *ws, size_t ws_bytes, gt_cost_coeffs *fitted /* host, may be NULL */, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Optional per-kernel timing (the paper reports GPU kernel time measured with a profiler; this
+ * gives the same quantity from inside a timed region).  While enabled, every aggregation
+ * gather kernel and every combination kernel launched by this library is bracketed by two HIP
+ * events on its own stream.  Host-side state, not thread-safe; off by default.
+ *   kind: 0 aggregation (given CSR), 1 aggregation (transposed), 2 combination
+ *   width: feature width F (aggregation) or N (combination); rows: output rows;
+ *   work: edges gathered (aggregation) or M*N*K (combination); ms: kernel duration.
+ * gt_trace_get synchronises on the record's end event.
+ * ------------------------------------------------------------------------------------------ */
+gt_status gt_trace_enable(int on);
+gt_status gt_trace_reset(void);
+gt_status gt_trace_count(int64_t *n /* host */);
+gt_status gt_trace_get(int64_t i, int *kind, int64_t *width, int64_t *rows, int64_t *work, double *ms);
+
 const char *gt_status_string(gt_status s);
 const char *gt_last_error(void);
 const char *gt_version(void);

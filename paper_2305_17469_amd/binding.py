@@ -50,7 +50,8 @@ class GtError(RuntimeError):
 EXPORTS = ["gt_graph_plan_size", "gt_graph_create", "gt_graph_destroy", "gt_graph_outputs", "gt_graph_info",
            "gt_graph_validate", "gt_aggregate_ws_size", "gt_aggregate_fwd", "gt_aggregate_bwd", "gt_combine_ws_size",
            "gt_combine", "gt_cost_get", "gt_cost_set", "gt_cost_benefits", "gt_layer_decide", "gt_layer_ws_size",
-           "gt_layer_fwd", "gt_layer_bwd", "gt_calibrate_ws_size", "gt_calibrate", "gt_status_string",
+           "gt_layer_fwd", "gt_layer_bwd", "gt_calibrate_ws_size", "gt_calibrate", "gt_trace_enable", "gt_trace_reset",
+           "gt_trace_count", "gt_trace_get", "gt_status_string",
            "gt_last_error", "gt_version"]
 
 for _n in EXPORTS:
@@ -83,6 +84,11 @@ lib.gt_layer_fwd.argtypes = [c_void_p, POINTER(gt_layer_desc), c_int, c_void_p, 
 lib.gt_layer_bwd.argtypes = [c_void_p, POINTER(gt_layer_desc), c_int, c_int, c_void_p, c_int64, c_void_p, c_int64,
                              c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_int64, c_void_p,
                              c_void_p, c_void_p, POINTER(c_int), c_void_p]
+lib.gt_trace_enable.argtypes = [c_int]
+lib.gt_trace_reset.argtypes = []
+lib.gt_trace_count.argtypes = [POINTER(c_int64)]
+lib.gt_trace_get.argtypes = [c_int64, POINTER(c_int), POINTER(c_int64), POINTER(c_int64), POINTER(c_int64),
+                             POINTER(c_double)]
 lib.gt_calibrate_ws_size.argtypes = [POINTER(c_size_t)]
 lib.gt_calibrate.argtypes = [c_void_p, c_size_t, POINTER(gt_cost_coeffs), c_void_p]
 
@@ -298,6 +304,26 @@ def gt_calibrate(device="cuda"):
     c = gt_cost_coeffs()
     _check(lib.gt_calibrate(_ptr(ws), ws.numel(), byref(c), _stream()))
     return c
+
+
+def gt_trace_enable(on):
+    _check(lib.gt_trace_enable(int(on)))
+
+
+def gt_trace_reset():
+    _check(lib.gt_trace_reset())
+
+
+def gt_trace_records():
+    """[(kind, width, rows, work, ms)] of every kernel launch recorded since the last reset."""
+    n = c_int64()
+    _check(lib.gt_trace_count(byref(n)))
+    out = []
+    for i in range(n.value):
+        k, w, r, wk, ms = c_int(), c_int64(), c_int64(), c_int64(), c_double()
+        _check(lib.gt_trace_get(i, byref(k), byref(w), byref(r), byref(wk), byref(ms)))
+        out.append((k.value, w.value, r.value, wk.value, ms.value))
+    return out
 
 
 def gt_version():

@@ -15,6 +15,7 @@
 // aggregation is an aggregation whose outputs are the source vertices (paper, "Training for
 // GNNs").
 #include "gt_internal.h"
+#include "gt_trace.h"
 
 namespace {
 
@@ -38,6 +39,8 @@ struct AggArgs {
     int64_t ldp;
     const gt_split *splits;
     int64_t n_splits;
+    int trace_kind;          // host-side bookkeeping of the optional kernel timing
+    int64_t n_rows, n_edges;
 };
 
 typedef uint16_t bf16_t;
@@ -254,7 +257,9 @@ gt_status launch(const AggArgs &a, hipStream_t st) {
     const unsigned gy = (unsigned)((a.F + tile - 1) / tile);
     if (a.n_items > 0) {
         const int64_t gx = (a.n_items + 4 * NG - 1) / (4 * NG);
+        const int tr = gt_trace_open(a.trace_kind, a.F, a.n_rows, a.n_edges, st);
         k_aggregate<T, V, G, NP, U><<<dim3((unsigned)gx, gy), 256, 0, st>>>(a);
+        gt_trace_close(tr, st);
         GT_LAUNCH_CHECK("k_aggregate");
     }
     if (a.n_splits > 0) {
@@ -334,6 +339,8 @@ gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce,
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy; a.F = F;
     a.partials = static_cast<float *>(ws); a.ldp = (F + 7) / 8 * 8;
     a.splits = sc.splits; a.n_splits = sc.n_splits;
+    a.trace_kind = transposed ? GT_TRACE_AGG_BWD : GT_TRACE_AGG_FWD;
+    a.n_rows = n_out; a.n_edges = g->n_edges;
 
     if (in_dtype == GT_F32) {
         const bool vec = aligned16(X) && aligned16(Y) && (ldx % 4 == 0) && (ldy % 4 == 0);

@@ -10,6 +10,7 @@
 // workgroups and summed in a fixed order, so results are reproducible.
 #include "gt_internal.h"
 #include "gt_combine.h"
+#include "gt_trace.h"
 
 namespace {
 
@@ -254,7 +255,16 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(const float *P, int split
     if (idx >= M * N) return;
     const int64_t row = idx / N, col = idx % N;
     float v = 0.0f;
-    for (int z = 0; z < splits; ++z) v += P[(int64_t)z * M * N + idx];
+    const int64_t stride = M * N;
+    int z = 0;
+    for (; z + 8 <= splits; z += 8) {   // eight independent loads in flight, added in z order
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = P[(int64_t)(z + u) * stride + idx];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v += t[u];
+    }
+    for (; z < splits; ++z) v += P[(int64_t)z * stride + idx];
     if (rowscale) v *= rowscale[row];
     if (Cin) v += c_bf16 ? bf16_to_f32(static_cast<const bf16_t *>(Cin)[row * ldcin + col])
                          : static_cast<const float *>(Cin)[row * ldcin + col];
@@ -276,7 +286,7 @@ SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
     if (K <= 0) { p.k_per_split = KT; return p; }
     // the reduction is cut only for the weight-gradient shape: few output tiles, very long K
     if (!transA || tiles >= 256 || K < 64 * KT) return p;
-    int64_t want = (1024 + tiles - 1) / tiles;                // about four workgroups per CU
+    int64_t want = (512 + tiles - 1) / tiles;                 // about two workgroups per CU
     const int64_t max_by_len = K / (16 * KT);                 // at least 16 k-tiles per split
     if (want > max_by_len) want = max_by_len;
     if (want < 1) want = 1;
@@ -343,8 +353,10 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     g.bias = bias; g.rowscale = rowscale; g.relu = (act == GT_ACT_RELU); g.c_bf16 = (c_dtype == GT_BF16);
     g.Cin = Cin; g.ldcin = ldcin;
     if (p.splits > 1) { g.C = ws; g.ldc = N; } else { g.C = C; g.ldc = ldc; }
+    const int tr = gt_trace_open(GT_TRACE_COMBINE, N, M, M * N * K, st);
     gt_status s = (dtype == GT_F32) ? launch_gemm_t<float>(g, transA, transB, p.splits, st)
                                     : launch_gemm_t<bf16_t>(g, transA, transB, p.splits, st);
+    gt_trace_close(tr, st);
     if (s != GT_OK) return s;
     if (p.splits > 1) {
         const int64_t n = M * N;

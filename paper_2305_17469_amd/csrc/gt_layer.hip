@@ -48,36 +48,63 @@ template <typename T> __device__ inline void stf(T *p, float v);
 template <> __device__ inline void stf<float>(float *p, float v) { *p = v; }
 template <> __device__ inline void stf<bf16_t>(bf16_t *p, float v) { *p = (bf16_t)f32_to_bf16(v); }
 
-constexpr int CS_ROWS = 256;   // rows per workgroup of the column-sum kernels
+constexpr int CS_ROWS = 128;   // rows per workgroup of the column-sum kernels
 
 // dZ = dY * [Y > 0] (or dY when Y is null) and per-workgroup column sums of dZ.
-// One workgroup covers CS_ROWS rows; thread t owns columns t, t+256, ...; sums run down the rows
-// in order, so the result does not depend on scheduling.
+// One workgroup covers CS_ROWS rows.  Its 256 threads form cw column lanes x 256/cw row lanes
+// (cw = columns padded to a power of two, at most 256); a thread sums every (256/cw)-th row of
+// its column, the row lanes are then added in lane order through LDS.  Every sum has a fixed
+// order, so the result does not depend on scheduling.
 template <typename T>
 __global__ void __launch_bounds__(256) k_mask_colsum(const T *dY, int64_t lddy, const T *Y, int64_t ldy, T *dZ,
-                                                     int64_t lddz, int64_t rows, int64_t cols, float *partial) {
+                                                     int64_t lddz, int64_t rows, int64_t cols, int cw, float *partial) {
+    __shared__ float red[256];
+    const int rl_count = 256 / cw;
+    const int cl = threadIdx.x % cw, rl = threadIdx.x / cw;
     const int64_t r0 = (int64_t)blockIdx.x * CS_ROWS;
     const int64_t r1 = r0 + CS_ROWS < rows ? r0 + CS_ROWS : rows;
-    for (int64_t c = threadIdx.x; c < cols; c += 256) {
+    for (int64_t c0 = 0; c0 < cols; c0 += cw) {
+        const int64_t c = c0 + cl;
         float s = 0.0f;
-        for (int64_t r = r0; r < r1; ++r) {
-            float g = ldf<T>(dY + r * lddy + c);
-            if (Y) {
-                g = ldf<T>(Y + r * ldy + c) > 0.0f ? g : 0.0f;
-                stf<T>(dZ + r * lddz + c, g);
+        if (c < cols) {
+#pragma unroll 4
+            for (int64_t r = r0 + rl; r < r1; r += rl_count) {
+                float g = ldf<T>(dY + r * lddy + c);
+                if (Y) {
+                    g = ldf<T>(Y + r * ldy + c) > 0.0f ? g : 0.0f;
+                    stf<T>(dZ + r * lddz + c, g);
+                }
+                s += g;
             }
-            s += g;
         }
-        if (partial) partial[(int64_t)blockIdx.x * cols + c] = s;
+        if (partial) {
+            red[threadIdx.x] = s;
+            __syncthreads();
+            if (rl == 0 && c < cols) {
+                float t = 0.0f;
+                for (int k = 0; k < rl_count; ++k) t += red[k * cw + cl];
+                partial[(int64_t)blockIdx.x * cols + c] = t;
+            }
+            __syncthreads();
+        }
     }
 }
 
+// out[c] = sum over the nblk partial rows, 16 columns per workgroup, 16 row lanes per column
 __global__ void __launch_bounds__(256) k_colsum_final(const float *partial, int64_t nblk, int64_t cols, float *out) {
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (c >= cols) return;
+    __shared__ float red[256];
+    const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
+    const int64_t c = (int64_t)blockIdx.x * 16 + cl;
     float s = 0.0f;
-    for (int64_t b = 0; b < nblk; ++b) s += partial[b * cols + c];
-    out[c] = s;
+    if (c < cols)
+        for (int64_t b = rl; b < nblk; b += 16) s += partial[b * cols + c];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (rl == 0 && c < cols) {
+        float t = 0.0f;
+        for (int k = 0; k < 16; ++k) t += red[k * 16 + cl];
+        out[c] = t;
+    }
 }
 
 int64_t pad_ld(int64_t F, gt_dtype t) {
@@ -182,17 +209,19 @@ gt_status mask_colsum(const void *dY, int64_t lddy, const void *Y, int64_t ldy, 
                       int64_t cols, float *partial, float *db, hipStream_t st) {
     if (rows <= 0) {
         if (db) {   // empty sum: zeros, written by the same final kernel (no memset node)
-            k_colsum_final<<<(unsigned)((cols + 255) / 256), 256, 0, st>>>(partial, 0, cols, db);
+            k_colsum_final<<<(unsigned)((cols + 15) / 16), 256, 0, st>>>(partial, 0, cols, db);
             GT_LAUNCH_CHECK("k_colsum_final");
         }
         return GT_OK;
     }
     const int64_t nblk = (rows + CS_ROWS - 1) / CS_ROWS;
+    int cw = 16;
+    while (cw < 256 && cw < cols) cw <<= 1;
     k_mask_colsum<T><<<(unsigned)nblk, 256, 0, st>>>(static_cast<const T *>(dY), lddy, static_cast<const T *>(Y), ldy,
-                                                     static_cast<T *>(dZ), lddz, rows, cols, db ? partial : nullptr);
+                                                     static_cast<T *>(dZ), lddz, rows, cols, cw, db ? partial : nullptr);
     GT_LAUNCH_CHECK("k_mask_colsum");
     if (db) {
-        k_colsum_final<<<(unsigned)((cols + 255) / 256), 256, 0, st>>>(partial, nblk, cols, db);
+        k_colsum_final<<<(unsigned)((cols + 15) / 16), 256, 0, st>>>(partial, nblk, cols, db);
         GT_LAUNCH_CHECK("k_colsum_final");
     }
     return GT_OK;

@@ -1,0 +1,84 @@
+"""A multi-layer GNN driven through gt_layer_fwd / gt_layer_bwd with every buffer allocated once.
+
+Marshalling only: which kernels run, and in which order, is decided inside the library
+(gt_layer_decide); this class keeps the device tensors alive and passes pointers.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+def _pad(F, dtype):
+    v = 8 if dtype == "bf16" else 4
+    return (F + v - 1) // v * v
+
+
+class LayerStack:
+    """`blocks`: per-layer dict(rowptr, colidx, n_dst, n_src) of device int32 tensors (a full
+    graph repeats the same dict).  Weights are device tensors of the layer dtype, biases fp32.
+    Hidden layers use ReLU, the last layer none; the first layer produces no input gradient."""
+
+    def __init__(self, blocks, dims, dtype, reduce, W, b, W_root=None, pad=True):
+        self.dtype, self.reduce, self.dims = dtype, reduce, list(dims)
+        self.tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.L = len(dims) - 1
+        self.W, self.b = W, b
+        self.W_root = W_root if W_root is not None else [None] * self.L
+        self.graphs, seen = [], {}
+        for blk in blocks:
+            key = blk["rowptr"].data_ptr()
+            if key not in seen:
+                seen[key] = B.Graph(blk["rowptr"], blk["colidx"], blk["n_src"], blk.get("edge_weight"))
+            self.graphs.append(seen[key])
+        dev = self.graphs[0].device
+        ld = (lambda F: _pad(F, dtype)) if pad else (lambda F: F)
+        self.descs, self.bufs, self.H, self.dH = [], [], [], []
+        self.dW, self.dW_root, self.db = [], [], []
+        for l in range(self.L):
+            g = self.graphs[l]
+            d = B.make_desc(reduce, dtype, l < self.L - 1, dims[l], dims[l + 1], has_root=self.W_root[l] is not None,
+                            need_dx=l > 0)
+            self.descs.append(d)
+            self.bufs.append(B.LayerBuffers(g, d))
+            self.H.append(torch.zeros((g.n_dst, ld(dims[l + 1])), dtype=self.tdt, device=dev)[:, :dims[l + 1]])
+            self.dH.append(torch.zeros((g.n_src, ld(dims[l])), dtype=self.tdt, device=dev)[:, :dims[l]] if l > 0 else None)
+            self.dW.append(torch.zeros((dims[l], dims[l + 1]), dtype=torch.float32, device=dev))
+            self.dW_root.append(torch.zeros_like(self.dW[-1]) if self.W_root[l] is not None else None)
+            self.db.append(torch.zeros((dims[l + 1],), dtype=torch.float32, device=dev))
+        self.used_fwd = [None] * self.L
+        self.used_bwd = [None] * self.L
+
+    def forward(self, X, order="auto"):
+        orders = order if isinstance(order, (list, tuple)) else [order] * self.L
+        self.X = X
+        h = X
+        for l in range(self.L):
+            _, self.used_fwd[l] = B.gt_layer_fwd(self.graphs[l], self.descs[l], h, self.W[l], self.b[l], self.bufs[l],
+                                                 orders[l], self.W_root[l], out=self.H[l])
+            h = self.H[l]
+        return h
+
+    def backward(self, dOut, order="auto"):
+        orders = order if isinstance(order, (list, tuple)) else [order] * self.L
+        dh = dOut
+        stream = B._stream()
+        for l in reversed(range(self.L)):
+            g, d = self.graphs[l], self.descs[l]
+            x = self.X if l == 0 else self.H[l - 1]
+            dX = self.dH[l]
+            used = B.c_int()
+            B._check(B.lib.gt_layer_bwd(g.handle, B.byref(d), B.ORDER[self.used_fwd[l]], B.ORDER[orders[l]],
+                                        B._ptr(dh), dh.stride(0), B._ptr(x), x.stride(0), B._ptr(self.W[l]),
+                                        B._ptr(self.W_root[l]), B._ptr(self.H[l]), self.H[l].stride(0),
+                                        B._ptr(self.bufs[l].saved), B._ptr(self.bufs[l].scratch),
+                                        B._ptr(dX), dX.stride(0) if dX is not None else 0, B._ptr(self.dW[l]),
+                                        B._ptr(self.dW_root[l]), B._ptr(self.db[l]), B.byref(used), stream))
+            self.used_bwd[l] = B.ORDER_NAME[used.value]
+            dh = dX
+        return self.dW, self.db
+
+    def step(self, X, dOut, fwd_order="auto", bwd_order="auto"):
+        self.forward(X, fwd_order)
+        self.backward(dOut, bwd_order)
