@@ -1,0 +1,145 @@
+"""Parity at the full sizes of the benchmark workloads, in the launch configuration bench.py times
+(LayerStack, padded strides, AUTO placement).
+
+The oracle cannot run whole models at these sizes in seconds, so every layer is checked on sampled
+outputs the oracle computes one by one from that layer's actual inputs (the GPU's own previous
+activations / upstream gradients, which are exact fp32 or bf16 values):
+  forward   H[R]   = act(A[R,:] X W (+ X[R] W_root) + b)      R: random rows + the longest rows
+  backward  dX[Rs] = (A^T dZ)[Rs] W^T (+ dZ[Rs] W_root^T)      Rs: random sources + busiest sources
+            dW[ks] = (A X[:, ks])^T dZ                         ks: a few input columns
+            db     = column sums of dZ                         (all of it)
+with dZ = dY * [Y > 0] formed from the GPU's Y (the ReLU decision is taken in the kernel's
+precision).  Tolerance: max|gpu - ref| / max|ref| over the sample <= 1e-5 (fp32) / 2e-2 (bf16).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gt_inputs import configs, tensors
+from gpu_util import announce, down, max_rel_err, pad_to, tol_for
+
+pytestmark = pytest.mark.gpu
+
+
+def _up(a, dt, dev, ld=None):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    n, F = a.shape
+    ld = pad_to(F, dt) if ld is None else ld
+    host = torch.from_numpy(tensors.to_bf16_bits(a).view(np.int16)).view(torch.bfloat16) if dt == "bf16" \
+        else torch.from_numpy(a)
+    buf = torch.zeros((n, ld), dtype=host.dtype, device=dev)
+    buf[:, :F] = host.to(dev)
+    return buf[:, :F]
+
+
+def _f32(t):
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+def _sample(n, weights, k_rand, k_top, rng):
+    idx = set(rng.choice(n, size=min(k_rand, n), replace=False).tolist())
+    idx.update(np.argsort(weights)[-k_top:].tolist())
+    idx.update(np.argsort(weights)[:4].tolist())
+    return np.array(sorted(idx), dtype=np.int64)
+
+
+def run_and_check(cfg, n_rand=768, n_top=12, n_cols=6):
+    from paper_2305_17469_amd.stack import LayerStack
+    dev = torch.device("cuda:0")
+    dt = cfg["dtype"]
+    tol = tol_for(dt)
+    sage = cfg["model"] == "sage"
+    blocks, seen = [], {}
+    for blk in cfg["blocks"]:
+        if id(blk["rowptr"]) not in seen:
+            seen[id(blk["rowptr"])] = dict(rowptr=torch.from_numpy(blk["rowptr"]).to(dev),
+                                           colidx=torch.from_numpy(blk["colidx"]).to(dev),
+                                           n_dst=blk["n_dst"], n_src=blk["n_src"])
+        blocks.append(seen[id(blk["rowptr"])])
+    W = [_up(w, dt, dev, w.shape[1]) for w in cfg["W"]]
+    Wr = [_up(w, dt, dev, w.shape[1]) for w in cfg["W_root"]] if sage else None
+    bias = [np.random.default_rng(40 + i).standard_normal(b.size).astype(np.float32) * 0.1 for i, b in enumerate(cfg["b"])]
+    bs = [torch.from_numpy(b).to(dev) for b in bias]
+    X, G = _up(cfg["X"], dt, dev), _up(cfg["G"], dt, dev)
+    model = LayerStack(blocks, cfg["dims"], dt, cfg["reduce"], W, bs, Wr)
+    model.step(X, G)
+    model.step(X, G)          # second step into the same buffers, as in the benchmark loop
+    torch.cuda.synchronize()
+    L = model.L
+    rng = np.random.default_rng(123)
+    errs = {}
+    for l in range(L):
+        blk = cfg["blocks"][l]
+        rp, ci, ns, nd = blk["rowptr"], blk["colidx"], blk["n_src"], blk["n_dst"]
+        relu = l < L - 1
+        Xl = _f32(X if l == 0 else model.H[l - 1])
+        Yl = _f32(model.H[l])
+        dYl = _f32(G if l == L - 1 else model.dH[l + 1])
+        Wl = cfg["W"][l].astype(np.float64)
+        Wrl = cfg["W_root"][l].astype(np.float64) if sage else None
+        deg_in = np.diff(rp)
+        deg_out = np.bincount(ci, minlength=ns)
+        # ---- forward on sampled destinations
+        R = _sample(nd, deg_in, n_rand, n_top, rng)
+        M = oracle.aggregate_fwd(rp, ci, ns, Xl, cfg["reduce"], rows=R)
+        Z = oracle.combine(M, Wl)
+        if sage:
+            Z = Z + oracle.combine(Xl[R].astype(np.float64), Wrl)
+        Z = Z + bias[l].astype(np.float64)[None, :]
+        H = np.maximum(Z, 0.0) if relu else Z
+        if dt == "bf16":
+            H = oracle.round_bf16(H)
+        errs["H%d" % l] = max_rel_err(Yl[R].astype(np.float64), H)
+        # ---- backward
+        dZ = dYl * (Yl > 0) if relu else dYl
+        errs["db%d" % l] = max_rel_err(down(model.db[l]), dZ.astype(np.float64).sum(axis=0))
+        ks = np.sort(rng.choice(cfg["dims"][l], size=min(n_cols, cfg["dims"][l]), replace=False))
+        Mk = oracle.aggregate_fwd(rp, ci, ns, np.ascontiguousarray(Xl[:, ks]), cfg["reduce"])
+        dWk = oracle.combine(Mk, dZ.astype(np.float64), transA=True)
+        scale = float(np.abs(down(model.dW[l])).max())
+        errs["dW%d" % l] = float(np.abs(down(model.dW[l])[ks] - dWk).max() / scale)
+        if sage:
+            dWr = oracle.combine(Xl[:nd][:, ks].astype(np.float64), dZ.astype(np.float64), transA=True)
+            errs["dWr%d" % l] = float(np.abs(down(model.dW_root[l])[ks] - dWr).max() / np.abs(down(model.dW_root[l])).max())
+        if l > 0:
+            Rs = _sample(ns, deg_out, n_rand, n_top, rng)
+            S = oracle.aggregate_bwd(rp, ci, ns, dZ, cfg["reduce"], src_rows=Rs)
+            dX = oracle.combine(S, Wl, transB=True)
+            if sage:
+                inb = Rs < nd
+                dX[inb] += oracle.combine(dZ[Rs[inb]].astype(np.float64), Wrl, transB=True)
+            if dt == "bf16":
+                dX = oracle.round_bf16(dX)
+            errs["dX%d" % l] = max_rel_err(_f32(model.dH[l])[Rs].astype(np.float64), dX)
+    worst = max(errs.values())
+    assert worst <= tol, (cfg["name"], errs, model.used_fwd, model.used_bwd)
+    return errs, model
+
+
+def test_config2_full_size_benchmark_configuration():
+    announce("full size: config 2 (R-MAT 2^18, 602-128-41 fp32)")
+    errs, model = run_and_check(configs.reddit_like())
+    assert model.used_fwd == ["comb_first", "comb_first"]
+    print(errs)
+
+
+def test_config4_full_size_sage_minibatch():
+    announce("full size: config 4 (SAGE mini-batch, 1,024 seeds, fanout 25/10)")
+    errs, model = run_and_check(configs.sage_minibatch())
+    print(errs)
+
+
+@pytest.mark.parametrize("wide_to_narrow", [True, False])
+def test_config5_full_size_reorder_stress(wide_to_narrow):
+    announce("full size: config 5 (ER 2^20), wide_to_narrow =", wide_to_narrow)
+    for reduce in ("sum", "mean"):
+        errs, model = run_and_check(configs.reorder_stress(20, wide_to_narrow, reduce), n_rand=384, n_cols=4)
+        assert model.used_fwd == ["comb_first" if wide_to_narrow else "agg_first"]
+        print(reduce, errs)
+
+
+def test_config3_full_size_bf16_power_law():
+    announce("full size: config 3 (R-MAT 2^21, bf16 100-256-256-47)")
+    errs, model = run_and_check(configs.products_like(), n_rand=512, n_cols=4)
+    print(errs)
