@@ -117,6 +117,8 @@ def main():
     ap.add_argument("--fwd-order", default="auto")
     ap.add_argument("--bwd-order", default="auto")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--reorder-check", action="store_true",
+                    help="time every layer's fwd+bwd in both forced orders and compare with AUTO's choice")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -168,6 +170,35 @@ def main():
     torch.cuda.synchronize()
     plan_ms = (time.perf_counter() - t0) * 1e3      # plan build (+ buffer allocation), once per graph
 
+    if args.reorder_check:
+        def timed(fo, bo, reps=args.steps):
+            for _ in range(max(2, args.warmup)):
+                model.step(X, G, fo, bo)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                model.step(X, G, fo, bo)
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / reps
+        model.step(X, G)
+        auto_f, auto_b = list(model.used_fwd), list(model.used_bwd)
+        t_auto = timed("auto", "auto")
+        layers = []
+        for l in range(model.L):
+            row = dict(layer=l, in_dim=cfg["dims"][l], out_dim=cfg["dims"][l + 1], auto_fwd=auto_f[l], auto_bwd=auto_b[l])
+            for of in ("agg_first", "comb_first"):
+                for ob in ("agg_first", "comb_first"):
+                    fo, bo = list(auto_f), list(auto_b)
+                    fo[l], bo[l] = of, ob
+                    row["ms_%s_%s" % (of[:4], ob[:4])] = timed(fo, bo)
+            best = min((v, k) for k, v in row.items() if k.startswith("ms_"))
+            row["best"] = best[1]
+            row["ms_auto"] = row["ms_%s_%s" % (auto_f[l][:4], auto_b[l][:4])]
+            row["auto_within_5pct_of_best"] = bool(row["ms_auto"] <= 1.05 * best[0])
+            layers.append(row)
+        print(json.dumps(dict(metric="reorder_check", workload=cfg["name"], ms_per_step_auto=t_auto, layers=layers,
+                              all_ok=all(r["auto_within_5pct_of_best"] for r in layers))))
+        return
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)

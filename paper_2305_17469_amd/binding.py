@@ -147,7 +147,7 @@ class Graph:
 
     def __del__(self):
         h = getattr(self, "handle", None)
-        if h:
+        if h and lib is not None:       # `lib` is already gone at interpreter shutdown
             lib.gt_graph_destroy(h)
             self.handle = None
 

@@ -7,7 +7,7 @@
 // row is written once, so no atomics or locks are needed.  What differs for CDNA4 and for full
 // power-law graphs: a "group" is G = 4..64 lanes of a 64-wide wavefront, each lane moving
 // 16 bytes per gathered row, so narrow rows still issue full-width memory instructions; rows
-// longer than GT_SPLIT_MIN entries are cut into GT_CHUNK-entry work items whose fp32 partial rows
+// longer than 1.5 chunks (a chunk is 512 entries, fewer on small graphs) are cut into chunk-sized work items whose fp32 partial rows
 // are added by a second kernel in chunk order (deterministic, no floating-point atomics); work
 // items are ordered longest first so the groups of a wavefront see similar trip counts.
 //
@@ -24,10 +24,8 @@ struct AggArgs {
     int64_t n_items;
     const int32_t *rowptr;   // of the output rows (for the mean's divisor)
     const int32_t *nbr;
-    const float *wt;         // per-entry weight or null
-    const float *pre;        // per-neighbour scale or null
-    const float *post;       // per-output-row scale (post_mode 1) or null
-    int post_mode;           // 0 none, 1 multiply by post[row], 2 divide by the row's entry count
+    const float *coef;       // per-entry coefficient (edge weight x normalisation) or null (= 1)
+    int post_mode;           // 0 none, 2 divide by the row's entry count (mean, forward)
     const float *bias;       // per-column bias added after scaling, or null
     int relu;
     const void *X;
@@ -39,6 +37,7 @@ struct AggArgs {
     int64_t ldp;
     const gt_split *splits;
     int64_t n_splits;
+    int64_t table_bytes;     // host-side: size of the gathered table (picks the unroll)
     int trace_kind;          // host-side bookkeeping of the optional kernel timing
     int64_t n_rows, n_edges;
 };
@@ -52,6 +51,34 @@ __device__ inline uint32_t f32_to_bf16(float f) {   // round to nearest even; Na
     if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
     u += 0x7fffu + ((u >> 16) & 1u);
     return u >> 16;
+}
+
+// Raw (unconverted) V consecutive elements, as they travel from memory: 16 bytes when V > 1.
+template <typename T, int V> struct Raw;
+template <> struct Raw<float, 4> { typedef float4 type; };
+template <> struct Raw<float, 1> { typedef float type; };
+template <> struct Raw<bf16_t, 8> { typedef uint4 type; };
+template <> struct Raw<bf16_t, 1> { typedef bf16_t type; };
+
+template <typename T, int V>
+__device__ inline typename Raw<T, V>::type load_raw(const T *p) {
+    return *reinterpret_cast<const typename Raw<T, V>::type *>(p);
+}
+
+// acc += c * raw  (fp32 accumulation)
+__device__ inline void fma_raw(float (&acc)[4], float c, const float4 &v) {
+    acc[0] = fmaf(c, v.x, acc[0]); acc[1] = fmaf(c, v.y, acc[1]);
+    acc[2] = fmaf(c, v.z, acc[2]); acc[3] = fmaf(c, v.w, acc[3]);
+}
+__device__ inline void fma_raw(float (&acc)[1], float c, const float &v) { acc[0] = fmaf(c, v, acc[0]); }
+__device__ inline void fma_raw(float (&acc)[8], float c, const uint4 &v) {
+    acc[0] = fmaf(c, __uint_as_float(v.x << 16), acc[0]); acc[1] = fmaf(c, __uint_as_float(v.x & 0xffff0000u), acc[1]);
+    acc[2] = fmaf(c, __uint_as_float(v.y << 16), acc[2]); acc[3] = fmaf(c, __uint_as_float(v.y & 0xffff0000u), acc[3]);
+    acc[4] = fmaf(c, __uint_as_float(v.z << 16), acc[4]); acc[5] = fmaf(c, __uint_as_float(v.z & 0xffff0000u), acc[5]);
+    acc[6] = fmaf(c, __uint_as_float(v.w << 16), acc[6]); acc[7] = fmaf(c, __uint_as_float(v.w & 0xffff0000u), acc[7]);
+}
+__device__ inline void fma_raw(float (&acc)[1], float c, const bf16_t &v) {
+    acc[0] = fmaf(c, __uint_as_float((uint32_t)v << 16), acc[0]);
 }
 
 // V consecutive elements starting at p (p is 16-byte aligned when V > 1) -> fp32
@@ -111,12 +138,9 @@ __device__ inline void store_vec<bf16_t, 1>(bf16_t *p, const float (&v)[1], int 
 // scale, bias, activation and store of one finished output row segment
 template <typename T, int V, int G, int NP>
 __device__ inline void finish_row(const AggArgs &a, int row, int gl, int64_t col0, float (&acc)[NP][V]) {
-    float mul = 1.0f;
     bool zero = false;
     float div = 1.0f;
-    if (a.post_mode == 1) {
-        mul = a.post[row];
-    } else if (a.post_mode == 2) {
+    if (a.post_mode == 2) {
         const int d = a.rowptr[row + 1] - a.rowptr[row];
         zero = d <= 0;
         div = (float)(d > 0 ? d : 1);
@@ -131,7 +155,6 @@ __device__ inline void finish_row(const AggArgs &a, int row, int gl, int64_t col
 #pragma unroll
         for (int i = 0; i < V; ++i) {
             float x = acc[p][i];
-            if (a.post_mode == 1) x *= mul;
             if (a.post_mode == 2) x = zero ? 0.0f : x / div;
             if (a.bias && i < n) x += a.bias[col + i];
             if (a.relu) x = x > 0.0f ? x : 0.0f;
@@ -153,7 +176,13 @@ __global__ void __launch_bounds__(256) k_aggregate(const AggArgs a) {
     const int64_t item_id = ((int64_t)blockIdx.x * 4 + wave) * NG + grp;
     if (item_id >= a.n_items) return;   // whole groups leave together; no barriers are used below
     const int4 raw = reinterpret_cast<const int4 *>(a.items)[item_id];
-    const int row = raw.x, e0 = raw.y, e1 = raw.z, slot = raw.w;
+    int row = raw.x, e0 = raw.y, e1 = raw.z, slot = raw.w;
+    if constexpr (G == 64) {   // one item per wavefront: keep its bounds in scalar registers
+        row = __builtin_amdgcn_readfirstlane(row);
+        e0 = __builtin_amdgcn_readfirstlane(e0);
+        e1 = __builtin_amdgcn_readfirstlane(e1);
+        slot = __builtin_amdgcn_readfirstlane(slot);
+    }
     const int64_t col0 = (int64_t)blockIdx.y * (G * V * NP);
     const T *X = static_cast<const T *>(a.X);
 
@@ -163,45 +192,55 @@ __global__ void __launch_bounds__(256) k_aggregate(const AggArgs a) {
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[p][i] = 0.0f;
 
+    typedef typename Raw<T, V>::type raw_t;
+    // The group fetches G neighbour ids and coefficients with one coalesced load and walks them;
+    // the next G are requested before the current ones are used, so the id fetch of the next
+    // batch overlaps the row gathers of this one.
+    int idx_next = 0;
+    float c_next = 0.0f;
+    if (e0 + gl < e1) {
+        idx_next = a.nbr[e0 + gl];
+        c_next = a.coef ? a.coef[e0 + gl] : 1.0f;
+    }
     for (int base = e0; base < e1; base += G) {
-        // the group fetches G neighbour ids and coefficients at once, then walks them
-        const int e = base + gl;
-        int idx = 0;
-        float c = 0.0f;
-        if (e < e1) {
-            idx = a.nbr[e];
-            c = a.wt ? a.wt[e] : 1.0f;
-            if (a.pre) c *= a.pre[idx];
+        const int idx = idx_next;
+        const float c = c_next;
+        const int en = base + G + gl;
+        idx_next = 0;
+        c_next = 0.0f;
+        if (en < e1) {
+            idx_next = a.nbr[en];
+            c_next = a.coef ? a.coef[en] : 1.0f;
         }
         const int cnt = (e1 - base) < G ? (e1 - base) : G;
         for (int j = 0; j < cnt; j += U) {
-            float v[U][NP][V];
+            raw_t v[U][NP];
             float cj[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int jj = j + u;
-                const int src = __shfl(idx, jj & (G - 1), G);
-                cj[u] = __shfl(c, jj & (G - 1), G);
+                int src;
+                if constexpr (G == 64) {   // wave-uniform: scalar broadcast, scalar row base
+                    src = __builtin_amdgcn_readlane(idx, jj & 63);
+                    cj[u] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(c), jj & 63));
+                } else {
+                    src = __shfl(idx, jj & (G - 1), G);
+                    cj[u] = __shfl(c, jj & (G - 1), G);
+                }
                 const bool live = jj < cnt;
                 if (!live) cj[u] = 0.0f;
                 const T *xr = X + (int64_t)src * a.ldx;
 #pragma unroll
                 for (int p = 0; p < NP; ++p) {
                     const int64_t col = col0 + (int64_t)(p * G + gl) * V;
-                    if (live && col < a.F) {
-                        load_vec<T, V>(xr + col, v[u][p]);
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < V; ++i) v[u][p][i] = 0.0f;
-                    }
+                    v[u][p] = raw_t{};
+                    if (live && col < a.F) v[u][p] = load_raw<T, V>(xr + col);
                 }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int p = 0; p < NP; ++p)
-#pragma unroll
-                    for (int i = 0; i < V; ++i) acc[p][i] = fmaf(cj[u], v[u][p][i], acc[p][i]);
+                for (int p = 0; p < NP; ++p) fma_raw(acc[p], cj[u], v[u][p]);
         }
     }
 
@@ -270,17 +309,28 @@ gt_status launch(const AggArgs &a, hipStream_t st) {
     return GT_OK;
 }
 
+// Row loads kept in flight per lane.  Measured on MI355X: two are enough (and best) once the
+// gathered table lives in HBM or rows are 512 bytes or more; narrow rows of a table that fits the
+// last-level cache gain from eight.
+template <typename T, int V, int G, int NP>
+gt_status launch_u(const AggArgs &a, hipStream_t st) {
+    if constexpr (NP == 1 && G <= 16) {
+        if (a.table_bytes <= ((int64_t)96 << 20)) return launch<T, V, G, NP, 8>(a, st);
+    }
+    return launch<T, V, G, NP, 2>(a, st);
+}
+
 template <typename T, int V>
 gt_status dispatch(const AggArgs &a, hipStream_t st) {
     const int64_t nvec = (a.F + V - 1) / V;   // lanes needed to cover one row
-    if (nvec <= 4) return launch<T, V, 4, 1, 4>(a, st);
-    if (nvec <= 8) return launch<T, V, 8, 1, 4>(a, st);
-    if (nvec <= 16) return launch<T, V, 16, 1, 4>(a, st);
-    if (nvec <= 32) return launch<T, V, 32, 1, 4>(a, st);
-    if (nvec <= 64) return launch<T, V, 64, 1, 4>(a, st);
-    if (nvec <= 128) return launch<T, V, 64, 2, 2>(a, st);
-    if (nvec <= 192) return launch<T, V, 64, 3, 2>(a, st);
-    return launch<T, V, 64, 4, 2>(a, st);   // wider rows take several column tiles (grid.y)
+    if (nvec <= 4) return launch_u<T, V, 4, 1>(a, st);
+    if (nvec <= 8) return launch_u<T, V, 8, 1>(a, st);
+    if (nvec <= 16) return launch_u<T, V, 16, 1>(a, st);
+    if (nvec <= 32) return launch_u<T, V, 32, 1>(a, st);
+    if (nvec <= 64) return launch_u<T, V, 64, 1>(a, st);
+    if (nvec <= 128) return launch_u<T, V, 64, 2>(a, st);
+    if (nvec <= 192) return launch_u<T, V, 64, 3>(a, st);
+    return launch_u<T, V, 64, 4>(a, st);   // wider rows take several column tiles (grid.y)
 }
 
 bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
@@ -327,18 +377,19 @@ gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce,
 
     AggArgs a{};
     a.items = sc.items; a.n_items = sc.n_items;
-    a.rowptr = sc.rowptr; a.nbr = sc.nbr; a.wt = sc.wt;
-    a.pre = nullptr; a.post = nullptr; a.post_mode = 0;
+    a.rowptr = sc.rowptr; a.nbr = sc.nbr;
+    a.coef = sc.wt; a.post_mode = 0;
     if (reduce == GT_MEAN) {
-        if (!transposed) a.post_mode = 2;   // divide by the destination's in-degree
-        else a.pre = g->rdeg;               // each term carries 1/indeg of its destination
+        if (!transposed) a.post_mode = 2;   // divide by the destination's in-degree (exact for ones)
+        else a.coef = sc.coef_mean;         // w_e / indeg(dst), stored per transposed entry
     } else if (reduce == GT_SYMNORM) {
-        a.pre = g->dinv; a.post = g->dinv; a.post_mode = 1;
+        a.coef = sc.coef_sym;               // w_e / sqrt(d(u) d(v)), stored per entry
     }
     a.bias = bias; a.relu = (act == GT_ACT_RELU);
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy; a.F = F;
     a.partials = static_cast<float *>(ws); a.ldp = (F + 7) / 8 * 8;
     a.splits = sc.splits; a.n_splits = sc.n_splits;
+    a.table_bytes = n_in * ldx * (int64_t)es;
     a.trace_kind = transposed ? GT_TRACE_AGG_BWD : GT_TRACE_AGG_FWD;
     a.n_rows = n_out; a.n_edges = g->n_edges;
 

@@ -285,9 +285,9 @@ SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
     SplitPlan p{1, (K + KT - 1) / KT * KT};
     if (K <= 0) { p.k_per_split = KT; return p; }
     // the reduction is cut only for the weight-gradient shape: few output tiles, very long K
-    if (!transA || tiles >= 256 || K < 64 * KT) return p;
+    if (!transA || tiles >= 256 || K < 8 * KT) return p;
     int64_t want = (512 + tiles - 1) / tiles;                 // about two workgroups per CU
-    const int64_t max_by_len = K / (16 * KT);                 // at least 16 k-tiles per split
+    const int64_t max_by_len = K / (4 * KT);                  // at least 4 k-tiles per split
     if (want > max_by_len) want = max_by_len;
     if (want < 1) want = 1;
     int64_t kps = ((K + want - 1) / want + KT - 1) / KT * KT;

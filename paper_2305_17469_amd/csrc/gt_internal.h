@@ -6,12 +6,20 @@
 
 #include "gt.h"
 
-// Work decomposition of one aggregation direction.  A row with more than GT_SPLIT_MIN entries is
-// cut into chunks of GT_CHUNK entries; every chunk becomes a work item that writes an fp32
+// Work decomposition of one aggregation direction.  A row with more than 1.5 x chunk entries is
+// cut into chunks of `chunk` entries; every chunk becomes a work item that writes an fp32
 // partial row, and a second kernel adds a row's partials in chunk order.  All other rows are
 // one item each and are written directly.  Items are ordered longest first.
-#define GT_CHUNK 512
-#define GT_SPLIT_MIN 768
+// The chunk is 512 entries on large graphs and shrinks (down to 64) on small ones, so that a
+// small graph with a few long rows still yields enough items to occupy the GPU.
+#define GT_CHUNK_MAX 512
+#define GT_CHUNK_MIN 64
+static inline int gt_chunk_for(int64_t n_edges) {
+    int c = GT_CHUNK_MAX;
+    while (c > GT_CHUNK_MIN && n_edges / c < 4096) c >>= 1;
+    return c;
+}
+static inline int gt_split_min(int chunk) { return chunk + chunk / 2; }
 
 struct gt_item {   // 16 bytes, loaded as one int4
     int32_t row;   // output row
@@ -31,6 +39,8 @@ struct gt_sched {
     const int32_t *rowptr = nullptr;  // [n_rows + 1]
     const int32_t *nbr = nullptr;     // [E] neighbour (gathered row) of every entry
     const float *wt = nullptr;        // [E] per-entry weight or null
+    const float *coef_sym = nullptr;  // [E] w_e / sqrt(d(u) d(v)) (square graphs), in this direction's entry order
+    const float *coef_mean = nullptr; // [E] w_e / indeg(dst) (transposed direction only)
     const gt_item *items = nullptr;
     const gt_split *splits = nullptr;
     int64_t n_rows = 0, n_items = 0, n_splits = 0, n_partials = 0;
@@ -38,6 +48,7 @@ struct gt_sched {
 
 struct gt_graph {
     int64_t n_dst = 0, n_src = 0, n_edges = 0;
+    int chunk = GT_CHUNK_MAX;   // entries per work item of a split row
     const int32_t *rowptr = nullptr, *colidx = nullptr;
     const float *ew = nullptr;
     // plan (device, inside the caller's workspace)
@@ -45,6 +56,7 @@ struct gt_graph {
     float *ew_t = nullptr;
     float *dinv = nullptr;  // in_deg^-1/2 (square graphs only), 0 where the degree is 0
     float *rdeg = nullptr;  // 1 / in_deg, 0 where the degree is 0
+    float *coef_sym_f = nullptr, *coef_sym_b = nullptr, *coef_mean_b = nullptr;   // per-entry coefficients
     unsigned long long *vcount = nullptr;  // device counter of gt_graph_validate
     gt_sched fwd, bwd;
 };

@@ -267,8 +267,14 @@ __global__ void k_boundaries(const uint32_t *skeys, int64_t E, int64_t n_src, in
     for (int64_t u = lo + 1; u <= hi; ++u) rowptr_t[u] = (int32_t)k;
 }
 
+// Per transposed entry k (position e = perm[k] in the given CSR): its destination, its weight, and
+// the per-entry coefficients of the normalised reduce modes, written in both entry orders:
+//   symmetric norm  w_e / sqrt(d(src) d(dst))   (coef_sym_f[e], coef_sym_b[k]; square graphs)
+//   mean, backward  w_e / indeg(dst)            (coef_mean_b[k])
 __global__ void k_transposed_entries(const int32_t *rowptr, int64_t n_dst, const int32_t *perm, int64_t E,
-                                     const float *ew, int32_t *colidx_t, float *ew_t) {
+                                     const int32_t *colidx, const float *ew, const float *dinv, const float *rdeg,
+                                     int32_t *colidx_t, float *ew_t, float *coef_sym_f, float *coef_sym_b,
+                                     float *coef_mean_b) {
     const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= E) return;
     const int32_t e = perm[k];
@@ -279,17 +285,24 @@ __global__ void k_transposed_entries(const int32_t *rowptr, int64_t n_dst, const
         if (rowptr[mid] <= e) lo = mid; else hi = mid;
     }
     colidx_t[k] = (int32_t)lo;
-    if (ew_t) ew_t[k] = ew[e];
+    const float w = ew ? ew[e] : 1.0f;
+    if (ew_t) ew_t[k] = w;
+    if (dinv) {
+        const float c = (w * dinv[colidx[e]]) * dinv[lo];
+        coef_sym_f[e] = c;
+        coef_sym_b[k] = c;
+    }
+    coef_mean_b[k] = w * rdeg[lo];
 }
 
 // per-row item / partial / split counts
-__global__ void k_item_counts(const int32_t *rowptr, int64_t n_rows, int32_t *c_items, int32_t *c_parts,
+__global__ void k_item_counts(const int32_t *rowptr, int64_t n_rows, int chunk, int32_t *c_items, int32_t *c_parts,
                               int32_t *c_splits) {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= n_rows) return;
     const int32_t d = rowptr[r + 1] - rowptr[r];
-    const bool split = d > GT_SPLIT_MIN;
-    const int32_t chunks = (d + GT_CHUNK - 1) / GT_CHUNK;
+    const bool split = d > chunk + chunk / 2;
+    const int32_t chunks = (d + chunk - 1) / chunk;
     c_items[r] = split ? chunks : 1;
     c_parts[r] = split ? chunks : 0;
     c_splits[r] = split ? 1 : 0;
@@ -307,14 +320,14 @@ __device__ inline uint32_t length_key(int32_t len) {
     return 255u - k;
 }
 
-__global__ void k_fill_items(const int32_t *rowptr, int64_t n_rows, const int32_t *o_items, const int32_t *o_parts,
+__global__ void k_fill_items(const int32_t *rowptr, int64_t n_rows, int chunk, const int32_t *o_items, const int32_t *o_parts,
                              const int32_t *o_splits, gt_item *items, uint32_t *keys, gt_split *splits) {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= n_rows) return;
     const int32_t b = rowptr[r], e = rowptr[r + 1], d = e - b;
     int32_t it = o_items[r];
-    if (d > GT_SPLIT_MIN) {
-        const int32_t chunks = (d + GT_CHUNK - 1) / GT_CHUNK;
+    if (d > chunk + chunk / 2) {
+        const int32_t chunks = (d + chunk - 1) / chunk;
         const int32_t p0 = o_parts[r];
         gt_split s;
         s.row = (int32_t)r; s.first = p0; s.count = chunks; s.pad = 0;
@@ -322,8 +335,8 @@ __global__ void k_fill_items(const int32_t *rowptr, int64_t n_rows, const int32_
         for (int32_t c = 0; c < chunks; ++c) {
             gt_item x;
             x.row = (int32_t)r;
-            x.e0 = b + c * GT_CHUNK;
-            x.e1 = min(e, x.e0 + GT_CHUNK);
+            x.e0 = b + c * chunk;
+            x.e1 = min(e, x.e0 + chunk);
             x.slot = p0 + c;
             items[it + c] = x;
             keys[it + c] = length_key(x.e1 - x.e0);
@@ -361,13 +374,13 @@ struct PlanLayout {
     size_t counts;                       // 8 int32 read back by the host
     size_t ca, cb, cc;                   // per-row count arrays (max(n_dst, n_src) + 1 each)
     size_t items_tmp, item_keys, item_keys2, item_idx;   // unsorted items, sort keys / indices
-    size_t k0, v0, k1, v1;               // sort ping-pong (E each)
+    size_t k0, v0, k1, v1;               // sort ping-pong (E each); k0, v0, v1 hold the coefficient arrays afterwards
     size_t hist, scan_tmp;
     size_t total;
 };
 
-int64_t max_items(int64_t n_rows, int64_t E) { return n_rows + E / GT_CHUNK + 1; }
-int64_t max_splits(int64_t E) { return E / GT_SPLIT_MIN + 1; }
+int64_t max_items(int64_t n_rows, int64_t E) { return n_rows + E / gt_chunk_for(E) + 1; }
+int64_t max_splits(int64_t E) { return E / gt_split_min(gt_chunk_for(E)) + 1; }
 
 PlanLayout plan_layout(int64_t n_dst, int64_t n_src, int64_t E, bool has_ew) {
     PlanLayout L{};
@@ -413,15 +426,15 @@ T *at(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(w
 
 // counts of one direction into cnt[0..2] (items, partials, splits): scans of the per-row counts;
 // the exclusive scan over n_rows + 1 entries (last input 0) leaves the total in element n_rows.
-gt_status count_direction(const int32_t *rowptr, int64_t n_rows, void *ws, const PlanLayout &L, int32_t *cnt3,
-                          hipStream_t st) {
+gt_status count_direction(const int32_t *rowptr, int64_t n_rows, int chunk, void *ws, const PlanLayout &L,
+                          int32_t *cnt3, hipStream_t st) {
     int32_t *ca = at<int32_t>(ws, L.ca), *cb = at<int32_t>(ws, L.cb), *cc = at<int32_t>(ws, L.cc);
     int32_t *stmp = at<int32_t>(ws, L.scan_tmp);
     GT_HIP(hipMemsetAsync(ca + n_rows, 0, 4, st));
     GT_HIP(hipMemsetAsync(cb + n_rows, 0, 4, st));
     GT_HIP(hipMemsetAsync(cc + n_rows, 0, 4, st));
     if (n_rows > 0) {
-        k_item_counts<<<nblocks(n_rows), PT, 0, st>>>(rowptr, n_rows, ca, cb, cc);
+        k_item_counts<<<nblocks(n_rows), PT, 0, st>>>(rowptr, n_rows, chunk, ca, cb, cc);
         GT_LAUNCH_CHECK("k_item_counts");
     }
     gt_status s;
@@ -435,14 +448,14 @@ gt_status count_direction(const int32_t *rowptr, int64_t n_rows, void *ws, const
 }
 
 // items of one direction, sorted longest first (stable, so equal lengths keep row order).
-gt_status build_direction(const int32_t *rowptr, int64_t n_rows, int64_t n_items, void *ws, const PlanLayout &L,
-                          gt_item *items_out, gt_split *splits_out, hipStream_t st) {
+gt_status build_direction(const int32_t *rowptr, int64_t n_rows, int chunk, int64_t n_items, void *ws,
+                          const PlanLayout &L, gt_item *items_out, gt_split *splits_out, hipStream_t st) {
     if (n_rows <= 0 || n_items <= 0) return GT_OK;
     int32_t *ca = at<int32_t>(ws, L.ca), *cb = at<int32_t>(ws, L.cb), *cc = at<int32_t>(ws, L.cc);
     gt_item *tmp = at<gt_item>(ws, L.items_tmp);
     uint32_t *keys = at<uint32_t>(ws, L.item_keys), *keys2 = at<uint32_t>(ws, L.item_keys2);
     uint32_t *idx = at<uint32_t>(ws, L.item_idx);
-    k_fill_items<<<nblocks(n_rows), PT, 0, st>>>(rowptr, n_rows, ca, cb, cc, tmp, keys, splits_out);
+    k_fill_items<<<nblocks(n_rows), PT, 0, st>>>(rowptr, n_rows, chunk, ca, cb, cc, tmp, keys, splits_out);
     GT_LAUNCH_CHECK("k_fill_items");
     SortTmp t{at<int32_t>(ws, L.hist), at<int32_t>(ws, L.scan_tmp)};
     gt_status s = radix_pass(keys, nullptr, keys2, idx, n_items, 0, t, st);
@@ -535,7 +548,13 @@ extern "C" gt_status gt_graph_create(gt_graph **out, int64_t n_dst, int64_t n_sr
         PLAN_LAUNCH("k_row_degrees(out)");
     }
     if (E > 0) {
-        k_transposed_entries<<<nblocks(E), PT, 0, st>>>(rowptr, n_dst, g->perm, E, ew, g->colidx_t, g->ew_t);
+        // the sort's ping-pong buffers are dead from here on; three of them hold the coefficients
+        g->coef_sym_f = g->dinv ? reinterpret_cast<float *>(v0) : nullptr;
+        g->coef_sym_b = g->dinv ? reinterpret_cast<float *>(v1) : nullptr;
+        g->coef_mean_b = reinterpret_cast<float *>(k0);
+        k_transposed_entries<<<nblocks(E), PT, 0, st>>>(rowptr, n_dst, g->perm, E, colidx, ew, g->dinv, g->rdeg,
+                                                        g->colidx_t, g->ew_t, g->coef_sym_f, g->coef_sym_b,
+                                                        g->coef_mean_b);
         PLAN_LAUNCH("k_transposed_entries");
     }
     // work-list sizes of both directions, read back once
@@ -543,26 +562,29 @@ extern "C" gt_status gt_graph_create(gt_graph **out, int64_t n_dst, int64_t n_sr
     int32_t h_counts[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     // forward counts are consumed (scanned arrays) before the transposed direction reuses them,
     // so the forward items are filled between the two counting steps.
-    if ((s = count_direction(rowptr, n_dst, ws, L, d_counts, st)) != GT_OK) return fail(s);
+    g->chunk = gt_chunk_for(E);
+    if ((s = count_direction(rowptr, n_dst, g->chunk, ws, L, d_counts, st)) != GT_OK) return fail(s);
     PLAN_HIP(hipMemcpyAsync(h_counts, d_counts, 3 * 4, hipMemcpyDeviceToHost, st));
     PLAN_HIP(hipStreamSynchronize(st));
     g->fwd.rowptr = rowptr; g->fwd.nbr = colidx; g->fwd.wt = ew; g->fwd.n_rows = n_dst;
+    g->fwd.coef_sym = g->coef_sym_f;
     g->fwd.n_items = h_counts[0]; g->fwd.n_partials = h_counts[1]; g->fwd.n_splits = h_counts[2];
     g->fwd.items = at<gt_item>(ws, L.items_f); g->fwd.splits = at<gt_split>(ws, L.splits_f);
     if (g->fwd.n_items > max_items(n_dst, E) || g->fwd.n_splits > max_splits(E))
         return fail(gt_fail(GT_ERR_INTERNAL, "gt_graph_create: forward work list exceeds its bound (is rowptr valid?)"));
-    if ((s = build_direction(rowptr, n_dst, g->fwd.n_items, ws, L, at<gt_item>(ws, L.items_f),
+    if ((s = build_direction(rowptr, n_dst, g->chunk, g->fwd.n_items, ws, L, at<gt_item>(ws, L.items_f),
                              at<gt_split>(ws, L.splits_f), st)) != GT_OK) return fail(s);
 
-    if ((s = count_direction(g->rowptr_t, n_src, ws, L, d_counts + 4, st)) != GT_OK) return fail(s);
+    if ((s = count_direction(g->rowptr_t, n_src, g->chunk, ws, L, d_counts + 4, st)) != GT_OK) return fail(s);
     PLAN_HIP(hipMemcpyAsync(h_counts + 4, d_counts + 4, 3 * 4, hipMemcpyDeviceToHost, st));
     PLAN_HIP(hipStreamSynchronize(st));
     g->bwd.rowptr = g->rowptr_t; g->bwd.nbr = g->colidx_t; g->bwd.wt = g->ew_t; g->bwd.n_rows = n_src;
+    g->bwd.coef_sym = g->coef_sym_b; g->bwd.coef_mean = g->coef_mean_b;
     g->bwd.n_items = h_counts[4]; g->bwd.n_partials = h_counts[5]; g->bwd.n_splits = h_counts[6];
     g->bwd.items = at<gt_item>(ws, L.items_b); g->bwd.splits = at<gt_split>(ws, L.splits_b);
     if (g->bwd.n_items > max_items(n_src, E) || g->bwd.n_splits > max_splits(E))
         return fail(gt_fail(GT_ERR_INTERNAL, "gt_graph_create: transposed work list exceeds its bound"));
-    if ((s = build_direction(g->rowptr_t, n_src, g->bwd.n_items, ws, L, at<gt_item>(ws, L.items_b),
+    if ((s = build_direction(g->rowptr_t, n_src, g->chunk, g->bwd.n_items, ws, L, at<gt_item>(ws, L.items_b),
                              at<gt_split>(ws, L.splits_b), st)) != GT_OK) return fail(s);
     PLAN_HIP(hipStreamSynchronize(st));
 #undef PLAN_HIP

@@ -50,10 +50,13 @@ def test_plan_bit_exact(case):
     np.testing.assert_array_equal(cit, ocit)
     info = g.info()
     deg_t = np.diff(orpt) if n_src else np.zeros(0, int)
+    chunk = 512                       # 512 entries per work item, halved while E / chunk < 4096 (floor 64)
+    while chunk > 64 and ci.size // chunk < 4096:
+        chunk //= 2
     for key, deg in (("fwd", odin), ("bwd", deg_t)):
-        split = deg > 768
+        split = deg > chunk + chunk // 2
         assert info[key + "_split_rows"] == int(split.sum())
-        assert info[key + "_items"] == int((~split).sum() + np.ceil(deg[split] / 512).sum())
+        assert info[key + "_items"] == int((~split).sum() + np.ceil(deg[split] / chunk).sum())
 
 
 def test_validate_counts_violations():
