@@ -14,37 +14,10 @@
 
 namespace {
 
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef uint16_t bf16_t;
-
-constexpr int KT = 32;   // k-tile
-
-__device__ inline uint32_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
-__device__ inline float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
-
-template <typename T> struct Elem;
-template <> struct Elem<float> { static constexpr int VE = 4; static constexpr int PAD = 4; };
-template <> struct Elem<bf16_t> { static constexpr int VE = 8; static constexpr int PAD = 8; };
-
-struct GemmArgs {
-    const void *A; int64_t lda;
-    const void *B; int64_t ldb;
-    void *C; int64_t ldc;          // output (type c_bf16 ? bf16 : f32), or fp32 partials when splits > 1
-    const void *Cin; int64_t ldcin; // optional addend, same type as C
-    const float *bias;
-    const float *rowscale;         // optional per-row factor applied to the product before addend/bias
-    int relu;
-    int c_bf16;
-    int64_t M, N, K;
-    int64_t k_per_split;           // multiple of KT
-    int vecA, vecB;                // 16-byte loads allowed
-};
+typedef gemm_bf16_t bf16_t;
+constexpr int KT = GEMM_KT;
+__device__ inline uint32_t f32_to_bf16(float f) { return gemm_f32_to_bf16(f); }
+__device__ inline float bf16_to_f32(uint32_t h) { return gemm_bf16_to_f32(h); }
 
 // Global -> registers for a ROWS x COLS tile whose COLS direction is contiguous in memory.
 // Element (r, c) sits at p[(r0 + r) * ld + c0 + c]; anything at or beyond (rlim, clim) reads 0.
@@ -215,36 +188,7 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
         }
     }
 
-    // Epilogue.  Accumulator register r of lane (h, l32) holds row 8*(r/4) + 4*h + r%4, column l32.
-    const bool partial = gridDim.z > 1;
-#pragma unroll
-    for (int a = 0; a < TM; ++a) {
-#pragma unroll
-        for (int b = 0; b < TN; ++b) {
-            const int64_t col = n0 + (wn * TN + b) * 32 + l32;
-            if (col >= g.N) continue;
-            const float bia = (!partial && g.bias) ? g.bias[col] : 0.0f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = m0 + (wm * TM + a) * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                if (row >= g.M) continue;
-                float v = acc[a][b][r];
-                if (partial) {
-                    static_cast<float *>(g.C)[((int64_t)blockIdx.z * g.M + row) * g.N + col] = v;
-                    continue;
-                }
-                if (g.rowscale) v *= g.rowscale[row];
-                if (g.Cin) {
-                    v += g.c_bf16 ? bf16_to_f32(static_cast<const bf16_t *>(g.Cin)[row * g.ldcin + col])
-                                  : static_cast<const float *>(g.Cin)[row * g.ldcin + col];
-                }
-                v += bia;
-                if (g.relu) v = v > 0.0f ? v : 0.0f;
-                if (g.c_bf16) static_cast<bf16_t *>(g.C)[row * g.ldc + col] = (bf16_t)f32_to_bf16(v);
-                else static_cast<float *>(g.C)[row * g.ldc + col] = v;
-            }
-        }
-    }
+    gemm_epilogue<TM, TN>(g, acc, m0 + wm * TM * 32, n0 + wn * TN * 32, l32, h);
 }
 
 // C = act(sum_z P[z] + C_in + bias), partials added in z order
@@ -354,8 +298,12 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     g.Cin = Cin; g.ldcin = ldcin;
     if (p.splits > 1) { g.C = ws; g.ldc = N; } else { g.C = C; g.ldc = ldc; }
     const int tr = gt_trace_open(GT_TRACE_COMBINE, N, M, M * N * K, st);
-    gt_status s = (dtype == GT_F32) ? launch_gemm_t<float>(g, transA, transB, p.splits, st)
-                                    : launch_gemm_t<bf16_t>(g, transA, transB, p.splits, st);
+    // fp32 shapes bound by matrix throughput go through the split-bf16 kernel (3/8 of the fp32
+    // MFMA cost at fp32-level accuracy); skinny, memory-bound shapes keep the plain fp32 MFMA
+    const bool x3 = dtype == GT_F32 && N > 64 && K >= 64 && (double)M * (double)N * (double)K >= 268435456.0;
+    gt_status s = x3 ? gt_gemm_x3_launch(g, transA, transB, p.splits, st)
+                     : (dtype == GT_F32) ? launch_gemm_t<float>(g, transA, transB, p.splits, st)
+                                         : launch_gemm_t<bf16_t>(g, transA, transB, p.splits, st);
     gt_trace_close(tr, st);
     if (s != GT_OK) return s;
     if (p.splits > 1) {

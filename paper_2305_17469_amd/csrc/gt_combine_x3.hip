@@ -1,0 +1,199 @@
+// fp32 combination on the bf16 matrix cores by exact three-way splitting.
+//
+// Every fp32 operand element x is cut into three bf16 pieces by truncation, x = hi + mid + lo
+// exactly (8 + 8 + 8 significand bits; the residuals x - hi and x - hi - mid are exact in fp32).
+// A product a*b is then the sum of nine bf16 x bf16 products, each exact in fp32; the six
+// largest (hi*hi, hi*mid, mid*hi, hi*lo, lo*hi, mid*mid) are accumulated in fp32 by
+// v_mfma_f32_32x32x16_bf16 and the three dropped ones are below 2^-24 of |a*b|, i.e. at the
+// level of fp32 rounding itself.  On CDNA4 the bf16 MFMA rate is 16x the fp32 MFMA rate, so six
+// bf16 instructions per product block cost 3/8 of the fp32 instruction they replace.  Used for
+// the shapes of the combination that are bound by matrix throughput (wide K and N); the skinny,
+// memory-bound shapes stay on the plain fp32 MFMA kernel.
+//
+// Layout: 128 x 128 workgroup tile, 4 wavefronts of 64 x 64 accumulators, k-tile 32.  Both
+// operands are converted and split while they are stored to LDS, k-contiguous per row
+// ([row][k], three planes), so every MFMA fragment is one ds_read_b128.  Operands whose global
+// layout is k-major (the weight matrix, both operands of the weight gradient) are transposed on
+// the way in registers: a thread loads a 4(k) x 4(row) patch and writes four 8-byte k-runs.
+#include <type_traits>
+
+#include "gt_internal.h"
+#include "gt_combine.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int KT = GEMM_KT;          // 32
+constexpr int BM = 128, BN = 128;
+constexpr int STR = KT + 8;          // LDS row stride in bf16 elements (80 bytes: 16-byte aligned, bank friendly)
+constexpr int PLANE = BM * STR;      // elements per plane
+
+// three truncated bf16 pieces of x: x == hi + mid + lo exactly (barring underflow)
+__device__ inline void split3(float x, uint32_t &hi, uint32_t &mid, uint32_t &lo) {
+    const uint32_t h = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(h);
+    const uint32_t m = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(m);
+    hi = h; mid = m; lo = __float_as_uint(r2) & 0xffff0000u;
+}
+
+// four consecutive-k values -> three 8-byte k-runs (one per plane) at lds[plane][row][k]
+__device__ inline void store_run4(gemm_bf16_t *lds, int row, int k, float x0, float x1, float x2, float x3) {
+    uint32_t h[4], m[4], l[4];
+    split3(x0, h[0], m[0], l[0]);
+    split3(x1, h[1], m[1], l[1]);
+    split3(x2, h[2], m[2], l[2]);
+    split3(x3, h[3], m[3], l[3]);
+    gemm_bf16_t *p = lds + row * STR + k;
+    *reinterpret_cast<uint2 *>(p) = make_uint2((h[0] >> 16) | h[1], (h[2] >> 16) | h[3]);
+    *reinterpret_cast<uint2 *>(p + PLANE) = make_uint2((m[0] >> 16) | m[1], (m[2] >> 16) | m[3]);
+    *reinterpret_cast<uint2 *>(p + 2 * PLANE) = make_uint2((l[0] >> 16) | l[1], (l[2] >> 16) | l[3]);
+}
+
+__device__ inline float4 load4(const float *p, int64_t off, int64_t c, int64_t clim, bool row_ok, int vec) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (row_ok && c < clim) {
+        const float *s = p + off;
+        if (vec && c + 4 <= clim) {
+            v = *reinterpret_cast<const float4 *>(s);
+        } else {
+            v.x = s[0];
+            if (c + 1 < clim) v.y = s[1];
+            if (c + 2 < clim) v.z = s[2];
+            if (c + 3 < clim) v.w = s[3];
+        }
+    }
+    return v;
+}
+
+// 128 rows x 32 k of an operand whose k direction is contiguous in memory: element (i, k) at
+// p[(i0 + i) * ld + k0 + k].  Four float4 per thread, lanes run along k first.
+struct LoadKC {
+    float4 r[4];
+    __device__ inline void load(const float *p, int64_t ld, int64_t i0, int64_t k0, int64_t ilim, int64_t klim, int vec) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int u = threadIdx.x + 256 * it;
+            const int i = u >> 3, kq = u & 7;
+            const int64_t gi = i0 + i, gk = k0 + kq * 4;
+            r[it] = load4(p, gi * ld + gk, gk, klim, gi < ilim, vec);
+        }
+    }
+    __device__ inline void store(gemm_bf16_t *lds) const {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int u = threadIdx.x + 256 * it;
+            store_run4(lds, u >> 3, (u & 7) * 4, r[it].x, r[it].y, r[it].z, r[it].w);
+        }
+    }
+};
+
+// 32 k x 128 rows of an operand whose row direction is contiguous in memory: element (i, k) at
+// p[(k0 + k) * ld + i0 + i].  One 4(k) x 4(i) patch per thread, transposed in registers.
+struct LoadKM {
+    float4 r[4];   // r[dk] = rows i..i+3 at k + dk
+    __device__ inline void load(const float *p, int64_t ld, int64_t i0, int64_t k0, int64_t ilim, int64_t klim, int vec) {
+        const int kq = threadIdx.x & 7, iq = threadIdx.x >> 3;
+#pragma unroll
+        for (int dk = 0; dk < 4; ++dk) {
+            const int64_t gk = k0 + kq * 4 + dk, gi = i0 + iq * 4;
+            r[dk] = load4(p, gk * ld + gi, gi, ilim, gk < klim, vec);
+        }
+    }
+    __device__ inline void store(gemm_bf16_t *lds) const {
+        const int kq = threadIdx.x & 7, iq = threadIdx.x >> 3;
+        store_run4(lds, iq * 4 + 0, kq * 4, r[0].x, r[1].x, r[2].x, r[3].x);
+        store_run4(lds, iq * 4 + 1, kq * 4, r[0].y, r[1].y, r[2].y, r[3].y);
+        store_run4(lds, iq * 4 + 2, kq * 4, r[0].z, r[1].z, r[2].z, r[3].z);
+        store_run4(lds, iq * 4 + 3, kq * 4, r[0].w, r[1].w, r[2].w, r[3].w);
+    }
+};
+
+template <bool TA, bool TB>
+__global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) gemm_bf16_t As[3 * PLANE];
+    __shared__ __attribute__((aligned(16))) gemm_bf16_t Bs[3 * PLANE];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
+    const int64_t kend = (kbeg + g.k_per_split < g.K) ? kbeg + g.k_per_split : g.K;
+    const float *A = static_cast<const float *>(g.A);
+    const float *B = static_cast<const float *>(g.B);
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+
+    // op(A)(i,k) = TA ? A[k*lda + i] : A[i*lda + k];  op(B)(k,j) = TB ? B[j*ldb + k] : B[k*ldb + j]
+    typename std::conditional<TA, LoadKM, LoadKC>::type la;
+    typename std::conditional<TB, LoadKC, LoadKM>::type lb;
+    if (kbeg < kend) {
+        la.load(A, g.lda, m0, kbeg, g.M, kend, g.vecA);
+        lb.load(B, g.ldb, n0, kbeg, g.N, kend, g.vecB);
+    }
+    // One register stage: the loads of k-tile t+1 are in flight while tile t is multiplied.  (Two
+    // stages were measured slower on MI355X: the extra registers halve the occupancy.)
+    for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
+        __syncthreads();
+        la.store(As);
+        lb.store(Bs);
+        __syncthreads();
+        if (k0 + KT < kend) {
+            la.load(A, g.lda, m0, k0 + KT, g.M, kend, g.vecA);
+            lb.load(B, g.ldb, n0, k0 + KT, g.N, kend, g.vecB);
+        }
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int kk = s * 16 + h * 8;   // lane half h supplies k = kk .. kk+7 of this step
+            bf16x8 af[2][3], bf[2][3];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                const int i = (wm * 2 + a) * 32 + l32;
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+                    af[a][p] = *reinterpret_cast<const bf16x8 *>(&As[p * PLANE + i * STR + kk]);
+            }
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int j = (wn * 2 + b) * 32 + l32;
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+                    bf[b][p] = *reinterpret_cast<const bf16x8 *>(&Bs[p * PLANE + j * STR + kk]);
+            }
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    floatx16 c = acc[a][b];
+                    // smallest terms first: lo*hi, hi*lo, mid*mid, then mid*hi, hi*mid, then hi*hi
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a][2], bf[b][0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a][0], bf[b][2], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a][1], bf[b][1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a][1], bf[b][0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a][0], bf[b][1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a][0], bf[b][0], c, 0, 0, 0);
+                    acc[a][b] = c;
+                }
+        }
+    }
+    gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h);
+}
+
+}  // namespace
+
+gt_status gt_gemm_x3_launch(const GemmArgs &g, int transA, int transB, int splits, hipStream_t st) {
+    dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM), (unsigned)splits);
+    if (!transA && !transB) k_gemm_x3<false, false><<<grid, 256, 0, st>>>(g);
+    else if (!transA && transB) k_gemm_x3<false, true><<<grid, 256, 0, st>>>(g);
+    else if (transA && !transB) k_gemm_x3<true, false><<<grid, 256, 0, st>>>(g);
+    else k_gemm_x3<true, true><<<grid, 256, 0, st>>>(g);
+    GT_LAUNCH_CHECK("k_gemm_x3");
+    return GT_OK;
+}

@@ -18,7 +18,9 @@ pytestmark = pytest.mark.gpu
 
 # (M, N, K): several tiles, ragged tails in every dimension, the skinny widths of the workloads
 SHAPES = [(1, 1, 1), (300, 64, 64), (257, 16, 100), (515, 41, 128), (130, 47, 256), (260, 128, 602),
-          (129, 256, 100), (70, 1024, 16), (200, 16, 1024), (33, 130, 37)]
+          (129, 256, 100), (70, 1024, 16), (200, 16, 1024), (33, 130, 37),
+          # large enough for the fp32 path that runs on the bf16 matrix cores by three-way splitting
+          (2100, 130, 1000), (1030, 602, 450)]
 
 
 def _check(got, ref, absr, dtype, c_bf16, what):
@@ -66,12 +68,27 @@ def test_combine_all_transposes(shape, dtype):
                     _check(down(C32), ref_lin, absr, dtype, False, ("f32out", tA, tB))
 
 
+def test_split_bf16_path_keeps_fp32_accuracy_on_hard_inputs():
+    """Inputs with a wide dynamic range and no cancellation: the relative error of every output
+    must stay at fp32 level (the three dropped cross products are below 2^-24 of each term)."""
+    from paper_2305_17469_amd import binding as B
+    rng = np.random.default_rng(9)
+    M, N, K = 1500, 192, 1024
+    A = (np.abs(tensors.normal((M, K), seed=1)) * np.exp2(rng.integers(-20, 20, (M, 1)))).astype(np.float32)
+    Bm = (np.abs(tensors.normal((K, N), seed=2)) * np.exp2(rng.integers(-20, 20, (1, N)))).astype(np.float32)
+    announce("combine split-bf16 accuracy", (M, N, K))
+    C = B.gt_combine(up_feat(A, "f32"), up_feat(Bm, "f32"))
+    ref = oracle.combine(A, Bm)
+    rel = np.abs(down(C) - ref) / ref          # all terms positive: ref is the sum of magnitudes
+    assert rel.max() <= 1e-5, rel.max()   # fp32 accumulation of 1,024 positive terms: ~sqrt(K) * 2^-24
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_weight_gradient_shape_split_reduction(dtype):
     """op(A)^T op(B) with a long reduction (the node dimension): split over workgroups, summed in
     a fixed order; must be reproducible bit for bit."""
     from paper_2305_17469_amd import binding as B
-    rows, fi, fo = 40_000, 100, 47
+    rows, fi, fo = (40_000, 100, 47) if dtype == "bf16" else (30_000, 130, 100)
     A = tensors.normal((rows, fi), seed=11)
     G = tensors.normal((rows, fo), seed=12)
     if dtype == "bf16":
