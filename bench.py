@@ -119,6 +119,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--reorder-check", action="store_true",
                     help="time every layer's fwd+bwd in both forced orders and compare with AUTO's choice")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step from a captured HIP graph (launch-bound workloads); per-kernel "
+                         "timing then comes from a separate eager pass")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -210,10 +213,29 @@ def main():
     torch.cuda.synchronize()
     B.gt_trace_reset()
     B.gt_trace_enable(True)
+    graph = None
+    if args.graph:
+        # eager traced pass for the per-kernel figures, then capture one step and time replays
+        for _ in range(args.steps):
+            model.step(X, G, args.fwd_order, args.bwd_order)
+        torch.cuda.synchronize()
+        B.gt_trace_enable(False)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            model.step(X, G, args.fwd_order, args.bwd_order)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                model.step(X, G, args.fwd_order, args.bwd_order)
+        for _ in range(args.warmup):
+            graph.replay()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        model.step(X, G, args.fwd_order, args.bwd_order)
+        if graph is not None:
+            graph.replay()
+        else:
+            model.step(X, G, args.fwd_order, args.bwd_order)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     B.gt_trace_enable(False)
@@ -269,7 +291,7 @@ def main():
                            dims=cfg["dims"], model=None, reduce=cfg["reduce"], layers=L,
                            orders_fwd=model.used_fwd, orders_bwd=model.used_bwd,
                            nominal_edge_features_per_step=nominal_ef, executed_edge_features_per_step=executed_ef,
-                           plan_ms=plan_ms, input_generation_s=gen_s),
+                           plan_ms=plan_ms, input_generation_s=gen_s, hip_graph=bool(args.graph)),
                roofline=roofline, kernels=kernels[:8])
     del out["config"]["model"]
     if not args.no_cpu_baseline:

@@ -23,9 +23,9 @@ namespace {
 
 typedef uint16_t bf16_t;
 
-// Coefficients in seconds.  Defaults are MI355X figures (a gather near 3 TB/s, fp32 MFMA near
-// 60 TFLOP/s sustained); gt_calibrate replaces them with fitted values.
-gt_cost_coeffs g_cost = {3.3e-14, 2.0e-12, 1.3e-12, 1.3e-12, 3.3e-14, 2.0e-12, 1.3e-12, 1.3e-12};
+// Coefficients in seconds.  Defaults are the values gt_calibrate fitted on an MI355X (fp32);
+// gt_calibrate replaces them with values fitted on the device at hand.
+gt_cost_coeffs g_cost = {1.2e-14, 2.0e-12, 5.1e-13, 8.4e-13, 1.1e-14, 2.1e-12, 4.6e-13, 1.26e-12};
 
 double t_comb(const gt_cost_coeffs &c, bool bwd, double rows, double in, double out) {
     return bwd ? rows * (c.alpha_bwd * in * out + c.beta_bwd * in) : rows * (c.alpha_fwd * in * out + c.beta_fwd * out);

@@ -1,0 +1,110 @@
+"""Run-time facilities around the kernels: coefficient calibration, per-kernel event timing, and
+replay of a whole fwd+bwd step from a captured HIP graph (the layer calls allocate nothing, never
+synchronise and record no memset nodes, so a caller may capture them)."""
+import numpy as np
+import pytest
+import torch
+
+from gt_inputs import configs
+from gpu_util import announce, up_feat, up_i32
+
+pytestmark = pytest.mark.gpu
+
+
+def _stack(cfg, dev):
+    from paper_2305_17469_amd.stack import LayerStack
+    dt = cfg["dtype"]
+    blocks, seen = [], {}
+    for blk in cfg["blocks"]:
+        if id(blk["rowptr"]) not in seen:
+            seen[id(blk["rowptr"])] = dict(rowptr=up_i32(blk["rowptr"]), colidx=up_i32(blk["colidx"]),
+                                           n_dst=blk["n_dst"], n_src=blk["n_src"])
+        blocks.append(seen[id(blk["rowptr"])])
+    sage = cfg["model"] == "sage"
+    W = [up_feat(w, dt) for w in cfg["W"]]
+    Wr = [up_feat(w, dt) for w in cfg["W_root"]] if sage else None
+    bs = [torch.from_numpy(b).to(dev) for b in cfg["b"]]
+    return LayerStack(blocks, cfg["dims"], dt, cfg["reduce"], W, bs, Wr)
+
+
+def test_calibrate_fits_positive_coefficients_and_keeps_decisions():
+    from paper_2305_17469_amd import binding as B
+    announce("gt_calibrate")
+    old = B.gt_cost_get()
+    try:
+        c = B.gt_calibrate()
+        vals = {f[0]: getattr(c, f[0]) for f in c._fields_}
+        print(vals)
+        assert all(np.isfinite(v) and v >= 0 for v in vals.values())
+        assert vals["gamma_fwd"] > 0 and vals["gamma_bwd"] > 0 and vals["alpha_fwd"] > 0 and vals["alpha_bwd"] > 0
+        # a gather of one fp32 feature takes between 0.05 and 50 ps on this class of device
+        assert 5e-14 < vals["gamma_fwd"] < 5e-11 and 5e-14 < vals["gamma_bwd"] < 5e-11
+        got = B.gt_cost_get()
+        assert got.gamma_fwd == c.gamma_fwd and got.alpha_bwd == c.alpha_bwd       # installed
+        cfg = configs.reddit_like(11)
+        blk = cfg["blocks"][0]
+        g = B.Graph(up_i32(blk["rowptr"]), up_i32(blk["colidx"]), blk["n_src"])
+        assert B.gt_layer_decide(g, B.make_desc("symnorm", "f32", True, 602, 128, need_dx=False))[0] == "comb_first"
+        assert B.gt_layer_decide(g, B.make_desc("symnorm", "f32", True, 16, 1024))[0] == "agg_first"
+    finally:
+        B.gt_cost_set(old)
+
+
+def test_kernel_trace_records_every_gather_and_combine_launch():
+    from paper_2305_17469_amd import binding as B
+    announce("gt_trace")
+    dev = torch.device("cuda:0")
+    cfg = configs.tiny()
+    m = _stack(cfg, dev)
+    X, G = up_feat(cfg["X"], "f32"), up_feat(cfg["G"], "f32")
+    m.step(X, G)
+    B.gt_trace_reset()
+    B.gt_trace_enable(True)
+    m.step(X, G, "comb_first", "comb_first")
+    torch.cuda.synchronize()
+    B.gt_trace_enable(False)
+    recs = B.gt_trace_records()
+    B.gt_trace_reset()
+    kinds = [r[0] for r in recs]
+    # per layer: 1 forward gather, 1 transposed gather (A^T dZ), 3 combinations (X W, dW, dX) -- the
+    # first layer has no dX
+    assert kinds.count(0) == 2 and kinds.count(1) == 2 and kinds.count(2) == 5
+    assert all(r[4] > 0 for r in recs)
+    assert {r[1] for r in recs if r[0] == 0} == {64, 16}
+    m.step(X, G)
+    assert B.gt_trace_records() == []            # disabled: nothing recorded
+
+
+@pytest.mark.parametrize("which", ["tiny", "sage"])
+def test_step_replays_from_a_captured_graph(which):
+    announce("graph capture of a fwd+bwd step:", which)
+    dev = torch.device("cuda:0")
+    cfg = configs.tiny() if which == "tiny" else configs.sage_minibatch(13, 128)
+    m = _stack(cfg, dev)
+    X, G = up_feat(cfg["X"], "f32"), up_feat(cfg["G"], "f32")
+    m.step(X, G)                                  # eager reference (also fixes the AUTO orders)
+    torch.cuda.synchronize()
+    ref_out = m.H[-1].clone()
+    ref_dW = [w.clone() for w in m.dW]
+    ref_db = [b.clone() for b in m.db]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        m.step(X, G)                              # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            m.step(X, G)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        # eager work and a synchronisation between replays; outputs are clobbered first
+        m.H[-1].zero_()
+        for w in m.dW:
+            w.fill_(float(rep))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(m.H[-1], ref_out), rep
+        for a, b in zip(m.dW, ref_dW):
+            assert torch.equal(a, b), rep
+        for a, b in zip(m.db, ref_db):
+            assert torch.equal(a, b), rep
