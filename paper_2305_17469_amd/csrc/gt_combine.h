@@ -40,40 +40,115 @@ struct GemmArgs {
     int64_t M, N, K;
     int64_t k_per_split;           // multiple of KT
     int vecA, vecB;                // 16-byte loads allowed
+    int ntm, ntn;                  // output tiles along M and N (host side; see gemm_tile_of_block)
 };
+
+// Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  The
+// 1-D grid is therefore read as (xcd, sequence number within the xcd): an XCD walks one row tile
+// at a time through all of its column tiles, so the row tile of op(A) that those column tiles
+// share is fetched into one L2 once.  Returns false for the padding workgroups of a ragged grid.
+// Used only when there are many row tiles; with few (the weight-gradient shape) the plain order
+// keeps all XCDs busy.
+#define GEMM_SWIZZLE_MIN_ROW_TILES 64
+__device__ inline bool gemm_tile_of_block(const GemmArgs &g, int &tile_m, int &tile_n) {
+    const int L = blockIdx.x;
+    if (g.ntm < GEMM_SWIZZLE_MIN_ROW_TILES) {
+        tile_n = L % g.ntn;
+        tile_m = L / g.ntn;
+        return true;
+    }
+    const int xcd = L & 7, i = L >> 3;
+    tile_n = i % g.ntn;
+    tile_m = (i / g.ntn) * 8 + xcd;
+    return tile_m < g.ntm;
+}
+static inline unsigned gemm_grid_x(int ntm, int ntn) {
+    return (unsigned)((ntm < GEMM_SWIZZLE_MIN_ROW_TILES ? ntm : (ntm + 7) / 8 * 8) * ntn);
+}
 
 
 // Epilogue of a wavefront's TM x TN grid of 32x32 MFMA accumulators whose top-left element is
-// (row0, col0).  Accumulator register r of lane (h, l32) holds row 8*(r/4) + 4*h + r%4, column l32.
+// (row0, col0).  Accumulator register r of lane (h, l32) holds row 8*(r/4) + 4*h + r%4, column l32,
+// i.e. a lane owns single columns: storing from registers would write 4-byte pieces.  The tile is
+// therefore passed through a per-wavefront LDS stage (32 rows at a time) and written row-major,
+// four consecutive columns per lane, so every store instruction covers whole 128-byte lines.
+// `stage` is this wavefront's private region of GEMM_STAGE_FLOATS(TN) floats; the caller has
+// already put a workgroup barrier between the last operand read and this call.
+#define GEMM_STAGE_STRIDE(TN) ((TN) * 32 + 4)
+#define GEMM_STAGE_FLOATS(TN) (32 * GEMM_STAGE_STRIDE(TN))
+
 template <int TM, int TN>
 __device__ inline void gemm_epilogue(const GemmArgs &g, floatx16 (&acc)[TM][TN], int64_t row0, int64_t col0, int l32,
-                                     int h) {
+                                     int h, float *stage) {
+    constexpr int STRIDE = GEMM_STAGE_STRIDE(TN);
+    constexpr int LPR = TN * 8;            // lanes per row: 4 columns each
+    constexpr int RPI = 64 / LPR;          // rows per store instruction
     const bool partial = gridDim.z > 1;
+    const int lane = h * 32 + l32;
+    const int c4 = (lane % LPR) * 4;
+    const int64_t col = col0 + c4;
+    float *out_f = static_cast<float *>(g.C);
+    gemm_bf16_t *out_h = static_cast<gemm_bf16_t *>(g.C);
+    const int64_t ldc = partial ? g.N : g.ldc;
+    if (partial) out_f += (int64_t)blockIdx.z * g.M * g.N;
+    const bool as_bf16 = !partial && g.c_bf16;
+    const bool vec_ok = (ldc % 4 == 0) && (((uintptr_t)g.C & 15) == 0) && (col + 4 <= g.N);
+    float bia[4] = {0.f, 0.f, 0.f, 0.f};
+    if (!partial && g.bias) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (col + i < g.N) bia[i] = g.bias[col + i];
+    }
 #pragma unroll
     for (int a = 0; a < TM; ++a) {
+        // registers -> stage: lanes write consecutive columns of one row (conflict free)
 #pragma unroll
-        for (int b = 0; b < TN; ++b) {
-            const int64_t col = col0 + b * 32 + l32;
-            if (col >= g.N) continue;
-            const float bia = (!partial && g.bias) ? g.bias[col] : 0.0f;
+        for (int b = 0; b < TN; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int64_t row = row0 + a * 32 + 8 * (r / 4) + 4 * h + (r % 4);
-                if (row >= g.M) continue;
-                float v = acc[a][b][r];
-                if (partial) {
-                    static_cast<float *>(g.C)[((int64_t)blockIdx.z * g.M + row) * g.N + col] = v;
-                    continue;
+            for (int r = 0; r < 16; ++r)
+                stage[(8 * (r / 4) + 4 * h + (r % 4)) * STRIDE + b * 32 + l32] = acc[a][b][r];
+        // stage -> memory, row-major (same wavefront wrote and reads: no workgroup barrier needed,
+        // LDS operations of one wavefront complete in order)
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+            const int rr = it * RPI + lane / LPR;
+            const int64_t row = row0 + a * 32 + rr;
+            const float4 v4 = *reinterpret_cast<const float4 *>(&stage[rr * STRIDE + c4]);
+            if (row >= g.M || col >= g.N) continue;
+            float v[4] = {v4.x, v4.y, v4.z, v4.w};
+            if (!partial) {
+                const float rs = g.rowscale ? g.rowscale[row] : 1.0f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    float x = v[i];
+                    if (g.rowscale) x *= rs;
+                    if (g.Cin && col + i < g.N)
+                        x += g.c_bf16 ? gemm_bf16_to_f32(static_cast<const gemm_bf16_t *>(g.Cin)[row * g.ldcin + col + i])
+                                      : static_cast<const float *>(g.Cin)[row * g.ldcin + col + i];
+                    x += bia[i];
+                    if (g.relu) x = x > 0.0f ? x : 0.0f;
+                    v[i] = x;
                 }
-                if (g.rowscale) v *= g.rowscale[row];
-                if (g.Cin) {
-                    v += g.c_bf16 ? gemm_bf16_to_f32(static_cast<const gemm_bf16_t *>(g.Cin)[row * g.ldcin + col])
-                                  : static_cast<const float *>(g.Cin)[row * g.ldcin + col];
+            }
+            if (as_bf16) {
+                gemm_bf16_t *p = out_h + row * ldc + col;
+                if (vec_ok) {
+                    *reinterpret_cast<uint2 *>(p) = make_uint2(gemm_f32_to_bf16(v[0]) | (gemm_f32_to_bf16(v[1]) << 16),
+                                                               gemm_f32_to_bf16(v[2]) | (gemm_f32_to_bf16(v[3]) << 16));
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (col + i < g.N) p[i] = (gemm_bf16_t)gemm_f32_to_bf16(v[i]);
                 }
-                v += bia;
-                if (g.relu) v = v > 0.0f ? v : 0.0f;
-                if (g.c_bf16) static_cast<gemm_bf16_t *>(g.C)[row * g.ldc + col] = (gemm_bf16_t)gemm_f32_to_bf16(v);
-                else static_cast<float *>(g.C)[row * g.ldc + col] = v;
+            } else {
+                float *p = out_f + row * ldc + col;
+                if (vec_ok) {
+                    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (col + i < g.N) p[i] = v[i];
+                }
             }
         }
     }

@@ -15,7 +15,7 @@
 namespace {
 
 typedef gemm_bf16_t bf16_t;
-constexpr int KT = GEMM_KT;
+constexpr int KT = 64;   // granularity of the split-k ranges: a multiple of every kernel's k-tile
 __device__ inline uint32_t f32_to_bf16(float f) { return gemm_f32_to_bf16(f); }
 __device__ inline float bf16_to_f32(uint32_t h) { return gemm_bf16_to_f32(h); }
 
@@ -28,26 +28,41 @@ struct TileLoader {
     static constexpr int TOTAL = ROWS * VPR;
     static constexpr int NV = (TOTAL + 255) / 256;        // vectors per thread
     uint4 reg[NV];
+    int nvalid[NV];   // elements of reg[it] that lie inside the matrix; the rest is zeroed when the
+                      // vector is stored to LDS (masking at load time would consume the data and
+                      // stall the prefetch)
 
+    // Branch free: an out-of-range vector reads the (always valid) start of the matrix instead and
+    // is masked to zero afterwards, so all loads of a tile are issued back to back and stay in
+    // flight together.  `vec` is uniform over the grid.
     __device__ inline void load(const T *p, int64_t ld, int64_t r0, int64_t c0, int64_t rlim, int64_t clim, int vec) {
+        if (vec) {
 #pragma unroll
-        for (int it = 0; it < NV; ++it) {
-            const int q = threadIdx.x + 256 * it;
-            const int r = q / VPR, c = (q % VPR) * VE;
-            const int64_t gr = r0 + r, gc = c0 + c;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if ((TOTAL % 256 == 0 || q < TOTAL) && gr < rlim && gc < clim) {
-                const T *src = p + gr * ld + gc;
-                if (vec && gc + VE <= clim) {
-                    v = *reinterpret_cast<const uint4 *>(src);
-                } else {
-                    T tmp[VE];
-#pragma unroll
-                    for (int e = 0; e < VE; ++e) tmp[e] = (gc + e < clim) ? src[e] : (T)0;
-                    v = *reinterpret_cast<const uint4 *>(tmp);
-                }
+            for (int it = 0; it < NV; ++it) {
+                const int q = threadIdx.x + 256 * it;
+                const int r = q / VPR, c = (q % VPR) * VE;
+                const int64_t gr = r0 + r, gc = c0 + c;
+                const bool ok = (TOTAL % 256 == 0 || q < TOTAL) && gr < rlim && gc < clim;
+                reg[it] = *reinterpret_cast<const uint4 *>(p + (ok ? gr * ld + gc : 0));
+                nvalid[it] = ok ? (int)((clim - gc) < VE ? (clim - gc) : VE) : 0;
             }
-            reg[it] = v;
+        } else {
+#pragma unroll
+            for (int it = 0; it < NV; ++it) {
+                const int q = threadIdx.x + 256 * it;
+                const int r = q / VPR, c = (q % VPR) * VE;
+                const int64_t gr = r0 + r, gc = c0 + c;
+                const bool rok = (TOTAL % 256 == 0 || q < TOTAL) && gr < rlim;
+                T tmp[VE];
+#pragma unroll
+                for (int e = 0; e < VE; ++e) {
+                    const bool ok = rok && gc + e < clim;
+                    const T x = p[ok ? gr * ld + gc + e : 0];
+                    tmp[e] = ok ? x : (T)0;
+                }
+                reg[it] = *reinterpret_cast<const uint4 *>(tmp);
+                nvalid[it] = VE;
+            }
         }
     }
     template <int STR>
@@ -56,28 +71,50 @@ struct TileLoader {
         for (int it = 0; it < NV; ++it) {
             const int q = threadIdx.x + 256 * it;
             const int r = q / VPR, c = (q % VPR) * VE;
-            if (TOTAL % 256 == 0 || q < TOTAL) *reinterpret_cast<uint4 *>(lds + r * STR + c) = reg[it];
+            uint4 v = reg[it];
+            const int nv = nvalid[it];
+            if constexpr (sizeof(T) == 4) {
+                v.x = nv > 0 ? v.x : 0u; v.y = nv > 1 ? v.y : 0u; v.z = nv > 2 ? v.z : 0u; v.w = nv > 3 ? v.w : 0u;
+            } else {
+                v.x &= nv >= 2 ? 0xffffffffu : (nv == 1 ? 0x0000ffffu : 0u);
+                v.y &= nv >= 4 ? 0xffffffffu : (nv == 3 ? 0x0000ffffu : 0u);
+                v.z &= nv >= 6 ? 0xffffffffu : (nv == 5 ? 0x0000ffffu : 0u);
+                v.w &= nv >= 8 ? 0xffffffffu : (nv == 7 ? 0x0000ffffu : 0u);
+            }
+            if (TOTAL % 256 == 0 || q < TOTAL) *reinterpret_cast<uint4 *>(lds + r * STR + c) = v;
         }
     }
 };
 
 // op(A)(i,k): TA ? A[k*lda+i] : A[i*lda+k];   op(B)(k,j): TB ? B[j*ldb+k] : B[k*ldb+j]
-template <typename T, bool TA, bool TB, int WGM, int WGN, int TM, int TN>
+// VA / VB: the operand allows 16-byte loads (aligned base, row stride a multiple of 16 bytes)
+template <typename T, bool TA, bool TB, int WGM, int WGN, int TM, int TN, bool VA, bool VB>
 __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     constexpr int PAD = Elem<T>::PAD;
+    // k-tile of 32 for both types (64 was measured for bf16: fewer barrier rounds, but the extra
+    // staging registers cost a wavefront of occupancy and the memory-bound shapes got slower)
+    constexpr int KT = 32;
     constexpr int ASTR = TA ? BM + PAD : KT + PAD;
     constexpr int BSTR = TB ? KT + PAD : BN + PAD;
     constexpr int A_ELEMS = TA ? KT * ASTR : BM * ASTR;
     constexpr int B_ELEMS = TB ? BN * BSTR : KT * BSTR;
-    __shared__ __attribute__((aligned(16))) T As[A_ELEMS];
-    __shared__ __attribute__((aligned(16))) T Bs[B_ELEMS];
+    // one LDS buffer: operand tiles during the k-loop, the per-wavefront output stages afterwards
+    constexpr int TILE_BYTES = (A_ELEMS + B_ELEMS) * (int)sizeof(T);
+    constexpr int STAGE_BYTES = 4 * GEMM_STAGE_FLOATS(TN) * 4;
+    constexpr int SMEM_BYTES = TILE_BYTES > STAGE_BYTES ? TILE_BYTES : STAGE_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[SMEM_BYTES];
+    T *As = reinterpret_cast<T *>(smem);
+    T *Bs = As + A_ELEMS;
+    static_assert((A_ELEMS * sizeof(T)) % 16 == 0, "B tile must stay 16-byte aligned");
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     const int wm = wave / WGN, wn = wave % WGN;
-    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    int tile_m, tile_n;
+    if (!gemm_tile_of_block(g, tile_m, tile_n)) return;   // whole workgroup leaves before any barrier
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
     const int64_t kend = (kbeg + g.k_per_split < g.K) ? kbeg + g.k_per_split : g.K;
     const T *A = static_cast<const T *>(g.A);
@@ -93,20 +130,28 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
 
     typedef TileLoader<T, TA ? KT : BM, TA ? BM : KT> LoadA;
     typedef TileLoader<T, TB ? BN : KT, TB ? KT : BN> LoadB;
-    LoadA la;
-    LoadB lb;
-    auto fetch = [&](int64_t k0) {
-        if (TA) la.load(A, g.lda, k0, m0, kend, g.M, g.vecA); else la.load(A, g.lda, m0, k0, g.M, kend, g.vecA);
-        if (TB) lb.load(B, g.ldb, n0, k0, g.N, kend, g.vecB); else lb.load(B, g.ldb, k0, n0, kend, g.N, g.vecB);
+    // Register stages: the loads of k-tile t + STAGES are issued while tile t is multiplied.
+    constexpr int STAGES = 1;
+    LoadA la[STAGES];
+    LoadB lb[STAGES];
+    auto fetch = [&](LoadA &sa, LoadB &sb, int64_t k0) {
+        if (TA) sa.load(A, g.lda, k0, m0, kend, g.M, VA); else sa.load(A, g.lda, m0, k0, g.M, kend, VA);
+        if (TB) sb.load(B, g.ldb, n0, k0, g.N, kend, VB); else sb.load(B, g.ldb, k0, n0, kend, g.N, VB);
     };
+#pragma unroll
+    for (int st = 0; st < STAGES; ++st)
+        if (kbeg + st * KT < kend) fetch(la[st], lb[st], kbeg + st * KT);
 
-    if (kbeg < kend) fetch(kbeg);
-    for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
+    for (int64_t kb = kbeg; kb < kend; kb += STAGES * KT) {
+#pragma unroll
+      for (int st = 0; st < STAGES; ++st) {     // unrolled: every stage is addressed statically
+        const int64_t k0 = kb + st * KT;
+        if (k0 >= kend) break;
         __syncthreads();                      // previous tile fully consumed
-        la.template store<ASTR>(As);
-        lb.template store<BSTR>(Bs);
+        la[st].template store<ASTR>(As);
+        lb[st].template store<BSTR>(Bs);
         __syncthreads();
-        if (k0 + KT < kend) fetch(k0 + KT);   // overlaps the MFMA work below
+        if (k0 + STAGES * KT < kend) fetch(la[st], lb[st], k0 + STAGES * KT);
 
         if constexpr (sizeof(T) == 4) {
             // fp32: v_mfma_f32_32x32x2f32.  Lane half h owns k = h*16 + t of the tile at step t;
@@ -152,7 +197,7 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
         } else {
             // bf16: v_mfma_f32_32x32x16_bf16.  Lane half h supplies k = s*16 + h*8 .. +7.
 #pragma unroll
-            for (int s = 0; s < 2; ++s) {
+            for (int s = 0; s < KT / 16; ++s) {
                 bf16x8 af[TM], bf[TN];
                 const int kk = s * 16 + h * 8;
 #pragma unroll
@@ -186,9 +231,12 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
                         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[b], acc[a][b], 0, 0, 0);
             }
         }
+      }
     }
 
-    gemm_epilogue<TM, TN>(g, acc, m0 + wm * TM * 32, n0 + wn * TN * 32, l32, h);
+    __syncthreads();   // every wavefront is done reading the operand tiles
+    gemm_epilogue<TM, TN>(g, acc, m0 + wm * TM * 32, n0 + wn * TN * 32, l32, h,
+                          reinterpret_cast<float *>(smem) + wave * GEMM_STAGE_FLOATS(TN));
 }
 
 // C = act(sum_z P[z] + C_in + bias), partials added in z order
@@ -243,10 +291,20 @@ SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
 template <typename T, bool TA, bool TB>
 gt_status launch_gemm(GemmArgs g, int splits, hipStream_t st) {
     const int64_t bn = pick_bn(g.N), bm = pick_bm(bn);
-    dim3 grid((unsigned)((g.N + bn - 1) / bn), (unsigned)((g.M + bm - 1) / bm), (unsigned)splits);
-    if (bn == 128) k_gemm<T, TA, TB, 2, 2, 2, 2><<<grid, 256, 0, st>>>(g);
-    else if (bn == 64) k_gemm<T, TA, TB, 4, 1, 2, 2><<<grid, 256, 0, st>>>(g);
-    else k_gemm<T, TA, TB, 4, 1, 2, 1><<<grid, 256, 0, st>>>(g);
+    g.ntn = (int)((g.N + bn - 1) / bn);
+    g.ntm = (int)((g.M + bm - 1) / bm);
+    dim3 grid(gemm_grid_x(g.ntm, g.ntn), 1, (unsigned)splits);
+#define GT_GEMM_CFG(VA_, VB_)                                                                         \
+    do {                                                                                             \
+        if (bn == 128) k_gemm<T, TA, TB, 2, 2, 2, 2, VA_, VB_><<<grid, 256, 0, st>>>(g);             \
+        else if (bn == 64) k_gemm<T, TA, TB, 4, 1, 2, 2, VA_, VB_><<<grid, 256, 0, st>>>(g);         \
+        else k_gemm<T, TA, TB, 4, 1, 2, 1, VA_, VB_><<<grid, 256, 0, st>>>(g);                       \
+    } while (0)
+    if (g.vecA && g.vecB) GT_GEMM_CFG(true, true);
+    else if (g.vecA) GT_GEMM_CFG(true, false);
+    else if (g.vecB) GT_GEMM_CFG(false, true);
+    else GT_GEMM_CFG(false, false);
+#undef GT_GEMM_CFG
     GT_LAUNCH_CHECK("k_gemm");
     return GT_OK;
 }

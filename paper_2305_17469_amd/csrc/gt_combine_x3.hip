@@ -51,19 +51,29 @@ __device__ inline void store_run4(gemm_bf16_t *lds, int row, int k, float x0, fl
     *reinterpret_cast<uint2 *>(p + 2 * PLANE) = make_uint2((l[0] >> 16) | l[1], (l[2] >> 16) | l[3]);
 }
 
-__device__ inline float4 load4(const float *p, int64_t off, int64_t c, int64_t clim, bool row_ok, int vec) {
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (row_ok && c < clim) {
-        const float *s = p + off;
-        if (vec && c + 4 <= clim) {
-            v = *reinterpret_cast<const float4 *>(s);
-        } else {
-            v.x = s[0];
-            if (c + 1 < clim) v.y = s[1];
-            if (c + 2 < clim) v.z = s[2];
-            if (c + 3 < clim) v.w = s[3];
-        }
+// Four consecutive elements at p[off..off+3] (position c of a row that ends at clim).  Branch
+// free: an out-of-range request reads the (always valid) start of the matrix; `nv` receives the
+// number of elements that are real, and mask4 zeroes the rest when the data is consumed (masking at
+// load time would wait for the data and stall the prefetch).  `vec` is grid-uniform.
+__device__ inline float4 load4(const float *p, int64_t off, int64_t c, int64_t clim, bool row_ok, int vec, int &nv) {
+    const bool ok = row_ok && c < clim;
+    nv = ok ? (int)((clim - c) < 4 ? (clim - c) : 4) : 0;
+    float4 v;
+    if (vec) {
+        v = *reinterpret_cast<const float4 *>(p + (ok ? off : 0));
+    } else {
+        v.x = p[nv > 0 ? off : 0];
+        v.y = p[nv > 1 ? off + 1 : 0];
+        v.z = p[nv > 2 ? off + 2 : 0];
+        v.w = p[nv > 3 ? off + 3 : 0];
     }
+    return v;
+}
+__device__ inline float4 mask4(float4 v, int nv) {
+    v.x = nv > 0 ? v.x : 0.0f;
+    v.y = nv > 1 ? v.y : 0.0f;
+    v.z = nv > 2 ? v.z : 0.0f;
+    v.w = nv > 3 ? v.w : 0.0f;
     return v;
 }
 
@@ -71,20 +81,22 @@ __device__ inline float4 load4(const float *p, int64_t off, int64_t c, int64_t c
 // p[(i0 + i) * ld + k0 + k].  Four float4 per thread, lanes run along k first.
 struct LoadKC {
     float4 r[4];
+    int nv[4];
     __device__ inline void load(const float *p, int64_t ld, int64_t i0, int64_t k0, int64_t ilim, int64_t klim, int vec) {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int u = threadIdx.x + 256 * it;
             const int i = u >> 3, kq = u & 7;
             const int64_t gi = i0 + i, gk = k0 + kq * 4;
-            r[it] = load4(p, gi * ld + gk, gk, klim, gi < ilim, vec);
+            r[it] = load4(p, gi * ld + gk, gk, klim, gi < ilim, vec, nv[it]);
         }
     }
     __device__ inline void store(gemm_bf16_t *lds) const {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int u = threadIdx.x + 256 * it;
-            store_run4(lds, u >> 3, (u & 7) * 4, r[it].x, r[it].y, r[it].z, r[it].w);
+            const float4 v = mask4(r[it], nv[it]);
+            store_run4(lds, u >> 3, (u & 7) * 4, v.x, v.y, v.z, v.w);
         }
     }
 };
@@ -93,31 +105,37 @@ struct LoadKC {
 // p[(k0 + k) * ld + i0 + i].  One 4(k) x 4(i) patch per thread, transposed in registers.
 struct LoadKM {
     float4 r[4];   // r[dk] = rows i..i+3 at k + dk
+    int nv[4];
     __device__ inline void load(const float *p, int64_t ld, int64_t i0, int64_t k0, int64_t ilim, int64_t klim, int vec) {
         const int kq = threadIdx.x & 7, iq = threadIdx.x >> 3;
 #pragma unroll
         for (int dk = 0; dk < 4; ++dk) {
             const int64_t gk = k0 + kq * 4 + dk, gi = i0 + iq * 4;
-            r[dk] = load4(p, gk * ld + gi, gi, ilim, gk < klim, vec);
+            r[dk] = load4(p, gk * ld + gi, gi, ilim, gk < klim, vec, nv[dk]);
         }
     }
     __device__ inline void store(gemm_bf16_t *lds) const {
         const int kq = threadIdx.x & 7, iq = threadIdx.x >> 3;
-        store_run4(lds, iq * 4 + 0, kq * 4, r[0].x, r[1].x, r[2].x, r[3].x);
-        store_run4(lds, iq * 4 + 1, kq * 4, r[0].y, r[1].y, r[2].y, r[3].y);
-        store_run4(lds, iq * 4 + 2, kq * 4, r[0].z, r[1].z, r[2].z, r[3].z);
-        store_run4(lds, iq * 4 + 3, kq * 4, r[0].w, r[1].w, r[2].w, r[3].w);
+        const float4 a = mask4(r[0], nv[0]), b = mask4(r[1], nv[1]), c = mask4(r[2], nv[2]), d = mask4(r[3], nv[3]);
+        store_run4(lds, iq * 4 + 0, kq * 4, a.x, b.x, c.x, d.x);
+        store_run4(lds, iq * 4 + 1, kq * 4, a.y, b.y, c.y, d.y);
+        store_run4(lds, iq * 4 + 2, kq * 4, a.z, b.z, c.z, d.z);
+        store_run4(lds, iq * 4 + 3, kq * 4, a.w, b.w, c.w, d.w);
     }
 };
 
-template <bool TA, bool TB>
+template <bool TA, bool TB, bool VA, bool VB>
 __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
-    __shared__ __attribute__((aligned(16))) gemm_bf16_t As[3 * PLANE];
-    __shared__ __attribute__((aligned(16))) gemm_bf16_t Bs[3 * PLANE];
+    // one LDS buffer: operand planes during the k-loop, the per-wavefront output stages afterwards
+    __shared__ __attribute__((aligned(16))) gemm_bf16_t smem[6 * PLANE];
+    static_assert(6 * PLANE * 2 >= 4 * GEMM_STAGE_FLOATS(2) * 4, "output stages must fit");
+    gemm_bf16_t *As = smem, *Bs = smem + 3 * PLANE;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, h = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
-    const int64_t m0 = (int64_t)blockIdx.y * BM, n0 = (int64_t)blockIdx.x * BN;
+    int tile_m, tile_n;
+    if (!gemm_tile_of_block(g, tile_m, tile_n)) return;   // whole workgroup leaves before any barrier
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
     const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
     const int64_t kend = (kbeg + g.k_per_split < g.K) ? kbeg + g.k_per_split : g.K;
     const float *A = static_cast<const float *>(g.A);
@@ -135,8 +153,8 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
     typename std::conditional<TA, LoadKM, LoadKC>::type la;
     typename std::conditional<TB, LoadKC, LoadKM>::type lb;
     if (kbeg < kend) {
-        la.load(A, g.lda, m0, kbeg, g.M, kend, g.vecA);
-        lb.load(B, g.ldb, n0, kbeg, g.N, kend, g.vecB);
+        la.load(A, g.lda, m0, kbeg, g.M, kend, VA);
+        lb.load(B, g.ldb, n0, kbeg, g.N, kend, VB);
     }
     // One register stage: the loads of k-tile t+1 are in flight while tile t is multiplied.  (Two
     // stages were measured slower on MI355X: the extra registers halve the occupancy.)
@@ -146,8 +164,8 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
         lb.store(Bs);
         __syncthreads();
         if (k0 + KT < kend) {
-            la.load(A, g.lda, m0, k0 + KT, g.M, kend, g.vecA);
-            lb.load(B, g.ldb, n0, k0 + KT, g.N, kend, g.vecB);
+            la.load(A, g.lda, m0, k0 + KT, g.M, kend, VA);
+            lb.load(B, g.ldb, n0, k0 + KT, g.N, kend, VB);
         }
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
@@ -183,17 +201,30 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
                 }
         }
     }
-    gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h);
+    __syncthreads();   // every wavefront is done reading the operand planes
+    gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h,
+                        reinterpret_cast<float *>(smem) + wave * GEMM_STAGE_FLOATS(2));
 }
 
 }  // namespace
 
-gt_status gt_gemm_x3_launch(const GemmArgs &g, int transA, int transB, int splits, hipStream_t st) {
-    dim3 grid((unsigned)((g.N + BN - 1) / BN), (unsigned)((g.M + BM - 1) / BM), (unsigned)splits);
-    if (!transA && !transB) k_gemm_x3<false, false><<<grid, 256, 0, st>>>(g);
-    else if (!transA && transB) k_gemm_x3<false, true><<<grid, 256, 0, st>>>(g);
-    else if (transA && !transB) k_gemm_x3<true, false><<<grid, 256, 0, st>>>(g);
-    else k_gemm_x3<true, true><<<grid, 256, 0, st>>>(g);
+gt_status gt_gemm_x3_launch(const GemmArgs &g_in, int transA, int transB, int splits, hipStream_t st) {
+    GemmArgs g = g_in;
+    g.ntn = (int)((g.N + BN - 1) / BN);
+    g.ntm = (int)((g.M + BM - 1) / BM);
+    dim3 grid(gemm_grid_x(g.ntm, g.ntn), 1, (unsigned)splits);
+#define GT_X3(TA_, TB_)                                                                       \
+    do {                                                                                      \
+        if (g.vecA && g.vecB) k_gemm_x3<TA_, TB_, true, true><<<grid, 256, 0, st>>>(g);       \
+        else if (g.vecA) k_gemm_x3<TA_, TB_, true, false><<<grid, 256, 0, st>>>(g);           \
+        else if (g.vecB) k_gemm_x3<TA_, TB_, false, true><<<grid, 256, 0, st>>>(g);           \
+        else k_gemm_x3<TA_, TB_, false, false><<<grid, 256, 0, st>>>(g);                      \
+    } while (0)
+    if (!transA && !transB) GT_X3(false, false);
+    else if (!transA && transB) GT_X3(false, true);
+    else if (transA && !transB) GT_X3(true, false);
+    else GT_X3(true, true);
+#undef GT_X3
     GT_LAUNCH_CHECK("k_gemm_x3");
     return GT_OK;
 }
