@@ -48,7 +48,7 @@ template <typename T> __device__ inline void stf(T *p, float v);
 template <> __device__ inline void stf<float>(float *p, float v) { *p = v; }
 template <> __device__ inline void stf<bf16_t>(bf16_t *p, float v) { *p = (bf16_t)f32_to_bf16(v); }
 
-constexpr int CS_ROWS = 128;   // rows per workgroup of the column-sum kernels
+constexpr int CS_ROWS = 512;   // rows per workgroup of the column-sum kernels
 
 // dZ = dY * [Y > 0] (or dY when Y is null) and per-workgroup column sums of dZ.
 // One workgroup covers CS_ROWS rows.  Its 256 threads form cw column lanes x 256/cw row lanes
@@ -84,6 +84,85 @@ __global__ void __launch_bounds__(256) k_mask_colsum(const T *dY, int64_t lddy, 
                 float t = 0.0f;
                 for (int k = 0; k < rl_count; ++k) t += red[k * cw + cl];
                 partial[(int64_t)blockIdx.x * cols + c] = t;
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// 16-byte variant of k_mask_colsum for aligned, padded rows: a thread owns VE consecutive columns
+// of every (256/cv)-th row; loads and stores are full vectors (padding columns are read and, in
+// dZ, written; they never enter a sum that is stored).  Same fixed summation order as above.
+template <typename T> struct MaskVec;
+template <> struct MaskVec<float> {
+    static constexpr int VE = 4;
+    __device__ static void unpack(const uint4 &v, float (&o)[4]) {
+        o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y); o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
+    }
+    __device__ static uint4 pack(const float (&o)[4]) {
+        return make_uint4(__float_as_uint(o[0]), __float_as_uint(o[1]), __float_as_uint(o[2]), __float_as_uint(o[3]));
+    }
+};
+template <> struct MaskVec<bf16_t> {
+    static constexpr int VE = 8;
+    __device__ static void unpack(const uint4 &v, float (&o)[8]) {
+        o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
+        o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
+        o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xffff0000u);
+        o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+    __device__ static uint4 pack(const float (&o)[8]) {   // values are bf16 already: exact
+        return make_uint4((__float_as_uint(o[0]) >> 16) | (__float_as_uint(o[1]) & 0xffff0000u),
+                          (__float_as_uint(o[2]) >> 16) | (__float_as_uint(o[3]) & 0xffff0000u),
+                          (__float_as_uint(o[4]) >> 16) | (__float_as_uint(o[5]) & 0xffff0000u),
+                          (__float_as_uint(o[6]) >> 16) | (__float_as_uint(o[7]) & 0xffff0000u));
+    }
+};
+
+template <typename T>
+__global__ void __launch_bounds__(256) k_mask_colsum_vec(const T *dY, int64_t lddy, const T *Y, int64_t ldy, T *dZ,
+                                                         int64_t lddz, int64_t rows, int64_t cols, int cv,
+                                                         float *partial) {
+    constexpr int VE = MaskVec<T>::VE;
+    __shared__ float red[256 * VE];
+    const int rl_count = 256 / cv;
+    const int cl = threadIdx.x % cv, rl = threadIdx.x / cv;
+    const int64_t r0 = (int64_t)blockIdx.x * CS_ROWS;
+    const int64_t r1 = r0 + CS_ROWS < rows ? r0 + CS_ROWS : rows;
+    const int64_t nvec = (cols + VE - 1) / VE;
+    for (int64_t v0 = 0; v0 < nvec; v0 += cv) {
+        const int64_t vi = v0 + cl;
+        const int64_t c = vi * VE;
+        float s[VE];
+#pragma unroll
+        for (int e = 0; e < VE; ++e) s[e] = 0.0f;
+        if (vi < nvec) {
+#pragma unroll 4
+            for (int64_t r = r0 + rl; r < r1; r += rl_count) {
+                float g[VE];
+                MaskVec<T>::unpack(*reinterpret_cast<const uint4 *>(dY + r * lddy + c), g);
+                if (Y) {
+                    float y[VE];
+                    MaskVec<T>::unpack(*reinterpret_cast<const uint4 *>(Y + r * ldy + c), y);
+#pragma unroll
+                    for (int e = 0; e < VE; ++e) g[e] = y[e] > 0.0f ? g[e] : 0.0f;
+                    *reinterpret_cast<uint4 *>(dZ + r * lddz + c) = MaskVec<T>::pack(g);
+                }
+#pragma unroll
+                for (int e = 0; e < VE; ++e) s[e] += g[e];
+            }
+        }
+        if (partial) {
+#pragma unroll
+            for (int e = 0; e < VE; ++e) red[threadIdx.x * VE + e] = s[e];
+            __syncthreads();
+            if (rl == 0 && vi < nvec) {
+#pragma unroll
+                for (int e = 0; e < VE; ++e) {
+                    float t = 0.0f;
+                    for (int k = 0; k < rl_count; ++k) t += red[(k * cv + cl) * VE + e];
+                    if (c + e < cols) partial[(int64_t)blockIdx.x * cols + c + e] = t;
+                }
             }
             __syncthreads();
         }
@@ -215,10 +294,21 @@ gt_status mask_colsum(const void *dY, int64_t lddy, const void *Y, int64_t ldy, 
         return GT_OK;
     }
     const int64_t nblk = (rows + CS_ROWS - 1) / CS_ROWS;
-    int cw = 16;
-    while (cw < 256 && cw < cols) cw <<= 1;
-    k_mask_colsum<T><<<(unsigned)nblk, 256, 0, st>>>(static_cast<const T *>(dY), lddy, static_cast<const T *>(Y), ldy,
-                                                     static_cast<T *>(dZ), lddz, rows, cols, cw, db ? partial : nullptr);
+    constexpr int VE = MaskVec<T>::VE;
+    const bool vec = (((uintptr_t)dY | (uintptr_t)Y | (uintptr_t)dZ) & 15) == 0 && lddy % VE == 0 &&
+                     (!Y || (ldy % VE == 0 && lddz % VE == 0));
+    if (vec) {
+        int cv = 4;
+        while (cv < 256 && cv * VE < cols) cv <<= 1;
+        k_mask_colsum_vec<T><<<(unsigned)nblk, 256, 0, st>>>(static_cast<const T *>(dY), lddy, static_cast<const T *>(Y),
+                                                             ldy, static_cast<T *>(dZ), lddz, rows, cols, cv,
+                                                             db ? partial : nullptr);
+    } else {
+        int cw = 16;
+        while (cw < 256 && cw < cols) cw <<= 1;
+        k_mask_colsum<T><<<(unsigned)nblk, 256, 0, st>>>(static_cast<const T *>(dY), lddy, static_cast<const T *>(Y), ldy,
+                                                         static_cast<T *>(dZ), lddz, rows, cols, cw, db ? partial : nullptr);
+    }
     GT_LAUNCH_CHECK("k_mask_colsum");
     if (db) {
         k_colsum_final<<<(unsigned)((cols + 15) / 16), 256, 0, st>>>(partial, nblk, cols, db);
