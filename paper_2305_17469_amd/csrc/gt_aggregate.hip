@@ -276,14 +276,38 @@ __global__ void __launch_bounds__(256) k_reduce_partials(const AggArgs a) {
     for (int p = 0; p < NP; ++p)
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[p][i] = 0.0f;
-    for (int k = 0; k < s.count; ++k) {
-        const float *P = a.partials + (int64_t)(s.first + k) * a.ldp;
+    // Four partial rows are requested at a time (branch free: a request past the end re-reads the
+    // last row and is discarded) and added in chunk order.  Partial rows are padded to a multiple
+    // of 8 floats, so whole vectors can be read; padding lanes are never stored.
+    for (int k = 0; k < s.count; k += 4) {
+        float t[4][NP][V];
 #pragma unroll
-        for (int p = 0; p < NP; ++p) {
-            const int64_t col = col0 + (int64_t)(p * G + gl) * V;
+        for (int u = 0; u < 4; ++u) {
+            const int kk = (k + u < s.count) ? k + u : s.count - 1;
+            const float *P = a.partials + (int64_t)(s.first + kk) * a.ldp;
 #pragma unroll
-            for (int i = 0; i < V; ++i)
-                if (col + i < a.F) acc[p][i] += P[col + i];
+            for (int p = 0; p < NP; ++p) {
+                const int64_t col = col0 + (int64_t)(p * G + gl) * V;
+                const int64_t c = col < a.F ? col : 0;
+                if constexpr (V == 1) {
+                    t[u][p][0] = P[c];
+                } else {
+#pragma unroll
+                    for (int q = 0; q < V / 4; ++q) {
+                        const float4 x = *reinterpret_cast<const float4 *>(P + c + 4 * q);
+                        t[u][p][4 * q + 0] = x.x; t[u][p][4 * q + 1] = x.y;
+                        t[u][p][4 * q + 2] = x.z; t[u][p][4 * q + 3] = x.w;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const bool live = k + u < s.count;
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int i = 0; i < V; ++i) acc[p][i] += live ? t[u][p][i] : 0.0f;
         }
     }
     finish_row<T, V, G, NP>(a, s.row, gl, col0, acc);
