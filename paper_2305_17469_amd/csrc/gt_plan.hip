@@ -320,8 +320,18 @@ __device__ inline uint32_t length_key(int32_t len) {
     return 255u - k;
 }
 
-__global__ void k_fill_items(const int32_t *rowptr, int64_t n_rows, int chunk, const int32_t *o_items, const int32_t *o_parts,
-                             const int32_t *o_splits, gt_item *items, uint32_t *keys, gt_split *splits) {
+// Sort key of an item: length class (longest first) in bits 8-15, then the range its first
+// neighbour id falls in (256 ranges) in bits 0-7, so that items running at the same time gather
+// from the same region of the table and reuse each other's rows in the L2.
+__device__ inline uint32_t item_key(int32_t len, const int32_t *nbr, int32_t e0, int64_t n_in) {
+    uint32_t loc = 0;
+    if (len > 0 && n_in > 0) loc = (uint32_t)(((int64_t)nbr[e0] << 8) / n_in) & 255u;
+    return (length_key(len) << 8) | loc;
+}
+
+__global__ void k_fill_items(const int32_t *rowptr, const int32_t *nbr, int64_t n_in, int64_t n_rows, int chunk,
+                             const int32_t *o_items, const int32_t *o_parts, const int32_t *o_splits, gt_item *items,
+                             uint32_t *keys, gt_split *splits) {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= n_rows) return;
     const int32_t b = rowptr[r], e = rowptr[r + 1], d = e - b;
@@ -339,13 +349,13 @@ __global__ void k_fill_items(const int32_t *rowptr, int64_t n_rows, int chunk, c
             x.e1 = min(e, x.e0 + chunk);
             x.slot = p0 + c;
             items[it + c] = x;
-            keys[it + c] = length_key(x.e1 - x.e0);
+            keys[it + c] = item_key(x.e1 - x.e0, nbr, x.e0, n_in);
         }
     } else {
         gt_item x;
         x.row = (int32_t)r; x.e0 = b; x.e1 = e; x.slot = -1;
         items[it] = x;
-        keys[it] = length_key(d);
+        keys[it] = item_key(d, nbr, b, n_in);
     }
 }
 
@@ -373,7 +383,7 @@ struct PlanLayout {
     size_t items_f, splits_f, items_b, splits_b;
     size_t counts;                       // 8 int32 read back by the host
     size_t ca, cb, cc;                   // per-row count arrays (max(n_dst, n_src) + 1 each)
-    size_t items_tmp, item_keys, item_keys2, item_idx;   // unsorted items, sort keys / indices
+    size_t items_tmp, item_keys, item_keys2, item_idx, item_idx2;   // unsorted items, sort keys / indices
     size_t k0, v0, k1, v1;               // sort ping-pong (E each); k0, v0, v1 hold the coefficient arrays afterwards
     size_t hist, scan_tmp;
     size_t total;
@@ -408,6 +418,7 @@ PlanLayout plan_layout(int64_t n_dst, int64_t n_src, int64_t E, bool has_ew) {
     L.item_keys = take((size_t)imax * 4);
     L.item_keys2 = take((size_t)imax * 4);
     L.item_idx = take((size_t)imax * 4);
+    L.item_idx2 = take((size_t)imax * 4);
     L.k0 = take((size_t)E * 4);
     L.v0 = take((size_t)E * 4);
     L.k1 = take((size_t)E * 4);
@@ -448,19 +459,22 @@ gt_status count_direction(const int32_t *rowptr, int64_t n_rows, int chunk, void
 }
 
 // items of one direction, sorted longest first (stable, so equal lengths keep row order).
-gt_status build_direction(const int32_t *rowptr, int64_t n_rows, int chunk, int64_t n_items, void *ws,
-                          const PlanLayout &L, gt_item *items_out, gt_split *splits_out, hipStream_t st) {
+gt_status build_direction(const int32_t *rowptr, const int32_t *nbr, int64_t n_in, int64_t n_rows, int chunk,
+                          int64_t n_items, void *ws, const PlanLayout &L, gt_item *items_out, gt_split *splits_out,
+                          hipStream_t st) {
     if (n_rows <= 0 || n_items <= 0) return GT_OK;
     int32_t *ca = at<int32_t>(ws, L.ca), *cb = at<int32_t>(ws, L.cb), *cc = at<int32_t>(ws, L.cc);
     gt_item *tmp = at<gt_item>(ws, L.items_tmp);
     uint32_t *keys = at<uint32_t>(ws, L.item_keys), *keys2 = at<uint32_t>(ws, L.item_keys2);
-    uint32_t *idx = at<uint32_t>(ws, L.item_idx);
-    k_fill_items<<<nblocks(n_rows), PT, 0, st>>>(rowptr, n_rows, chunk, ca, cb, cc, tmp, keys, splits_out);
+    uint32_t *idx = at<uint32_t>(ws, L.item_idx), *idx2 = at<uint32_t>(ws, L.item_idx2);
+    k_fill_items<<<nblocks(n_rows), PT, 0, st>>>(rowptr, nbr, n_in, n_rows, chunk, ca, cb, cc, tmp, keys, splits_out);
     GT_LAUNCH_CHECK("k_fill_items");
     SortTmp t{at<int32_t>(ws, L.hist), at<int32_t>(ws, L.scan_tmp)};
-    gt_status s = radix_pass(keys, nullptr, keys2, idx, n_items, 0, t, st);
+    gt_status s = radix_pass(keys, nullptr, keys2, idx, n_items, 0, t, st);      // neighbour range
     if (s != GT_OK) return s;
-    k_gather_items<<<nblocks(n_items), PT, 0, st>>>(tmp, idx, n_items, items_out);
+    s = radix_pass(keys2, idx, keys, idx2, n_items, 8, t, st);                   // length class (stable)
+    if (s != GT_OK) return s;
+    k_gather_items<<<nblocks(n_items), PT, 0, st>>>(tmp, idx2, n_items, items_out);
     GT_LAUNCH_CHECK("k_gather_items");
     return GT_OK;
 }
@@ -572,7 +586,7 @@ extern "C" gt_status gt_graph_create(gt_graph **out, int64_t n_dst, int64_t n_sr
     g->fwd.items = at<gt_item>(ws, L.items_f); g->fwd.splits = at<gt_split>(ws, L.splits_f);
     if (g->fwd.n_items > max_items(n_dst, E) || g->fwd.n_splits > max_splits(E))
         return fail(gt_fail(GT_ERR_INTERNAL, "gt_graph_create: forward work list exceeds its bound (is rowptr valid?)"));
-    if ((s = build_direction(rowptr, n_dst, g->chunk, g->fwd.n_items, ws, L, at<gt_item>(ws, L.items_f),
+    if ((s = build_direction(rowptr, colidx, n_src, n_dst, g->chunk, g->fwd.n_items, ws, L, at<gt_item>(ws, L.items_f),
                              at<gt_split>(ws, L.splits_f), st)) != GT_OK) return fail(s);
 
     if ((s = count_direction(g->rowptr_t, n_src, g->chunk, ws, L, d_counts + 4, st)) != GT_OK) return fail(s);
@@ -584,7 +598,7 @@ extern "C" gt_status gt_graph_create(gt_graph **out, int64_t n_dst, int64_t n_sr
     g->bwd.items = at<gt_item>(ws, L.items_b); g->bwd.splits = at<gt_split>(ws, L.splits_b);
     if (g->bwd.n_items > max_items(n_src, E) || g->bwd.n_splits > max_splits(E))
         return fail(gt_fail(GT_ERR_INTERNAL, "gt_graph_create: transposed work list exceeds its bound"));
-    if ((s = build_direction(g->rowptr_t, n_src, g->chunk, g->bwd.n_items, ws, L, at<gt_item>(ws, L.items_b),
+    if ((s = build_direction(g->rowptr_t, g->colidx_t, n_dst, n_src, g->chunk, g->bwd.n_items, ws, L, at<gt_item>(ws, L.items_b),
                              at<gt_split>(ws, L.splits_b), st)) != GT_OK) return fail(s);
     PLAN_HIP(hipStreamSynchronize(st));
 #undef PLAN_HIP
