@@ -144,6 +144,60 @@ def round_bf16(x):
     return y
 
 
+EDGE_FN = {"dot": 0, "mul": 1}
+WEIGHT_FN = {"scale": 0, "add": 1, "mul": 2}
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def neighbor_apply(rowptr, colidx, Xs, Xd, g="mul"):
+    """Edge weights W = g(Xs[src], Xd[dst]) per edge: [E] for 'dot', [E, F] for 'mul'."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    Xs, Xd = _f64(Xs), _f64(Xd)
+    n_dst, F = rowptr.size - 1, Xs.shape[1]
+    assert Xd.shape == (n_dst, F)
+    W = np.empty(colidx.size if g == "dot" else (colidx.size, F), dtype=np.float64)
+    lib().gto_neighbor_apply(ctypes.c_int64(n_dst), _p(rowptr), _p(colidx), ctypes.c_int(EDGE_FN[g]), ctypes.c_int64(F),
+                             _p(Xs), _p(Xd), _p(W))
+    return W
+
+
+def neighbor_apply_bwd(rowptr, colidx, dW, Xs, Xd, g="mul"):
+    """(dXs, dXd) for upstream dW."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    Xs, Xd, dW = _f64(Xs), _f64(Xd), _f64(dW)
+    n_dst, (n_src, F) = rowptr.size - 1, Xs.shape
+    dXs, dXd = np.empty((n_src, F)), np.empty((n_dst, F))
+    lib().gto_neighbor_apply_bwd(ctypes.c_int64(n_dst), ctypes.c_int64(n_src), _p(rowptr), _p(colidx),
+                                 ctypes.c_int(EDGE_FN[g]), ctypes.c_int64(F), _p(dW), _p(Xs), _p(Xd), _p(dXs), _p(dXd))
+    return dXs, dXd
+
+
+def pull(rowptr, colidx, Xs, W, reduce="mean", h="add"):
+    """Y[v] = f over in-edges of h(Xs[src], W_e); reduce in {'sum','mean'}."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    Xs, W = _f64(Xs), _f64(W)
+    n_dst, F = rowptr.size - 1, Xs.shape[1]
+    Y = np.empty((n_dst, F))
+    lib().gto_pull(ctypes.c_int64(n_dst), _p(rowptr), _p(colidx), ctypes.c_int(int(reduce == "mean")),
+                   ctypes.c_int(WEIGHT_FN[h]), ctypes.c_int64(F), _p(Xs), _p(W), _p(Y))
+    return Y
+
+
+def pull_bwd(rowptr, colidx, dY, Xs, W, reduce="mean", h="add"):
+    """(dXs, dW) for upstream dY."""
+    rowptr, colidx = _i32(rowptr), _i32(colidx)
+    Xs, W, dY = _f64(Xs), _f64(W), _f64(dY)
+    n_dst, (n_src, F) = rowptr.size - 1, Xs.shape
+    dXs, dW = np.empty((n_src, F)), np.empty_like(W)
+    lib().gto_pull_bwd(ctypes.c_int64(n_dst), ctypes.c_int64(n_src), _p(rowptr), _p(colidx),
+                       ctypes.c_int(int(reduce == "mean")), ctypes.c_int(WEIGHT_FN[h]), ctypes.c_int64(F), _p(dY),
+                       _p(Xs), _p(W), _p(dXs), _p(dW))
+    return dXs, dW
+
+
 # ------------------------------------------------------------------------------------------
 # Layers and models (fp64).  `blk` is a dict(rowptr, colidx, n_dst, n_src).
 # ------------------------------------------------------------------------------------------

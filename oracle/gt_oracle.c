@@ -174,6 +174,105 @@ void gto_combine(int64_t M, int64_t N, int64_t K, const double *A, int64_t lda, 
     }
 }
 
+/* ---------------------------------------------------------------------------------------------
+ * Edge weighting (paper: Preliminaries, "edge weighting": a function g of the source and
+ * destination embeddings per edge, and a function h that transforms the source embedding with
+ * g's output before the aggregation f; Frontend section: NeighborApply computes g, Pull applies
+ * h and f).  Edge e = (u -> v) is position e of the given CSR.
+ *   g:  GTO_G_DOT  w_e    = sum_f Xs[u,f] * Xd[v,f]      (scalar; the SDDMM (D D^T) o S of the paper)
+ *       GTO_G_MUL  w_e[f] = Xs[u,f] * Xd[v,f]            (vector; NGCF's element-wise product)
+ *   h:  GTO_H_SCALE  w_e * Xs[u]   (scalar weight),  GTO_H_ADD  Xs[u] + w_e,  GTO_H_MUL  Xs[u] (.) w_e
+ *   f:  sum or mean over the in-edges of v (mean divides by the in-degree; empty row -> 0).
+ * ------------------------------------------------------------------------------------------- */
+enum { GTO_G_DOT = 0, GTO_G_MUL = 1 };
+enum { GTO_H_SCALE = 0, GTO_H_ADD = 1, GTO_H_MUL = 2 };
+
+/* W: [E] for DOT, [E, F] (row stride F) for MUL */
+void gto_neighbor_apply(int64_t n_dst, const int32_t *rowptr, const int32_t *colidx, int g, int64_t F,
+                        const double *Xs, const double *Xd, double *W) {
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t v = 0; v < n_dst; ++v)
+        for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            int64_t u = colidx[e];
+            if (g == GTO_G_DOT) {
+                double acc = 0.0;
+                for (int64_t f = 0; f < F; ++f) acc += Xs[(size_t)u * F + f] * Xd[(size_t)v * F + f];
+                W[e] = acc;
+            } else {
+                for (int64_t f = 0; f < F; ++f) W[(size_t)e * F + f] = Xs[(size_t)u * F + f] * Xd[(size_t)v * F + f];
+            }
+        }
+}
+
+/* Derivative of g for upstream dW (same shape as W): edge by edge, applied to both ends
+ * (paper, "Training for GNNs": g' is applied for both dst and src nodes).
+ * dXs[n_src, F], dXd[n_dst, F] are overwritten. */
+void gto_neighbor_apply_bwd(int64_t n_dst, int64_t n_src, const int32_t *rowptr, const int32_t *colidx, int g,
+                            int64_t F, const double *dW, const double *Xs, const double *Xd, double *dXs,
+                            double *dXd) {
+    for (size_t i = 0; i < (size_t)n_src * F; ++i) dXs[i] = 0.0;
+    for (size_t i = 0; i < (size_t)n_dst * F; ++i) dXd[i] = 0.0;
+    for (int64_t v = 0; v < n_dst; ++v)
+        for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            int64_t u = colidx[e];
+            for (int64_t f = 0; f < F; ++f) {
+                double d = (g == GTO_G_DOT) ? dW[e] : dW[(size_t)e * F + f];
+                dXs[(size_t)u * F + f] += d * Xd[(size_t)v * F + f];
+                dXd[(size_t)v * F + f] += d * Xs[(size_t)u * F + f];
+            }
+        }
+}
+
+static double h_apply(int h, double x, const double *W, int64_t e, int64_t F, int64_t f) {
+    if (h == GTO_H_SCALE) return W[e] * x;
+    if (h == GTO_H_ADD) return x + W[(size_t)e * F + f];
+    return x * W[(size_t)e * F + f];
+}
+
+/* Y[v,:] = f_{e in in(v)} h(Xs[u,:], W_e);  mean != 0 divides by the in-degree */
+void gto_pull(int64_t n_dst, const int32_t *rowptr, const int32_t *colidx, int mean, int h, int64_t F,
+              const double *Xs, const double *W, double *Y) {
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t v = 0; v < n_dst; ++v) {
+        int32_t deg = rowptr[v + 1] - rowptr[v];
+        for (int64_t f = 0; f < F; ++f) {
+            double acc = 0.0;
+            for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e)
+                acc += h_apply(h, Xs[(size_t)colidx[e] * F + f], W, e, F, f);
+            if (mean) acc = deg > 0 ? acc / (double)deg : 0.0;
+            Y[(size_t)v * F + f] = acc;
+        }
+    }
+}
+
+/* Derivative of Pull for upstream dY: dXs[n_src,F] (scatter over the edges) and dW (shape of W). */
+void gto_pull_bwd(int64_t n_dst, int64_t n_src, const int32_t *rowptr, const int32_t *colidx, int mean, int h,
+                  int64_t F, const double *dY, const double *Xs, const double *W, double *dXs, double *dW) {
+    for (size_t i = 0; i < (size_t)n_src * F; ++i) dXs[i] = 0.0;
+    for (int64_t v = 0; v < n_dst; ++v) {
+        int32_t deg = rowptr[v + 1] - rowptr[v];
+        double c = mean ? 1.0 / (double)deg : 1.0;
+        for (int32_t e = rowptr[v]; e < rowptr[v + 1]; ++e) {
+            int64_t u = colidx[e];
+            if (h == GTO_H_SCALE) dW[e] = 0.0;
+            for (int64_t f = 0; f < F; ++f) {
+                double up = c * dY[(size_t)v * F + f];          /* d loss / d h(...)[f] */
+                double x = Xs[(size_t)u * F + f];
+                if (h == GTO_H_SCALE) {
+                    dXs[(size_t)u * F + f] += up * W[e];
+                    dW[e] += up * x;
+                } else if (h == GTO_H_ADD) {
+                    dXs[(size_t)u * F + f] += up;
+                    dW[(size_t)e * F + f] = up;
+                } else {
+                    dXs[(size_t)u * F + f] += up * W[(size_t)e * F + f];
+                    dW[(size_t)e * F + f] = up * x;
+                }
+            }
+        }
+    }
+}
+
 /* fp64 -> nearest bf16 value (ties to even), returned as fp64.  bf16 has 8 significant bits
  * and the fp32 exponent range; values below the smallest normal round on the subnormal grid. */
 void gto_round_bf16(int64_t n, const double *x, double *y) {
