@@ -134,6 +134,46 @@ gt_status gt_aggregate_bwd(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, 
                            void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Edge weighting: NeighborApply (the edge-weight function g of the source and destination
+ * embeddings per edge, i.e. SDDMM) and Pull with per-call edge weights (the function h that
+ * transforms the source embedding with g's output before the aggregation f); paper:
+ * Preliminaries "edge weighting", "Training for GNNs" (g' is applied to both ends), Frontend
+ * section (NeighborApply, Pull, the NGCF listing).  Edge e = (u -> v) is position e of the CSR the
+ * plan was built from; the plan must have been built WITHOUT static edge weights (UNSUPPORTED
+ * otherwise).  Xs[n_src, F], Xd[n_dst, F], Y / dY[n_dst, F], dXs[n_src, F], dXd[n_dst, F] in `dtype`.
+ * Scalar edge data (GT_G_DOT, GT_H_SCALE) is float[E]; vector edge data is [E, F] in `dtype`
+ * with row stride ldw.  ws as for gt_aggregate_fwd (gt_aggregate_ws_size(F)).
+ *   g: GT_G_DOT  w_e = <Xs[u], Xd[v]>,   GT_G_MUL  w_e = Xs[u] (.) Xd[v]
+ *   h: GT_H_SCALE  w_e * Xs[u],   GT_H_ADD  Xs[u] + w_e,   GT_H_MUL  Xs[u] (.) w_e
+ *   f: GT_SUM or GT_MEAN over the in-edges of v (GT_SYMNORM: UNSUPPORTED).
+ * ------------------------------------------------------------------------------------------ */
+typedef enum { GT_G_DOT = 0, GT_G_MUL = 1 } gt_edge_fn;
+typedef enum { GT_H_SCALE = 0, GT_H_ADD = 1, GT_H_MUL = 2 } gt_weight_fn;
+
+/* W_e = g(Xs[u], Xd[v]) for every edge. */
+gt_status gt_neighbor_apply_fwd(const gt_graph *g, gt_edge_fn fn, gt_dtype dtype, int64_t F,
+                                const void *Xs, int64_t ldxs, const void *Xd, int64_t ldxd,
+                                void *W, int64_t ldw, void *stream);
+
+/* dXs[u] = sum over out-edges, dXd[v] = sum over in-edges of the derivative of g for upstream dW
+ * (shape of W).  Both outputs are overwritten. */
+gt_status gt_neighbor_apply_bwd(const gt_graph *g, gt_edge_fn fn, gt_dtype dtype, int64_t F,
+                                const void *dW, int64_t lddw, const void *Xs, int64_t ldxs,
+                                const void *Xd, int64_t ldxd, void *dXs, int64_t lddxs,
+                                void *dXd, int64_t lddxd, void *ws, size_t ws_bytes, void *stream);
+
+/* Y[v] = f_{e in in(v)} h(Xs[u], W_e). */
+gt_status gt_pull_fwd(const gt_graph *g, gt_reduce reduce, gt_weight_fn h, gt_dtype dtype, int64_t F,
+                      const void *Xs, int64_t ldxs, const void *W, int64_t ldw, void *Y, int64_t ldy,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* dXs[n_src, F] and dW (shape of W) for upstream dY; both overwritten. */
+gt_status gt_pull_bwd(const gt_graph *g, gt_reduce reduce, gt_weight_fn h, gt_dtype dtype, int64_t F,
+                      const void *dY, int64_t lddy, const void *Xs, int64_t ldxs,
+                      const void *W, int64_t ldw, void *dXs, int64_t lddxs, void *dW, int64_t lddw,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * Combination (Apply): C[M,N] = act(op(A) op(B) + bias), op(A) is M x K, op(B) is K x N.
  *   transA = 0: A stored M x K (lda >= K);  transA = 1: A stored K x M (lda >= M).
  *   transB = 0: B stored K x N (ldb >= N);  transB = 1: B stored N x K (ldb >= K).

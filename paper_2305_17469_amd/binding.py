@@ -49,7 +49,7 @@ class GtError(RuntimeError):
 
 EXPORTS = ["gt_graph_plan_size", "gt_graph_create", "gt_graph_destroy", "gt_graph_outputs", "gt_graph_info",
            "gt_graph_validate", "gt_aggregate_ws_size", "gt_aggregate_fwd", "gt_aggregate_bwd", "gt_combine_ws_size",
-           "gt_combine", "gt_cost_get", "gt_cost_set", "gt_cost_benefits", "gt_layer_decide", "gt_layer_ws_size",
+           "gt_combine", "gt_neighbor_apply_fwd", "gt_neighbor_apply_bwd", "gt_pull_fwd", "gt_pull_bwd", "gt_cost_get", "gt_cost_set", "gt_cost_benefits", "gt_layer_decide", "gt_layer_ws_size",
            "gt_layer_fwd", "gt_layer_bwd", "gt_calibrate_ws_size", "gt_calibrate", "gt_trace_enable", "gt_trace_reset",
            "gt_trace_count", "gt_trace_get", "gt_status_string",
            "gt_last_error", "gt_version"]
@@ -73,6 +73,14 @@ lib.gt_aggregate_bwd.argtypes = _AGG
 lib.gt_combine_ws_size.argtypes = [c_int, c_int, c_int, c_int64, c_int64, c_int64, POINTER(c_size_t)]
 lib.gt_combine.argtypes = [c_int, c_int, c_int, c_int64, c_int64, c_int64, c_void_p, c_int64, c_void_p, c_int64,
                            c_void_p, c_int, c_void_p, c_int64, c_int, c_void_p, c_size_t, c_void_p]
+lib.gt_neighbor_apply_fwd.argtypes = [c_void_p, c_int, c_int, c_int64, c_void_p, c_int64, c_void_p, c_int64, c_void_p,
+                                      c_int64, c_void_p]
+lib.gt_neighbor_apply_bwd.argtypes = [c_void_p, c_int, c_int, c_int64, c_void_p, c_int64, c_void_p, c_int64, c_void_p,
+                                      c_int64, c_void_p, c_int64, c_void_p, c_int64, c_void_p, c_size_t, c_void_p]
+lib.gt_pull_fwd.argtypes = [c_void_p, c_int, c_int, c_int, c_int64, c_void_p, c_int64, c_void_p, c_int64, c_void_p,
+                            c_int64, c_void_p, c_size_t, c_void_p]
+lib.gt_pull_bwd.argtypes = [c_void_p, c_int, c_int, c_int, c_int64, c_void_p, c_int64, c_void_p, c_int64, c_void_p,
+                            c_int64, c_void_p, c_int64, c_void_p, c_int64, c_void_p, c_size_t, c_void_p]
 lib.gt_cost_get.argtypes = [POINTER(gt_cost_coeffs)]
 lib.gt_cost_set.argtypes = [POINTER(gt_cost_coeffs)]
 lib.gt_cost_benefits.argtypes = [POINTER(gt_cost_coeffs), c_int64, c_int64, c_int64, c_int64, c_int64, c_int] + \
@@ -216,6 +224,56 @@ def gt_combine(A, B, bias=None, relu=False, transA=False, transB=False, out=None
                           _ptr(bias), GT_ACT_RELU if relu else GT_ACT_NONE, _ptr(C), _rows2d(C), _dtype(C),
                           _ptr(ws), ws.numel(), _stream()))
     return C
+
+
+EDGE_FN = {"dot": 0, "mul": 1}
+WEIGHT_FN = {"scale": 0, "add": 1, "mul": 2}
+
+
+def _ld(t):
+    return t.stride(0) if t.dim() == 2 else 0
+
+
+def gt_neighbor_apply_fwd(g: Graph, fn, Xs, Xd, out=None):
+    """W_e = g(Xs[src], Xd[dst]): float32 [E] for 'dot', [E, F] of the input dtype for 'mul'."""
+    F = Xs.shape[1]
+    if out is None:
+        out = torch.empty((g.n_edges,), dtype=torch.float32, device=Xs.device) if fn == "dot" else \
+            torch.empty((g.n_edges, F), dtype=Xs.dtype, device=Xs.device)
+    _check(lib.gt_neighbor_apply_fwd(g.handle, EDGE_FN[fn], _dtype(Xs), F, _ptr(Xs), _rows2d(Xs), _ptr(Xd), _rows2d(Xd),
+                                     _ptr(out), _ld(out), _stream()))
+    return out
+
+
+def gt_neighbor_apply_bwd(g: Graph, fn, dW, Xs, Xd, out_dXs=None, out_dXd=None):
+    F = Xs.shape[1]
+    dXs = torch.empty((g.n_src, F), dtype=Xs.dtype, device=Xs.device) if out_dXs is None else out_dXs
+    dXd = torch.empty((g.n_dst, F), dtype=Xs.dtype, device=Xs.device) if out_dXd is None else out_dXd
+    ws = g.aggregate_ws(F)
+    _check(lib.gt_neighbor_apply_bwd(g.handle, EDGE_FN[fn], _dtype(Xs), F, _ptr(dW), _ld(dW), _ptr(Xs), _rows2d(Xs),
+                                     _ptr(Xd), _rows2d(Xd), _ptr(dXs), _rows2d(dXs), _ptr(dXd), _rows2d(dXd),
+                                     _ptr(ws), ws.numel(), _stream()))
+    return dXs, dXd
+
+
+def gt_pull_fwd(g: Graph, reduce, h, Xs, W, out=None):
+    F = Xs.shape[1]
+    Y = torch.empty((g.n_dst, F), dtype=Xs.dtype, device=Xs.device) if out is None else out
+    ws = g.aggregate_ws(F)
+    _check(lib.gt_pull_fwd(g.handle, REDUCE[reduce], WEIGHT_FN[h], _dtype(Xs), F, _ptr(Xs), _rows2d(Xs), _ptr(W), _ld(W),
+                           _ptr(Y), _rows2d(Y), _ptr(ws), ws.numel(), _stream()))
+    return Y
+
+
+def gt_pull_bwd(g: Graph, reduce, h, dY, Xs, W, out_dXs=None, out_dW=None):
+    F = Xs.shape[1]
+    dXs = torch.empty((g.n_src, F), dtype=Xs.dtype, device=Xs.device) if out_dXs is None else out_dXs
+    dW = torch.empty_like(W) if out_dW is None else out_dW
+    ws = g.aggregate_ws(F)
+    _check(lib.gt_pull_bwd(g.handle, REDUCE[reduce], WEIGHT_FN[h], _dtype(Xs), F, _ptr(dY), _rows2d(dY), _ptr(Xs),
+                           _rows2d(Xs), _ptr(W), _ld(W), _ptr(dXs), _rows2d(dXs), _ptr(dW), _ld(dW), _ptr(ws),
+                           ws.numel(), _stream()))
+    return dXs, dW
 
 
 def make_desc(reduce, dtype, relu, in_dim, out_dim, has_root=False, need_dx=True):
