@@ -122,6 +122,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="replay the step from a captured HIP graph (launch-bound workloads); per-kernel "
                          "timing then comes from a separate eager pass")
+    ap.add_argument("--edge-bench", type=int, default=0, metavar="F",
+                    help="time the edge-weighting primitives (NeighborApply mul/dot, Pull add/scale, fwd+bwd) at "
+                         "width F on the workload's first graph instead of the model step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -173,6 +176,73 @@ def main():
     torch.cuda.synchronize()
     plan_ms = (time.perf_counter() - t0) * 1e3      # plan build (+ buffer allocation), once per graph
 
+    if args.edge_bench:
+        F = args.edge_bench
+        g = model.graphs[0]
+        E, nd, ns = g.n_edges, g.n_dst, g.n_src
+        tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+        Xs = torch.randn((ns, F), device=dev).to(tdt)
+        Xd = torch.randn((nd, F), device=dev).to(tdt)
+        dY = torch.randn((nd, F), device=dev).to(tdt)
+        Wv = torch.empty((E, F), dtype=tdt, device=dev)
+        dWv = torch.empty_like(Wv)
+        Wd = torch.empty((E,), dtype=torch.float32, device=dev)
+        dWd = torch.empty_like(Wd)
+        Y = torch.empty((nd, F), dtype=tdt, device=dev)
+        dXs, dXd = torch.empty_like(Xs), torch.empty_like(Xd)
+
+        def t_ms(fn):
+            for _ in range(max(2, args.warmup)):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps
+        ef, rf = E * F * s, (nd + ns) * F * s      # one pass over the edge tensor / the vertex tensors
+        cases = [
+            ("neighbor_apply_fwd mul", lambda: B.gt_neighbor_apply_fwd(g, "mul", Xs, Xd, out=Wv), 2 * ef + nd * F * s + 4 * E),
+            ("pull_fwd add mean", lambda: B.gt_pull_fwd(g, "mean", "add", Xs, Wv, out=Y), 2 * ef + nd * F * s + 4 * E),
+            ("pull_bwd add mean", lambda: B.gt_pull_bwd(g, "mean", "add", dY, Xs, Wv, out_dXs=dXs, out_dW=dWv),
+             2 * ef + rf + 12 * E),
+            ("neighbor_apply_bwd mul", lambda: B.gt_neighbor_apply_bwd(g, "mul", dWv, Xs, Xd, out_dXs=dXs, out_dXd=dXd),
+             4 * ef + rf + 12 * E),
+            ("neighbor_apply_fwd dot", lambda: B.gt_neighbor_apply_fwd(g, "dot", Xs, Xd, out=Wd), ef + nd * F * s + 8 * E),
+            ("pull_fwd scale mean", lambda: B.gt_pull_fwd(g, "mean", "scale", Xs, Wd, out=Y), ef + nd * F * s + 8 * E),
+            ("pull_bwd scale mean", lambda: B.gt_pull_bwd(g, "mean", "scale", dY, Xs, Wd, out_dXs=dXs, out_dW=dWd),
+             2 * ef + rf + 24 * E),
+            ("neighbor_apply_bwd dot", lambda: B.gt_neighbor_apply_bwd(g, "dot", dWd, Xs, Xd, out_dXs=dXs, out_dXd=dXd),
+             2 * ef + rf + 20 * E),
+        ]
+        rows = []
+        for name, fn, nbytes in cases:
+            ms = t_ms(fn)
+            rows.append(dict(op=name, ms=ms, algorithmic_bytes=nbytes, achieved_gbs=nbytes / ms / 1e6,
+                             frac_of_hbm_peak=nbytes / ms / 1e6 / HBM_PEAK_GBS, edge_features_per_s=E * F / ms * 1e3))
+        out = dict(metric="edge_weighting", workload=cfg["name"], width=F, dtype=dt, n_edges=E, n_dst=nd, n_src=ns, ops=rows)
+        if not args.no_cpu_baseline:
+            import oracle
+            blk = cfg["blocks"][0]
+            nsub = max(1, nd // 64)
+            rp = blk["rowptr"][:nsub + 1]
+            ci = blk["colidx"][:rp[-1]]
+            xs, xd = np.random.default_rng(0).standard_normal((ns, F)), np.random.default_rng(1).standard_normal((nsub, F))
+            t0 = time.perf_counter()
+            w = oracle.neighbor_apply(rp, ci, xs, xd, "mul")
+            y = oracle.pull(rp, ci, xs, w, "mean", "add")
+            oracle.pull_bwd(rp, ci, y, xs, w, "mean", "add")
+            oracle.neighbor_apply_bwd(rp, ci, w, xs, xd, "mul")
+            tc = time.perf_counter() - t0
+            gpu_ms = sum(r["ms"] for r in rows[:4])
+            out["cpu_baseline"] = dict(value=4 * ci.size * F / tc, unit="edge*feature/s", cores=oracle.num_threads(),
+                                       kind="oracle", sample="NGCF chain (NeighborApply mul, Pull add/mean, both "
+                                       "derivatives) on the first 1/64 of the destination rows (%d edges, %.2f s)"
+                                       % (ci.size, tc), gpu_value_same_chain=4 * E * F / gpu_ms * 1e3)
+        print(json.dumps(out))
+        return
     if args.reorder_check:
         def timed(fo, bo, reps=args.steps):
             for _ in range(max(2, args.warmup)):
