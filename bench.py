@@ -37,6 +37,10 @@ def build_workload(name, scale):
         return configs.reorder_stress(scale or 20, True, "sum")
     if name == "c5b":
         return configs.reorder_stress(scale or 20, False, "sum")
+    if name == "c6a":
+        return configs.paper_batch("light")
+    if name == "c6b":
+        return configs.paper_batch("heavy")
     raise SystemExit("unknown --config %s" % name)
 
 

@@ -82,6 +82,30 @@ def sage_minibatch(scale: int = 21, n_seeds: int = 1024):
                 blocks=blocks, dims=list(dims), X=X, W=W, W_root=Wr, b=b, G=G)
 
 
+@functools.lru_cache(maxsize=2)
+def paper_batch(kind: str = "light", n_seeds: int = 300, scale: int | None = None):
+    """The paper's own training regime (Evaluation, "GNN models" and "Workloads and datasets"):
+    a batch of 300 seed vertices, two GCN layers with mean aggregation and hidden width 64.
+    Two shapes from the dataset table's "Sampled graph" columns:
+      "light": the reddit2 row  (feature 602, 41 outputs, about 185 K sampled vertices, 57 K
+               destinations, 0.9 M edges),
+      "heavy": the wiki-talk row (feature 4353, 2 outputs, about 29 K vertices, 8 K
+               destinations, 60 K edges).
+    The sampler's fanouts are not given in the paper; they are chosen here so that the drawn
+    blocks come out near those sizes (light: 91 K vertices, 44 K destinations, 0.88 M edges;
+    heavy: 34 K vertices, 7 K destinations, 52 K edges)."""
+    if kind == "light":
+        sc, fanouts, dims, seed = scale or 18, (600, 16), (602, 64, 41), 6
+    elif kind == "heavy":
+        sc, fanouts, dims, seed = scale or 21, (27, 6), (4353, 64, 2), 7
+    else:
+        raise ValueError(kind)
+    blocks = graphs.drawn_blocks(sc, n_seeds, fanouts, seed)
+    X, W, Wr, b, G = _dense(seed, blocks[0]["n_src"], dims, "f32", n_out=blocks[-1]["n_dst"])
+    return dict(name="c6_paper_batch_%s" % kind, dtype="f32", model="gcn", reduce="mean",
+                blocks=blocks, dims=list(dims), X=X, W=W, W_root=Wr, b=b, G=G)
+
+
 @functools.lru_cache(maxsize=4)
 def reorder_stress(scale: int = 20, wide_to_narrow: bool = True, reduce: str = "sum",
                    wide: int = 1024, narrow: int = 16):

@@ -127,3 +127,42 @@ def sample_blocks(rowptr, colidx, n_seeds: int, fanouts, seed: int):
         dst_global = src_global
     blocks.reverse()
     return blocks
+
+
+def drawn_blocks(scale: int, n_seeds: int, fanouts, seed: int):
+    """Sampled bipartite blocks drawn directly, without a base graph: every destination draws
+    `fanout` in-neighbours from the source marginal of the R-MAT generator on 2**scale vertices
+    (popular vertices are drawn often, as in a sampled power-law graph) and duplicates within a
+    row are dropped.  Same conventions as `sample_blocks`: fanouts from the seed hop outwards,
+    destinations are the first local source ids, new sources get ids in first-seen order, the
+    list is ordered by layer.  Stands in for the paper's sampled batches (dataset table, "Sampled
+    graph" columns), whose sampler settings are not given.
+    """
+    rng = _rng(seed, 4)
+    n = 1 << scale
+    dst_global = rng.choice(n, size=n_seeds, replace=False).astype(np.int64)
+    blocks = []
+    for hop, fanout in enumerate(fanouts):
+        nd = dst_global.size
+        flat, _ = rmat_edges(scale, nd * fanout, seed * 131 + hop)
+        row_of = np.repeat(np.arange(nd, dtype=np.int64), fanout)
+        key = np.unique(row_of * np.int64(n) + flat)          # per-row duplicates dropped
+        row_of = key // np.int64(n)
+        flat = key - row_of * np.int64(n)
+        counts = np.bincount(row_of, minlength=nd)
+        seen = np.concatenate([dst_global, flat])
+        uniq, first = np.unique(seen, return_index=True)
+        order = np.argsort(first, kind="stable")
+        src_global = uniq[order]
+        local_of = np.empty(uniq.size, dtype=np.int64)
+        local_of[order] = np.arange(uniq.size)
+        local = local_of[np.searchsorted(uniq, flat)]
+        key = np.sort(row_of * np.int64(uniq.size) + local)   # rows canonical: ascending local id
+        local = key - (key // np.int64(uniq.size)) * np.int64(uniq.size)
+        rp = np.zeros(nd + 1, dtype=np.int64)
+        np.cumsum(counts, out=rp[1:])
+        blocks.append(dict(rowptr=rp.astype(np.int32), colidx=local.astype(np.int32),
+                           n_dst=int(nd), n_src=int(src_global.size), src_global=src_global))
+        dst_global = src_global
+    blocks.reverse()
+    return blocks

@@ -276,8 +276,10 @@ SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
     const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
     SplitPlan p{1, (K + KT - 1) / KT * KT};
     if (K <= 0) { p.k_per_split = KT; return p; }
-    // the reduction is cut only for the weight-gradient shape: few output tiles, very long K
-    if (!transA || tiles >= 256 || K < 8 * KT) return p;
+    // The reduction is cut when the output has too few tiles to fill the chip: the weight-gradient
+    // shape (very long K), and a tall product over a very wide feature row with few rows
+    if (tiles >= 256 || K < 8 * KT) return p;
+    if (!transA && (tiles >= 128 || K < 1024)) return p;
     int64_t want = (512 + tiles - 1) / tiles;                 // about two workgroups per CU
     const int64_t max_by_len = K / (4 * KT);                  // at least 4 k-tiles per split
     if (want > max_by_len) want = max_by_len;

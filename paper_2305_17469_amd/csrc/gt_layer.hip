@@ -169,19 +169,20 @@ __global__ void __launch_bounds__(256) k_mask_colsum_vec(const T *dY, int64_t ld
     }
 }
 
-// out[c] = sum over the nblk partial rows, 16 columns per workgroup, 16 row lanes per column
+// out[c] = sum over the nblk partial rows, 4 columns per workgroup, 64 row lanes per column; the
+// lanes' sums are added in lane order, so the result does not depend on scheduling
 __global__ void __launch_bounds__(256) k_colsum_final(const float *partial, int64_t nblk, int64_t cols, float *out) {
     __shared__ float red[256];
-    const int cl = threadIdx.x & 15, rl = threadIdx.x >> 4;
-    const int64_t c = (int64_t)blockIdx.x * 16 + cl;
+    const int cl = threadIdx.x & 3, rl = threadIdx.x >> 2;
+    const int64_t c = (int64_t)blockIdx.x * 4 + cl;
     float s = 0.0f;
     if (c < cols)
-        for (int64_t b = rl; b < nblk; b += 16) s += partial[b * cols + c];
+        for (int64_t b = rl; b < nblk; b += 64) s += partial[b * cols + c];
     red[threadIdx.x] = s;
     __syncthreads();
     if (rl == 0 && c < cols) {
         float t = 0.0f;
-        for (int k = 0; k < 16; ++k) t += red[k * 16 + cl];
+        for (int k = 0; k < 64; ++k) t += red[k * 4 + cl];
         out[c] = t;
     }
 }
@@ -221,10 +222,15 @@ LayerLayout layer_layout(const gt_graph *g, const gt_layer_desc *d) {
     const int64_t fmax = d->in_dim > d->out_dim ? d->in_dim : d->out_dim;
     L.agg_ws_bytes = gt_aggregate_ws_bytes(g, fmax);
     L.agg_ws = take(L.agg_ws_bytes);
-    const int64_t rows = g->n_src > g->n_dst ? g->n_src : g->n_dst;
-    L.gemm_ws_bytes = gt_gemm_ws_bytes(1, d->in_dim, d->out_dim, rows);
-    const size_t alt = gt_gemm_ws_bytes(1, d->in_dim, d->out_dim, g->n_dst);
-    if (alt > L.gemm_ws_bytes) L.gemm_ws_bytes = alt;
+    // split-k partials: the largest need over every product either order may run
+    L.gemm_ws_bytes = 0;
+    for (const int64_t rows : {g->n_src, g->n_dst}) {
+        const size_t need[3] = {gt_gemm_ws_bytes(1, d->in_dim, d->out_dim, rows),    // dW = X^T dZ
+                                gt_gemm_ws_bytes(0, rows, d->out_dim, d->in_dim),    // X W
+                                gt_gemm_ws_bytes(0, rows, d->in_dim, d->out_dim)};   // dZ W^T
+        for (size_t nb : need)
+            if (nb > L.gemm_ws_bytes) L.gemm_ws_bytes = nb;
+    }
     L.gemm_ws = take(L.gemm_ws_bytes);
     L.total = off;
     L.saved = gt_align_up((size_t)g->n_dst * L.ldi * es);
@@ -288,7 +294,7 @@ gt_status mask_colsum(const void *dY, int64_t lddy, const void *Y, int64_t ldy, 
                       int64_t cols, float *partial, float *db, hipStream_t st) {
     if (rows <= 0) {
         if (db) {   // empty sum: zeros, written by the same final kernel (no memset node)
-            k_colsum_final<<<(unsigned)((cols + 15) / 16), 256, 0, st>>>(partial, 0, cols, db);
+            k_colsum_final<<<(unsigned)((cols + 3) / 4), 256, 0, st>>>(partial, 0, cols, db);
             GT_LAUNCH_CHECK("k_colsum_final");
         }
         return GT_OK;
@@ -311,7 +317,7 @@ gt_status mask_colsum(const void *dY, int64_t lddy, const void *Y, int64_t ldy, 
     }
     GT_LAUNCH_CHECK("k_mask_colsum");
     if (db) {
-        k_colsum_final<<<(unsigned)((cols + 15) / 16), 256, 0, st>>>(partial, nblk, cols, db);
+        k_colsum_final<<<(unsigned)((cols + 3) / 4), 256, 0, st>>>(partial, nblk, cols, db);
         GT_LAUNCH_CHECK("k_colsum_final");
     }
     return GT_OK;
@@ -389,6 +395,7 @@ extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_
     const gt_dtype t = d->dtype;
     const int64_t fi = d->in_dim, fo = d->out_dim;
 
+    void *gws = at(scratch, L.gemm_ws);
     if (order == GT_AGG_FIRST) {
         // M = A X (kept for the weight gradient), then the combination on n_dst rows
         s = gt_aggregate_run(g, false, d->reduce, t, t, fi, X, ldx, saved, L.ldi, nullptr, GT_ACT_NONE,
@@ -396,16 +403,16 @@ extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_
         if (s != GT_OK) return s;
         if (!d->has_root)
             return gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, saved, L.ldi, W, fo, b, nullptr, d->act, nullptr, 0, Y, ldy,
-                               t, nullptr, 0, st);
+                               t, gws, L.gemm_ws_bytes, st);
         s = gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, saved, L.ldi, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, Y,
-                        ldy, t, nullptr, 0, st);
+                        ldy, t, gws, L.gemm_ws_bytes, st);
         if (s != GT_OK) return s;
     } else {
         // T = X W on n_src rows, then the aggregation at width out_dim with bias and activation
         // applied as the row is written
         void *T = at(scratch, L.T);
         s = gt_gemm_run(fn, t, 0, 0, g->n_src, fo, fi, X, ldx, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, T, L.ldo,
-                        t, nullptr, 0, st);
+                        t, gws, L.gemm_ws_bytes, st);
         if (s != GT_OK) return s;
         const bool fuse = !d->has_root;
         s = gt_aggregate_run(g, false, d->reduce, t, t, fo, T, L.ldo, Y, ldy, fuse ? b : nullptr,
@@ -413,8 +420,8 @@ extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_
         if (s != GT_OK || fuse) return s;
     }
     // root term: Y = act(Y + X[0:n_dst] W_root + b)
-    return gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, X, ldx, W_root, fo, b, nullptr, d->act, Y, ldy, Y, ldy, t, nullptr,
-                       0, st);
+    return gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, X, ldx, W_root, fo, b, nullptr, d->act, Y, ldy, Y, ldy, t, gws,
+                       L.gemm_ws_bytes, st);
 }
 
 extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_order fwd_used, gt_order req,
@@ -508,12 +515,12 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
     if (order == GT_COMB_FIRST) {
         // dX = (A^T dZ) W^T
         s = gt_gemm_run(fn, t, 0, 1, g->n_src, fi, fo, S, L.ldo, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dX, lddx,
-                        t, nullptr, 0, st);
+                        t, gws, L.gemm_ws_bytes, st);
     } else {
         // dM = dZ W^T (the combination's derivative uses the transposed weight), dX = A^T dM
         void *dM = at(scratch, L.dM);
         s = gt_gemm_run(fn, t, 0, 1, g->n_dst, fi, fo, dZ, lddz, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dM, L.ldi,
-                        t, nullptr, 0, st);
+                        t, gws, L.gemm_ws_bytes, st);
         if (s != GT_OK) return s;
         s = gt_aggregate_run(g, true, d->reduce, t, t, fi, dM, L.ldi, dX, lddx, nullptr, GT_ACT_NONE, aws, L.agg_ws_bytes, st);
     }
@@ -521,7 +528,7 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
     if (d->has_root) {
         // dX[0:n_dst] += dZ W_root^T
         s = gt_gemm_run(fn, t, 0, 1, g->n_dst, fi, fo, dZ, lddz, W_root, fo, nullptr, nullptr, GT_ACT_NONE, dX, lddx, dX,
-                        lddx, t, nullptr, 0, st);
+                        lddx, t, gws, L.gemm_ws_bytes, st);
     }
     return s;
 }

@@ -20,7 +20,9 @@ pytestmark = pytest.mark.gpu
 SHAPES = [(1, 1, 1), (300, 64, 64), (257, 16, 100), (515, 41, 128), (130, 47, 256), (260, 128, 602),
           (129, 256, 100), (70, 1024, 16), (200, 16, 1024), (33, 130, 37),
           # large enough for the fp32 path that runs on the bf16 matrix cores by three-way splitting
-          (2100, 130, 1000), (1030, 602, 450)]
+          (2100, 130, 1000), (1030, 602, 450),
+          # few output tiles under a very wide feature row: the reduction is cut for every orientation
+          (300, 64, 4353), (700, 2, 1100)]
 
 
 def _check(got, ref, absr, dtype, c_bf16, what):

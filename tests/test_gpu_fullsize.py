@@ -130,6 +130,21 @@ def test_config4_full_size_sage_minibatch():
     print(errs)
 
 
+@pytest.mark.parametrize("kind", ["light", "heavy"])
+def test_paper_batch_regime_full_size(kind):
+    """The paper's own regime (Evaluation: batches of 300 seeds, two mean-GCN layers, hidden 64)
+    on blocks shaped like the dataset table's sampled reddit2 and wiki-talk rows.  In the light
+    block every source row is gathered about eight times, so transforming 602 -> 64 first must
+    win (Dynamic kernel placement).  In the heavy block the sources outnumber the destinations
+    almost five to one while there are only 1.3 edges per source, so either order moves about
+    the same bytes; the order is left to the cost model there and only parity is asserted."""
+    announce("full size: paper batch regime,", kind)
+    errs, model = run_and_check(configs.paper_batch(kind))
+    if kind == "light":
+        assert model.used_fwd[0] == "comb_first"
+    print(errs, model.used_fwd, model.used_bwd)
+
+
 @pytest.mark.parametrize("wide_to_narrow", [True, False])
 def test_config5_full_size_reorder_stress(wide_to_narrow):
     announce("full size: config 5 (ER 2^20), wide_to_narrow =", wide_to_narrow)
