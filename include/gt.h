@@ -265,6 +265,59 @@ gt_status gt_calibrate_ws_size(size_t *ws_bytes /* host */);
 gt_status gt_calibrate(void *ws, size_t ws_bytes, gt_cost_coeffs *fitted /* host, may be NULL */, void *stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Batch preparation on the GPU: neighbour sampling (S), renumbering (R) and embedding lookup (K)
+ * (paper: Preliminaries, "Preprocessing for GNNs"; Service-wide tensor scheduler,
+ * "High-performance preprocessing").  The paper runs S, R and K on host threads, because graph
+ * and embedding table live in host memory, and adds T, the transfer to the GPU.  Here graph and
+ * table are resident in device memory: S, R and K are kernels on the caller's stream (so a
+ * batch can be prepared on one stream while the previous one trains on another) and T is gone.
+ *
+ * One subgraph per GNN layer, the layer nearest the seeds first: S on the seeds, R, then S on
+ * R's source list for the next layer outwards, R again, ..., and K on the outermost source list.
+ *
+ * The random choice ("unique random" in the paper, not specified further) is a keyed
+ * pseudo-random permutation pi of the positions 0..d-1 of a destination's in-neighbour list:
+ *   mix32(x): x ^= x>>16; x *= 0x7feb352d; x ^= x>>15; x *= 0x846ca68b; x ^= x>>16   (mod 2^32)
+ *   row key  rk = mix32(mix32(seed + 0x9E3779B9 * stream_id) ^ v),   v = global destination id
+ *   d <= 64: position j has key mix32(rk + 0x9E3779B9 * (j + 1)); pi orders positions by key
+ *   d >  64: 6-round balanced Feistel network on 2h bits (h = ceil(bitlength(d-1) / 2), round
+ *            r maps (L, R) to (R, L ^ (mix32(R ^ mix32(rk + 0x9E3779B9 * (r + 1))) & (2^h-1)))),
+ *            re-applied until the value is < d
+ * A destination with d <= fanout keeps its whole list in list order; otherwise its picks are
+ * colidx[rowptr[v] + pi(t)], t = 0..fanout-1, in that order.  The result depends on
+ * (seed, stream_id, v) only, not on the rest of the batch, and is bit-wise reproducible.
+ * ------------------------------------------------------------------------------------------ */
+
+/* S.  rowptr[n_vertices + 1], colidx: in-edge CSR of the WHOLE graph, global ids.  dst[n_dst]:
+ * the layer's destinations (global ids; an id outside [0, n_vertices) yields an empty row).
+ * out_rowptr[n_dst + 1]: offsets of the sampled rows; out_nbr: the picked global ids, capacity
+ * n_dst * fanout entries (< 2^31).  ws: >= gt_sample_ws_size bytes, 256-byte aligned. */
+gt_status gt_sample_ws_size(int64_t n_dst, size_t *ws_bytes /* host */);
+gt_status gt_sample_neighbors(const int32_t *rowptr, const int32_t *colidx, int64_t n_vertices,
+                              const int32_t *dst, int64_t n_dst, int32_t fanout, uint32_t seed,
+                              uint32_t stream_id, int32_t *out_rowptr, int32_t *out_nbr,
+                              void *ws, size_t ws_bytes, void *stream);
+
+/* R.  The table of sampled vertices: walking dst[0..n_dst) and then picked[0..n_picked) in
+ * order, an id met for the first time receives the next new id, counted from 0.  dst must hold
+ * distinct ids (then destination i has new id i); all ids must lie in [0, n_vertices).
+ *   src_global[n_dst + n_picked] (capacity): global id of every new id, first n_src entries;
+ *   colidx_local[n_picked]: picked[] rewritten in new ids (same order);
+ *   counts[2] (device): n_src, and the number of distinct ids among dst (== n_dst iff the
+ *   precondition holds; nothing else is guaranteed when it does not).
+ * Implemented as a stable radix sort of (id, position) and two scans: no hash table, no
+ * atomics, so the first-met order is exact.  n_dst + n_picked < 2^31. */
+gt_status gt_reindex_ws_size(int64_t n_dst, int64_t n_picked, size_t *ws_bytes /* host */);
+gt_status gt_reindex(const int32_t *dst, int64_t n_dst, const int32_t *picked, int64_t n_picked,
+                     int64_t n_vertices, int32_t *src_global, int32_t *colidx_local,
+                     int32_t *counts, void *ws, size_t ws_bytes, void *stream);
+
+/* K.  out[i, 0:F] = table[ids[i], 0:F] for i < n; an id outside [0, n_rows) yields a row of
+ * zeros.  Only the F logical columns of `out` are written. */
+gt_status gt_lookup(gt_dtype dtype, const void *table, int64_t n_rows, int64_t ld,
+                    const int32_t *ids, int64_t n, int64_t F, void *out, int64_t ldo, void *stream);
+
+/* ------------------------------------------------------------------------------------------
  * Optional per-kernel timing (the paper reports GPU kernel time measured with a profiler; this
  * gives the same quantity from inside a timed region).  While enabled, every aggregation
  * gather kernel and every combination kernel launched by this library is bracketed by two HIP

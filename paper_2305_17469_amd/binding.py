@@ -51,7 +51,8 @@ EXPORTS = ["gt_graph_plan_size", "gt_graph_create", "gt_graph_destroy", "gt_grap
            "gt_graph_validate", "gt_aggregate_ws_size", "gt_aggregate_fwd", "gt_aggregate_bwd", "gt_combine_ws_size",
            "gt_combine", "gt_neighbor_apply_fwd", "gt_neighbor_apply_bwd", "gt_pull_fwd", "gt_pull_bwd", "gt_cost_get", "gt_cost_set", "gt_cost_benefits", "gt_layer_decide", "gt_layer_ws_size",
            "gt_layer_fwd", "gt_layer_bwd", "gt_calibrate_ws_size", "gt_calibrate", "gt_trace_enable", "gt_trace_reset",
-           "gt_trace_count", "gt_trace_get", "gt_status_string",
+           "gt_trace_count", "gt_trace_get", "gt_sample_ws_size", "gt_sample_neighbors", "gt_reindex_ws_size",
+           "gt_reindex", "gt_lookup", "gt_status_string",
            "gt_last_error", "gt_version"]
 
 for _n in EXPORTS:
@@ -99,6 +100,15 @@ lib.gt_trace_get.argtypes = [c_int64, POINTER(c_int), POINTER(c_int64), POINTER(
                              POINTER(c_double)]
 lib.gt_calibrate_ws_size.argtypes = [POINTER(c_size_t)]
 lib.gt_calibrate.argtypes = [c_void_p, c_size_t, POINTER(gt_cost_coeffs), c_void_p]
+
+
+lib.gt_sample_ws_size.argtypes = [c_int64, POINTER(c_size_t)]
+lib.gt_sample_neighbors.argtypes = [c_void_p, c_void_p, c_int64, c_void_p, c_int64, c_int32, ctypes.c_uint32,
+                                    ctypes.c_uint32, c_void_p, c_void_p, c_void_p, c_size_t, c_void_p]
+lib.gt_reindex_ws_size.argtypes = [c_int64, c_int64, POINTER(c_size_t)]
+lib.gt_reindex.argtypes = [c_void_p, c_int64, c_void_p, c_int64, c_int64, c_void_p, c_void_p, c_void_p, c_void_p,
+                           c_size_t, c_void_p]
+lib.gt_lookup.argtypes = [c_int, c_void_p, c_int64, c_int64, c_void_p, c_int64, c_int64, c_void_p, c_int64, c_void_p]
 
 
 def _check(status):
@@ -381,6 +391,50 @@ def gt_trace_records():
         k, w, r, wk, ms = c_int(), c_int64(), c_int64(), c_int64(), c_double()
         _check(lib.gt_trace_get(i, byref(k), byref(w), byref(r), byref(wk), byref(ms)))
         out.append((k.value, w.value, r.value, wk.value, ms.value))
+    return out
+
+
+def gt_sample_neighbors(rowptr, colidx, dst, fanout, seed, stream_id):
+    """S for one layer: (out_rowptr[n_dst + 1], picked global ids).  rowptr / colidx: int32 device
+    tensors of the whole graph's in-edge CSR; dst: int32 device tensor of global ids.  Reads the
+    number of picks back from the device (one stream synchronisation) to trim the result."""
+    n_vertices, n_dst = rowptr.numel() - 1, dst.numel()
+    need = c_size_t()
+    _check(lib.gt_sample_ws_size(n_dst, byref(need)))
+    ws = _ws(need.value, dst.device)
+    out_rowptr = torch.empty(n_dst + 1, dtype=torch.int32, device=dst.device)
+    out_nbr = torch.empty(max(n_dst * int(fanout), 1), dtype=torch.int32, device=dst.device)
+    _check(lib.gt_sample_neighbors(_ptr(rowptr), _ptr(colidx), n_vertices, _ptr(dst), n_dst, int(fanout),
+                                   int(seed) & 0xFFFFFFFF, int(stream_id) & 0xFFFFFFFF, _ptr(out_rowptr),
+                                   _ptr(out_nbr), _ptr(ws), ws.numel(), _stream()))
+    n_picked = int(out_rowptr[-1].item())
+    return out_rowptr, out_nbr[:n_picked]
+
+
+def gt_reindex(dst, picked, n_vertices):
+    """R: (src_global[n_src], colidx_local[n_picked]); raises if dst holds a repeated id."""
+    n_dst, n_picked = dst.numel(), picked.numel()
+    need = c_size_t()
+    _check(lib.gt_reindex_ws_size(n_dst, n_picked, byref(need)))
+    ws = _ws(need.value, dst.device)
+    src_global = torch.empty(max(n_dst + n_picked, 1), dtype=torch.int32, device=dst.device)
+    colidx_local = torch.empty(max(n_picked, 1), dtype=torch.int32, device=dst.device)
+    counts = torch.empty(2, dtype=torch.int32, device=dst.device)
+    _check(lib.gt_reindex(_ptr(dst), n_dst, _ptr(picked), n_picked, int(n_vertices), _ptr(src_global),
+                          _ptr(colidx_local), _ptr(counts), _ptr(ws), ws.numel(), _stream()))
+    n_src, n_dst_distinct = counts.tolist()
+    if n_dst_distinct != n_dst:
+        raise ValueError("gt_reindex: destination ids must be distinct (%d distinct of %d)" % (n_dst_distinct, n_dst))
+    return src_global[:n_src], colidx_local[:n_picked]
+
+
+def gt_lookup(table, ids, out=None, F=None):
+    """K: out[i, :F] = table[ids[i], :F]."""
+    F = table.shape[1] if F is None else F
+    if out is None:
+        out = torch.empty((ids.numel(), F), dtype=table.dtype, device=table.device)
+    _check(lib.gt_lookup(_dtype(table), _ptr(table), table.shape[0], _rows2d(table), _ptr(ids), ids.numel(), F,
+                         _ptr(out), _rows2d(out), _stream()))
     return out
 
 
