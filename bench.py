@@ -111,6 +111,112 @@ def cpu_baseline(cfg, nominal_ef, budget_rows=1 << 16):
                 est_step_seconds=est)
 
 
+def feed_bench(args):
+    """Batch preparation (S, R, K on the GPU) in the paper's regime: 300 seeds per batch, two
+    mean-GCN layers with hidden width 64, on a resident R-MAT graph and embedding table.  Times
+    every phase of a batch, then whole batches prepared and trained back to back on one stream
+    and with the next batch prepared on a second stream while the current one trains."""
+    import numpy as np
+    import torch
+    from paper_2305_17469_amd import binding as B, feed
+    from paper_2305_17469_amd.stack import LayerStack
+    from gt_inputs import graphs, tensors
+
+    dev = torch.device("cuda:0")
+    scale, n_seeds, fanouts, dims = args.scale or 21, args.feed_seeds, (25, 10), (100, 64, 47)
+    t0 = time.time()
+    rp, ci = graphs.rmat_csr(scale, 25, seed=3, self_loops=False)
+    gen_s = time.time() - t0
+    n = rp.size - 1
+    rowptr, colidx = torch.from_numpy(rp).to(dev), torch.from_numpy(ci).to(dev)
+    table = torch.randn((n, dims[0]), device=dev, generator=torch.Generator(device=dev).manual_seed(1))
+    W = [torch.from_numpy(tensors.glorot(dims[l], dims[l + 1], 9, l)).to(dev) for l in range(2)]
+    bs = [torch.zeros(dims[l + 1], device=dev) for l in range(2)]
+    G = torch.randn((n_seeds, dims[-1]), device=dev)
+    rng = np.random.default_rng(0)
+    n_batches = args.steps + args.warmup
+    seeds = [torch.from_numpy(rng.choice(n, n_seeds, replace=False).astype(np.int32)).to(dev) for _ in range(n_batches)]
+
+    def sync_ms(fn):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        r = fn()
+        torch.cuda.synchronize()
+        return r, (time.perf_counter() - t) * 1e3
+
+    phases = {k: [] for k in ("S", "R", "K", "plan", "step")}
+    sizes = []
+    for i in range(n_batches):
+        dst, blocks, tS, tR = seeds[i], [], 0.0, 0.0
+        for hop, fanout in enumerate(fanouts):
+            (ptr, picked), t = sync_ms(lambda: B.gt_sample_neighbors(rowptr, colidx, dst, fanout, 5 + i, hop))
+            tS += t
+            (src, local), t = sync_ms(lambda: B.gt_reindex(dst, picked, n))
+            tR += t
+            blocks.append(dict(rowptr=ptr, colidx=local, n_dst=dst.numel(), n_src=src.numel(), src_global=src))
+            dst = src
+        blocks.reverse()
+        X, tK = sync_ms(lambda: B.gt_lookup(table, blocks[0]["src_global"]))
+        model, tP = sync_ms(lambda: LayerStack(blocks, dims, "f32", "mean", W, bs))
+        _, tT = sync_ms(lambda: model.step(X, G))
+        if i >= args.warmup:
+            for k, v in zip(("S", "R", "K", "plan", "step"), (tS, tR, tK, tP, tT)):
+                phases[k].append(v)
+            sizes.append((blocks[0]["n_src"], blocks[0]["n_dst"], int(blocks[0]["colidx"].numel()),
+                          int(blocks[1]["colidx"].numel())))
+
+    def prepare(i):
+        blocks, X = feed.prepare_batch(rowptr, colidx, table, seeds[i], fanouts, 5 + i)
+        return LayerStack(blocks, dims, "f32", "mean", W, bs), X
+
+    def run(pipelined):
+        comp, side = torch.cuda.current_stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        t_start = None
+        if not pipelined:
+            for i in range(n_batches):
+                if i == args.warmup:
+                    torch.cuda.synchronize()
+                    t_start = time.perf_counter()
+                model, X = prepare(i)
+                model.step(X, G)
+                comp.synchronize()
+        else:
+            with torch.cuda.stream(side):
+                nxt = prepare(0)
+                ev = side.record_event()
+            for i in range(n_batches):
+                if i == args.warmup:
+                    torch.cuda.synchronize()
+                    t_start = time.perf_counter()
+                (model, X), cur_ev = nxt, ev
+                comp.wait_event(cur_ev)
+                model.step(X, G)                       # enqueued; runs while the next batch is prepared
+                if i + 1 < n_batches:
+                    with torch.cuda.stream(side):
+                        nxt = prepare(i + 1)
+                        ev = side.record_event()
+                comp.synchronize()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t_start) * 1e3 / args.steps
+
+    serial_ms = run(False)
+    piped_ms = run(True)
+    med = {k: float(np.median(v)) for k, v in phases.items()}
+    sz = np.median(np.array(sizes), axis=0)
+    lookup_bytes = 2.0 * sz[0] * dims[0] * 4
+    print(json.dumps(dict(metric="batch preparation + training, batches/s", value=1e3 / piped_ms, unit="batch/s",
+                          n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=piped_ms, higher_is_better=True,
+                          dtype="int32", data="synthetic",
+                          config=dict(workload="feed_rmat%d_seeds%d_fanout%s" % (scale, n_seeds, "x".join(map(str, fanouts))),
+                                      n_vertices=int(n), n_edges=int(ci.size), dims=list(dims), table_gb=n * dims[0] * 4 / 1e9),
+                          ms_per_batch_one_stream=serial_ms, ms_per_batch_two_streams=piped_ms,
+                          phase_ms_median=med, phase_ms_sum=float(sum(med.values())),
+                          sampled_median=dict(n_src=float(sz[0]), n_dst_layer1=float(sz[1]), edges_layer1=float(sz[2]),
+                                              edges_layer2=float(sz[3])),
+                          lookup_gbps=lookup_bytes / med["K"] / 1e6, gen_seconds=gen_s)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -129,6 +235,10 @@ def main():
     ap.add_argument("--edge-bench", type=int, default=0, metavar="F",
                     help="time the edge-weighting primitives (NeighborApply mul/dot, Pull add/scale, fwd+bwd) at "
                          "width F on the workload's first graph instead of the model step")
+    ap.add_argument("--feed-bench", action="store_true",
+                    help="time batch preparation on the GPU (sampling, renumbering, lookup, plan) and training of "
+                         "300-seed batches, on one stream and with preparation overlapped on a second stream")
+    ap.add_argument("--feed-seeds", type=int, default=300, help="seed vertices per batch for --feed-bench")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -143,6 +253,8 @@ def main():
     from gt_inputs import tensors
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
+    if args.feed_bench:
+        return feed_bench(args)
     dev = torch.device("cuda:0")
     t0 = time.time()
     cfg = build_workload(args.config, args.scale)

@@ -109,19 +109,25 @@ __global__ void __launch_bounds__(RS_THREADS) k_rs_hist(const uint32_t *keys, in
     __shared__ int32_t h[256];
     h[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * RS_TILE;
-    for (int i = threadIdx.x; i < RS_TILE; i += RS_THREADS) {
-        int64_t p = base + i;
-        if (p < n) atomicAdd(&h[(keys[p] >> shift) & 255u], 1);
+    const int64_t base = (int64_t)blockIdx.x * RS_TILE + threadIdx.x;
+    uint32_t k[RS_TILE / RS_THREADS];
+#pragma unroll
+    for (int i = 0; i < RS_TILE / RS_THREADS; ++i) {
+        const int64_t p = base + (int64_t)i * RS_THREADS;
+        k[i] = p < n ? keys[p] : 0u;
     }
+#pragma unroll
+    for (int i = 0; i < RS_TILE / RS_THREADS; ++i)
+        if (base + (int64_t)i * RS_THREADS < n) atomicAdd(&h[(k[i] >> shift) & 255u], 1);
     __syncthreads();
     hist[(int64_t)threadIdx.x * nblk + blockIdx.x] = h[threadIdx.x];
 }
 
+// Scatter phase of one pass for the tile of this workgroup.  `digit_off` is, for digit
+// d = threadIdx.x, the output position of the tile's first item with that digit.
 // vals_in == nullptr means value = position (iota).
-__global__ void __launch_bounds__(RS_THREADS) k_rs_scatter(const uint32_t *keys_in, const uint32_t *vals_in,
-                                                           uint32_t *keys_out, uint32_t *vals_out, int64_t n,
-                                                           int shift, const int32_t *offs, int nblk) {
+__device__ inline void rs_scatter_tile(const uint32_t *keys_in, const uint32_t *vals_in, uint32_t *keys_out,
+                                       uint32_t *vals_out, int64_t n, int shift, int32_t digit_off) {
     __shared__ int32_t cnt[RS_WAVES][256];
     __shared__ int32_t wbase[RS_WAVES][256];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -131,11 +137,18 @@ __global__ void __launch_bounds__(RS_THREADS) k_rs_scatter(const uint32_t *keys_
     uint32_t key[RS_CHUNKS];
     int32_t rank[RS_CHUNKS];
     const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    // all loads first, so that their latencies overlap instead of adding up chunk by chunk
 #pragma unroll
     for (int c = 0; c < RS_CHUNKS; ++c) {
         const int64_t p = wstart + (int64_t)c * 64 + lane;
+        key[c] = p < n ? keys_in[p] : 0u;
+    }
+#pragma unroll
+    for (int c = 0; c < RS_CHUNKS; ++c) {
+        rank[c] = 0;
+        if (wstart + (int64_t)c * 64 >= n) continue;   // wavefront-uniform: the chunk is empty
+        const int64_t p = wstart + (int64_t)c * 64 + lane;
         const bool valid = p < n;
-        key[c] = valid ? keys_in[p] : 0u;
         const uint32_t digit = (key[c] >> shift) & 255u;
         uint64_t m = __ballot(valid);
 #pragma unroll
@@ -154,7 +167,7 @@ __global__ void __launch_bounds__(RS_THREADS) k_rs_scatter(const uint32_t *keys_
     __syncthreads();
     {
         const int d = threadIdx.x;   // 256 threads <-> 256 digits
-        int32_t run = offs[(int64_t)d * nblk + blockIdx.x];
+        int32_t run = digit_off;
 #pragma unroll
         for (int w = 0; w < RS_WAVES; ++w) {
             wbase[w][d] = run;
@@ -174,6 +187,48 @@ __global__ void __launch_bounds__(RS_THREADS) k_rs_scatter(const uint32_t *keys_
     }
 }
 
+__global__ void __launch_bounds__(RS_THREADS) k_rs_scatter(const uint32_t *keys_in, const uint32_t *vals_in,
+                                                           uint32_t *keys_out, uint32_t *vals_out, int64_t n,
+                                                           int shift, const int32_t *offs, int nblk) {
+    rs_scatter_tile(keys_in, vals_in, keys_out, vals_out, n, shift, offs[(int64_t)threadIdx.x * nblk + blockIdx.x]);
+}
+
+// A whole pass in one launch for inputs of at most RS_SMALL_TILES tiles: every workgroup counts
+// the digits of all tiles itself (the input is small enough to come from the L2), which gives it
+// the global digit bases and the counts of the tiles before its own without a histogram kernel,
+// a device-wide scan and their launch latencies.
+constexpr int RS_SMALL_TILES = 8;
+
+__global__ void __launch_bounds__(RS_THREADS) k_rs_pass_small(const uint32_t *keys_in, const uint32_t *vals_in,
+                                                              uint32_t *keys_out, uint32_t *vals_out, int64_t n,
+                                                              int shift, int nblk) {
+    __shared__ int32_t h[256];
+    const int d = threadIdx.x;
+    int32_t before = 0, total = 0;
+    for (int t = 0; t < nblk; ++t) {
+        h[d] = 0;
+        __syncthreads();
+        const int64_t base = (int64_t)t * RS_TILE + threadIdx.x;
+        uint32_t k[RS_TILE / RS_THREADS];
+#pragma unroll
+        for (int i = 0; i < RS_TILE / RS_THREADS; ++i) {
+            const int64_t p = base + (int64_t)i * RS_THREADS;
+            k[i] = p < n ? keys_in[p] : 0u;
+        }
+#pragma unroll
+        for (int i = 0; i < RS_TILE / RS_THREADS; ++i)
+            if (base + (int64_t)i * RS_THREADS < n) atomicAdd(&h[(k[i] >> shift) & 255u], 1);
+        __syncthreads();
+        const int32_t c = h[d];
+        if (t < (int)blockIdx.x) before += c;
+        total += c;
+        __syncthreads();
+    }
+    int32_t all;
+    const int32_t digit_base = block_exclusive_scan(total, &all);
+    rs_scatter_tile(keys_in, vals_in, keys_out, vals_out, n, shift, digit_base + before);
+}
+
 struct SortTmp {
     int32_t *hist;      // 256 * nblk
     int32_t *scan_tmp;  // scan_tmp_ints(256 * nblk)
@@ -185,6 +240,11 @@ gt_status radix_pass(const uint32_t *kin, const uint32_t *vin, uint32_t *kout, u
                      int shift, const SortTmp &t, hipStream_t st) {
     if (n <= 0) return GT_OK;
     const int nblk = rs_blocks(n);
+    if (nblk <= RS_SMALL_TILES) {
+        k_rs_pass_small<<<nblk, RS_THREADS, 0, st>>>(kin, vin, kout, vout, n, shift, nblk);
+        GT_LAUNCH_CHECK("k_rs_pass_small");
+        return GT_OK;
+    }
     k_rs_hist<<<nblk, RS_THREADS, 0, st>>>(kin, n, shift, t.hist, nblk);
     GT_LAUNCH_CHECK("k_rs_hist");
     gt_status s = scan_exclusive(t.hist, t.hist, (int64_t)256 * nblk, t.scan_tmp, st);

@@ -34,19 +34,39 @@ class LayerStack:
             self.graphs.append(seen[key])
         dev = self.graphs[0].device
         ld = (lambda F: _pad(F, dtype)) if pad else (lambda F: F)
-        self.descs, self.bufs, self.H, self.dH = [], [], [], []
-        self.dW, self.dW_root, self.db = [], [], []
+
+        # one zero-filled slab per element type (one fill launch instead of one per tensor);
+        # every tensor starts on a 256-byte boundary
+        def carve(shapes, tdt):
+            es = torch.empty((), dtype=tdt).element_size()
+            offs, off = [], 0
+            for sh in shapes:
+                offs.append(off)
+                n = 1
+                for v in sh:
+                    n *= v
+                off += (n * es + 255) // 256 * 256 // es
+            slab = torch.zeros(max(off, 1), dtype=tdt, device=dev)
+            return [slab[o:o + sh[0] * sh[1]].view(sh) if len(sh) == 2 else slab[o:o + sh[0]] for o, sh in zip(offs, shapes)]
+
+        self.descs, self.bufs = [], []
+        feat_shapes, f32_shapes = [], []
         for l in range(self.L):
             g = self.graphs[l]
             d = B.make_desc(reduce, dtype, l < self.L - 1, dims[l], dims[l + 1], has_root=self.W_root[l] is not None,
                             need_dx=l > 0)
             self.descs.append(d)
             self.bufs.append(B.LayerBuffers(g, d))
-            self.H.append(torch.zeros((g.n_dst, ld(dims[l + 1])), dtype=self.tdt, device=dev)[:, :dims[l + 1]])
-            self.dH.append(torch.zeros((g.n_src, ld(dims[l])), dtype=self.tdt, device=dev)[:, :dims[l]] if l > 0 else None)
-            self.dW.append(torch.zeros((dims[l], dims[l + 1]), dtype=torch.float32, device=dev))
-            self.dW_root.append(torch.zeros_like(self.dW[-1]) if self.W_root[l] is not None else None)
-            self.db.append(torch.zeros((dims[l + 1],), dtype=torch.float32, device=dev))
+            feat_shapes += [(g.n_dst, ld(dims[l + 1])), (g.n_src if l > 0 else 0, ld(dims[l]))]
+            f32_shapes += [(dims[l], dims[l + 1]), (dims[l], dims[l + 1]) if self.W_root[l] is not None else (0, 1),
+                           (dims[l + 1],)]
+        feat = carve(feat_shapes, self.tdt)
+        f32 = carve(f32_shapes, torch.float32)
+        self.H = [feat[2 * l][:, :dims[l + 1]] for l in range(self.L)]
+        self.dH = [feat[2 * l + 1][:, :dims[l]] if l > 0 else None for l in range(self.L)]
+        self.dW = [f32[3 * l] for l in range(self.L)]
+        self.dW_root = [f32[3 * l + 1] if self.W_root[l] is not None else None for l in range(self.L)]
+        self.db = [f32[3 * l + 2] for l in range(self.L)]
         self.used_fwd = [None] * self.L
         self.used_bwd = [None] * self.L
 
