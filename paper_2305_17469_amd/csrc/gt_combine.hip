@@ -361,9 +361,14 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     // fp32 shapes bound by matrix throughput go through the split-bf16 kernel (3/8 of the fp32
     // MFMA cost at fp32-level accuracy); skinny, memory-bound shapes keep the plain fp32 MFMA
     const bool x3 = dtype == GT_F32 && N > 64 && K >= 64 && (double)M * (double)N * (double)K >= 268435456.0;
-    gt_status s = x3 ? gt_gemm_x3_launch(g, transA, transB, p.splits, st)
-                     : (dtype == GT_F32) ? launch_gemm_t<float>(g, transA, transB, p.splits, st)
-                                         : launch_gemm_t<bf16_t>(g, transA, transB, p.splits, st);
+    // tall products with a small weight matrix are bound by streaming A and C once: the
+    // weight-stationary kernel does exactly that
+    const bool ws_path = p.splits == 1 && c_dtype == dtype && !Cin && !rowscale &&
+                         gt_gemm_ws_applicable(dtype, transA, M, N, K, g.vecA);
+    gt_status s = ws_path ? gt_gemm_ws_launch(g, dtype, transB, st)
+                  : x3 ? gt_gemm_x3_launch(g, transA, transB, p.splits, st)
+                       : (dtype == GT_F32) ? launch_gemm_t<float>(g, transA, transB, p.splits, st)
+                                           : launch_gemm_t<bf16_t>(g, transA, transB, p.splits, st);
     gt_trace_close(tr, st);
     if (s != GT_OK) return s;
     if (p.splits > 1) {

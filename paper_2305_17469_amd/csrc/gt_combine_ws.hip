@@ -1,0 +1,320 @@
+// Weight-stationary combination for tall, skinny products: C[M, N] = act(A[M, K] op(B) + ...)
+// with M in the millions and K, N at most a few hundred (every layer of a GNN on a large graph).
+//
+// Such a product is bound by reading A and writing C once; the tiled kernel misses that bound
+// because every 128-row workgroup fetches the weight tile again for every k-tile (half of all the
+// bytes it moves through the L2) and its k-loop is a chain of workgroup barriers with one exposed
+// load latency each.  Here the weight matrix is loaded into LDS ONCE per workgroup ([n][k],
+// k contiguous, zero padded) and stays there; the workgroups are persistent and every wavefront
+// works alone on 32-row blocks of A, with no workgroup barrier after the weights are in place:
+//   * A is read in slices of 32 rows x 128 bytes, eight lanes per row, so every load instruction
+//     covers whole 128-byte lines (loading MFMA fragments directly would touch 32 rows x 32 bytes
+//     per instruction and fetch every line four times);
+//   * a slice goes registers -> the wavefront's private LDS stage -> MFMA fragments; as soon as a
+//     slice has left its registers, the same registers receive the loads of the NEXT block's
+//     slice, so a whole block of loads is always in flight per wavefront;
+//   * the MFMA operands are swapped (weights as the first operand, rows of A as the second), so
+//     every lane ends up with four CONSECUTIVE columns of one output row per register group and
+//     stores them directly, with no transposing pass through LDS.
+//
+// Operand mapping.  bf16 (v_mfma_f32_32x32x16_bf16): lane (l32, h) supplies row l32 and
+// k = 16 s + 8 h .. + 7 of step s.  fp32 (v_mfma_f32_32x32x2f32) wants one k per lane half and
+// step; a lane instead reads four consecutive k (16 bytes) and feeds them to four consecutive
+// steps, i.e. step 4 c + j multiplies k = 8 c + 4 h + j; the weight fragment is read from LDS
+// with the same assignment, so every k is used exactly once.
+#include <mutex>
+
+#include "gt_internal.h"
+#include "gt_combine.h"
+
+namespace {
+
+typedef gemm_bf16_t bf16_t;
+
+template <typename T> struct WsGeom;
+// CK: k per MFMA chunk (both lane halves), HK: k per lane (16 bytes), SK: k per slice (128 bytes)
+template <> struct WsGeom<float>  { static constexpr int CK = 8,  HK = 4, SK = 32, PAD = 4; };
+template <> struct WsGeom<bf16_t> { static constexpr int CK = 16, HK = 8, SK = 64, PAD = 8; };
+
+// zero the elements of a 16-byte chunk from element nv on
+template <typename T>
+__device__ inline uint4 ws_mask(uint4 v, int nv) {
+    if constexpr (sizeof(T) == 4) {
+        v.x = nv > 0 ? v.x : 0u; v.y = nv > 1 ? v.y : 0u; v.z = nv > 2 ? v.z : 0u; v.w = nv > 3 ? v.w : 0u;
+    } else {
+        v.x &= nv >= 2 ? 0xffffffffu : (nv == 1 ? 0x0000ffffu : 0u);
+        v.y &= nv >= 4 ? 0xffffffffu : (nv == 3 ? 0x0000ffffu : 0u);
+        v.z &= nv >= 6 ? 0xffffffffu : (nv == 5 ? 0x0000ffffu : 0u);
+        v.w &= nv >= 8 ? 0xffffffffu : (nv == 7 ? 0x0000ffffu : 0u);
+    }
+    return v;
+}
+
+// One slice (32 rows x 128 bytes) of block rb: lane -> row lane/8 + 8 j (j = 0..3), chunk lane%8.
+// Rows past M read the last row (never stored); chunks at or past K read the row's first chunk
+// (always valid) and are zeroed when staged.
+template <typename T>
+__device__ inline void ws_load_slice(uint4 (&r)[4], const T *A, int64_t lda, int64_t rb, int s, int64_t M, int64_t K,
+                                     int lane) {
+    constexpr int HK = WsGeom<T>::HK, SK = WsGeom<T>::SK;
+    const int64_t k = (int64_t)s * SK + (lane & 7) * HK;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        int64_t row = rb * 32 + (lane >> 3) + 8 * j;
+        if (row >= M) row = M - 1;
+        r[j] = *reinterpret_cast<const uint4 *>(A + row * lda + (k < K ? k : 0));
+    }
+}
+
+// The products are formed as (weights)^T x (rows)^T, so accumulator register r of lane (h, l32)
+// holds output row l32 of the block and column 8 (r / 4) + 4 h + r % 4 of the 32-column group:
+// four consecutive columns per register quadruple, stored straight from registers.  The bias is
+// already in the accumulators (they start from it); only the activation is left to apply.
+// CB: C is bf16;  EX: bias and / or ReLU present.
+template <bool CB, bool EX, int NB>
+__device__ inline void ws_epilogue(const GemmArgs &g, floatx16 (&acc)[NB], int64_t row, int64_t n0, int h, bool vec) {
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int64_t col = n0 + b * 32 + 8 * q + 4 * h;
+            if (col >= g.N) continue;
+            const bool whole = vec && col + 4 <= g.N;
+            float v[4] = {acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]};
+            if (EX) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = (g.relu && !(v[i] > 0.0f)) ? 0.0f : v[i];
+            }
+            if (CB) {
+                gemm_bf16_t *p = static_cast<gemm_bf16_t *>(g.C) + row * g.ldc + col;
+                if (whole) {
+                    *reinterpret_cast<uint2 *>(p) = make_uint2(gemm_f32_to_bf16(v[0]) | (gemm_f32_to_bf16(v[1]) << 16),
+                                                               gemm_f32_to_bf16(v[2]) | (gemm_f32_to_bf16(v[3]) << 16));
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (col + i < g.N) p[i] = (gemm_bf16_t)gemm_f32_to_bf16(v[i]);
+                }
+            } else {
+                float *p = static_cast<float *>(g.C) + row * g.ldc + col;
+                if (whole) {
+                    *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (col + i < g.N) p[i] = v[i];
+                }
+            }
+        }
+    }
+}
+
+// LDS bytes of an instance: the weight slice, four private A stages, the bias of the column slice
+template <typename T, int NB, int NS>
+constexpr size_t ws_lds_bytes() {
+    return (size_t)NB * 32 * (NS * WsGeom<T>::SK + WsGeom<T>::PAD) * sizeof(T) + 4 * GEMM_STAGE_FLOATS(1) * 4 +
+           (size_t)NB * 32 * 4;
+}
+// two workgroups share a CU when their LDS allows it; the register budget is set to match
+template <typename T, int NB, int NS>
+constexpr int ws_per_cu() { return ws_lds_bytes<T, NB, NS>() <= 80 * 1024 ? 2 : 1; }
+
+// EX: bias and / or ReLU present.  C has the element type of A; products with a row scale or an
+// addend stay on the tiled kernel.
+template <typename T, int NB, int NS, bool EX>
+__global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const GemmArgs g, const int transB) {
+    constexpr int CK = WsGeom<T>::CK, HK = WsGeom<T>::HK, SK = WsGeom<T>::SK;
+    constexpr int KP = NS * SK;                 // K capacity of this instance
+    constexpr int WSTR = KP + WsGeom<T>::PAD;   // LDS row stride: 16 bytes past a multiple of 128
+    constexpr int ASTR = SK + WsGeom<T>::PAD;   // stage row stride (144 bytes)
+    constexpr int BN = NB * 32;
+    static_assert(32 * ASTR * sizeof(T) <= GEMM_STAGE_FLOATS(1) * 4, "a slice must fit the wavefront's stage");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    T *Ws = reinterpret_cast<T *>(smem);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    // this wavefront's private stage for A slices
+    T *As = reinterpret_cast<T *>(smem + (size_t)BN * WSTR * sizeof(T) + (size_t)wave * GEMM_STAGE_FLOATS(1) * 4);
+    float *bias_lds = reinterpret_cast<float *>(smem + (size_t)BN * WSTR * sizeof(T) + 4 * (size_t)GEMM_STAGE_FLOATS(1) * 4);
+    const T *A = static_cast<const T *>(g.A);
+    const T *B = static_cast<const T *>(g.B);
+    const int64_t n0 = (int64_t)blockIdx.y * BN;
+    for (int n = threadIdx.x; n < BN; n += 256) bias_lds[n] = (g.bias && n0 + n < g.N) ? g.bias[n0 + n] : 0.0f;
+    const int nslices = (int)((g.K + SK - 1) / SK);
+
+    // the weight slice, once: Ws[n][k] = op(B)(k, n0 + n), zero outside (K, N).  16-byte loads,
+    // several in flight per thread (the matrix is small, but one dependent load per element would
+    // cost a load latency each).
+    constexpr int VE = 16 / (int)sizeof(T);
+    if (g.vecB && transB) {          // B[n][k]: vectors along k go straight to the LDS row
+        constexpr int VPR = KP / VE;
+#pragma unroll 8
+        for (int idx = threadIdx.x; idx < BN * VPR; idx += 256) {
+            const int n = idx / VPR, k = (idx % VPR) * VE;
+            const bool ok = n0 + n < g.N && k < g.K;
+            uint4 v = *reinterpret_cast<const uint4 *>(B + (ok ? (n0 + n) * g.ldb + k : 0));
+            const int64_t left = g.K - k;
+            v = ws_mask<T>(v, ok ? (left < VE ? (int)left : VE) : 0);
+            *reinterpret_cast<uint4 *>(Ws + n * WSTR + k) = v;
+        }
+    } else if (g.vecB) {             // B[k][n]: a vector holds VE columns of one k, scattered to VE rows
+        constexpr int VPR = BN / VE;
+#pragma unroll 8
+        for (int idx = threadIdx.x; idx < KP * VPR; idx += 256) {
+            const int k = idx / VPR, n = (idx % VPR) * VE;
+            const bool ok = n0 + n < g.N && k < g.K;
+            uint4 v = *reinterpret_cast<const uint4 *>(B + (ok ? (int64_t)k * g.ldb + n0 + n : 0));
+            const int64_t left = g.N - (n0 + n);
+            v = ws_mask<T>(v, ok ? (left < VE ? (int)left : VE) : 0);
+            T e[VE];
+            __builtin_memcpy(e, &v, 16);
+#pragma unroll
+            for (int q = 0; q < VE; ++q) Ws[(n + q) * WSTR + k] = e[q];
+        }
+    } else if (transB) {
+        for (int idx = threadIdx.x; idx < BN * KP; idx += 256) {
+            const int n = idx / KP, k = idx % KP;
+            const bool ok = n0 + n < g.N && k < g.K;
+            const T v = B[ok ? (n0 + n) * g.ldb + k : 0];
+            Ws[n * WSTR + k] = ok ? v : (T)0;
+        }
+    } else {
+        for (int idx = threadIdx.x; idx < BN * KP; idx += 256) {
+            const int k = idx / BN, n = idx % BN;
+            const bool ok = n0 + n < g.N && k < g.K;
+            const T v = B[ok ? (int64_t)k * g.ldb + n0 + n : 0];
+            Ws[n * WSTR + k] = ok ? v : (T)0;
+        }
+    }
+    __syncthreads();
+
+    const bool out_vec = (g.ldc % 4 == 0) && (((uintptr_t)g.C & 15) == 0);   // 4-column groups of C are aligned
+    const int64_t nrb = (g.M + 31) / 32;
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    int64_t rb = (int64_t)blockIdx.x * 4 + wave;
+    if (rb >= nrb) return;   // no workgroup barrier below this point
+    uint4 R[NS][4];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        if (s < nslices) ws_load_slice<T>(R[s], A, g.lda, rb, s, g.M, g.K, lane);
+    for (; rb < nrb; rb += stride) {
+        const bool more = rb + stride < nrb;
+        // accumulators start from the bias of their columns (register r of lane half h: column
+        // 8 (r / 4) + 4 h + r % 4 of the group), so the epilogue has nothing to add
+        floatx16 acc[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (EX) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 c = *reinterpret_cast<const float4 *>(bias_lds + b * 32 + 8 * q + 4 * h);
+                    acc[b][4 * q] = c.x; acc[b][4 * q + 1] = c.y; acc[b][4 * q + 2] = c.z; acc[b][4 * q + 3] = c.w;
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (s >= nslices) continue;   // uniform
+            // LDS operations of one wavefront execute in program order; the compiler must not move
+            // this slice's stage writes above the previous slice's fragment reads
+            __asm__ volatile("" ::: "memory");
+            // registers -> stage (row-major, elements at or past K zeroed), then refill the registers
+            const int64_t left = g.K - ((int64_t)s * SK + (lane & 7) * HK);
+            const int nv = left >= HK ? HK : (left > 0 ? (int)left : 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint4 v = R[s][j];
+                if (nv < HK) v = ws_mask<T>(v, nv);
+                *reinterpret_cast<uint4 *>(As + ((lane >> 3) + 8 * j) * ASTR + (lane & 7) * HK) = v;
+            }
+            if (more) ws_load_slice<T>(R[s], A, g.lda, rb + stride, s, g.M, g.K, lane);
+#pragma unroll
+            for (int c = 0; c < SK / CK; ++c) {
+                if ((int64_t)s * SK + c * CK >= g.K) continue;   // uniform: nothing left in this slice
+                const uint4 a = *reinterpret_cast<const uint4 *>(As + l32 * ASTR + c * CK + h * HK);
+                const T *wrow = Ws + l32 * WSTR + s * SK + c * CK + h * HK;
+                if constexpr (sizeof(T) == 4) {
+                    const float a0 = __uint_as_float(a.x), a1 = __uint_as_float(a.y), a2 = __uint_as_float(a.z),
+                                a3 = __uint_as_float(a.w);
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        const float4 w = *reinterpret_cast<const float4 *>(wrow + b * 32 * WSTR);
+                        floatx16 cc = acc[b];
+                        cc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.x, a0, cc, 0, 0, 0);
+                        cc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.y, a1, cc, 0, 0, 0);
+                        cc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.z, a2, cc, 0, 0, 0);
+                        cc = __builtin_amdgcn_mfma_f32_32x32x2f32(w.w, a3, cc, 0, 0, 0);
+                        acc[b] = cc;
+                    }
+                } else {
+                    bf16x8 af;
+                    __builtin_memcpy(&af, &a, 16);
+#pragma unroll
+                    for (int b = 0; b < NB; ++b) {
+                        const bf16x8 w = *reinterpret_cast<const bf16x8 *>(wrow + b * 32 * WSTR);
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w, af, acc[b], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        const int64_t row = rb * 32 + l32;
+        if (row < g.M) ws_epilogue<sizeof(T) == 2, EX, NB>(g, acc, row, n0, h, out_vec);
+    }
+}
+
+template <typename T, int NB, int NS, bool EX>
+gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
+    constexpr size_t lds = ws_lds_bytes<T, NB, NS>();
+    // more than 64 KB of dynamic LDS has to be allowed per kernel, once
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    if (attr_err != hipSuccess) return gt_hip_fail(attr_err, "hipFuncSetAttribute(k_gemm_ws)");
+    const int64_t nrb = (g.M + 31) / 32;
+    const int per_cu = ws_per_cu<T, NB, NS>();
+    int64_t gx = (nrb + 3) / 4;
+    if (gx > 256 * per_cu) gx = 256 * per_cu;
+    dim3 grid((unsigned)gx, (unsigned)((g.N + NB * 32 - 1) / (NB * 32)), 1);
+    k_gemm_ws<T, NB, NS, EX><<<grid, 256, lds, st>>>(g, transB);
+    GT_LAUNCH_CHECK("k_gemm_ws");
+    return GT_OK;
+}
+
+template <typename T, int NB, int NS>
+gt_status ws_launch(const GemmArgs &g, int transB, hipStream_t st) {
+    const bool extras = g.bias || g.relu;
+    return extras ? ws_launch_ex<T, NB, NS, true>(g, transB, st) : ws_launch_ex<T, NB, NS, false>(g, transB, st);
+}
+
+template <typename T, int NB>
+gt_status ws_pick_ns(const GemmArgs &g, int transB, hipStream_t st) {
+    const int64_t slices = (g.K + WsGeom<T>::SK - 1) / WsGeom<T>::SK;
+    if (slices <= 1) return ws_launch<T, NB, 1>(g, transB, st);
+    if (slices <= 2) return ws_launch<T, NB, 2>(g, transB, st);
+    return ws_launch<T, NB, 4>(g, transB, st);
+}
+
+template <typename T>
+gt_status ws_pick(const GemmArgs &g, int transB, hipStream_t st) {
+    if (g.N <= 64) return ws_pick_ns<T, 2>(g, transB, st);
+    if (g.N <= 128) return ws_pick_ns<T, 4>(g, transB, st);
+    return ws_pick_ns<T, 8>(g, transB, st);
+}
+
+}  // namespace
+
+// (the caller also requires C to have A's element type and no row scale or addend)
+bool gt_gemm_ws_applicable(gt_dtype dtype, int transA, int64_t M, int64_t N, int64_t K, int vecA) {
+    const int64_t kcap = dtype == GT_BF16 ? 4 * WsGeom<bf16_t>::SK : 4 * WsGeom<float>::SK;   // 256 / 128
+    return !transA && vecA && K >= 1 && K <= kcap && N >= 1 && M >= 8192;
+}
+
+gt_status gt_gemm_ws_launch(const GemmArgs &g, gt_dtype dtype, int transB, hipStream_t st) {
+    return dtype == GT_BF16 ? ws_pick<bf16_t>(g, transB, st) : ws_pick<float>(g, transB, st);
+}

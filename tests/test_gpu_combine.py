@@ -22,7 +22,11 @@ SHAPES = [(1, 1, 1), (300, 64, 64), (257, 16, 100), (515, 41, 128), (130, 47, 25
           # large enough for the fp32 path that runs on the bf16 matrix cores by three-way splitting
           (2100, 130, 1000), (1030, 602, 450),
           # few output tiles under a very wide feature row: the reduction is cut for every orientation
-          (300, 64, 4353), (700, 2, 1100)]
+          (300, 64, 4353), (700, 2, 1100),
+          # tall with a small weight matrix: the weight-stationary kernel (row blocks with a ragged end,
+          # K and N off the chunk sizes, N beyond one column slice, K at both capacities)
+          (9001, 41, 128), (8200, 128, 41), (8300, 256, 256), (10007, 47, 100), (8193, 1024, 16), (12000, 300, 37),
+          (8192, 3, 5), (9000, 70, 250)]
 
 
 def _check(got, ref, absr, dtype, c_bf16, what):
