@@ -29,14 +29,19 @@ constexpr int BM = 128, BN = 128;
 constexpr int STR = KT + 8;          // LDS row stride in bf16 elements (80 bytes: 16-byte aligned, bank friendly)
 constexpr int PLANE = BM * STR;      // elements per plane
 
-// three truncated bf16 pieces of x: x == hi + mid + lo exactly (barring underflow)
+// Three truncated bf16 pieces of x: x == hi + mid + lo exactly (barring underflow).  The pieces are
+// returned as fp32 bit patterns whose upper halves are the bf16 values (the lower halves of `hi`
+// and `lo` are not cleared: only the upper halves are ever used).
 __device__ inline void split3(float x, uint32_t &hi, uint32_t &mid, uint32_t &lo) {
     const uint32_t h = __float_as_uint(x) & 0xffff0000u;
     const float r1 = x - __uint_as_float(h);
     const uint32_t m = __float_as_uint(r1) & 0xffff0000u;
     const float r2 = r1 - __uint_as_float(m);
-    hi = h; mid = m; lo = __float_as_uint(r2) & 0xffff0000u;
+    hi = h; mid = m; lo = __float_as_uint(r2);
 }
+
+// upper halves of two words as one word: (b & 0xffff0000) | (a >> 16), one v_perm_b32
+__device__ inline uint32_t pack_hi16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
 // four consecutive-k values -> three 8-byte k-runs (one per plane) at lds[plane][row][k]
 __device__ inline void store_run4(gemm_bf16_t *lds, int row, int k, float x0, float x1, float x2, float x3) {
@@ -46,9 +51,9 @@ __device__ inline void store_run4(gemm_bf16_t *lds, int row, int k, float x0, fl
     split3(x2, h[2], m[2], l[2]);
     split3(x3, h[3], m[3], l[3]);
     gemm_bf16_t *p = lds + row * STR + k;
-    *reinterpret_cast<uint2 *>(p) = make_uint2((h[0] >> 16) | h[1], (h[2] >> 16) | h[3]);
-    *reinterpret_cast<uint2 *>(p + PLANE) = make_uint2((m[0] >> 16) | m[1], (m[2] >> 16) | m[3]);
-    *reinterpret_cast<uint2 *>(p + 2 * PLANE) = make_uint2((l[0] >> 16) | l[1], (l[2] >> 16) | l[3]);
+    *reinterpret_cast<uint2 *>(p) = make_uint2(pack_hi16(h[0], h[1]), pack_hi16(h[2], h[3]));
+    *reinterpret_cast<uint2 *>(p + PLANE) = make_uint2(pack_hi16(m[0], m[1]), pack_hi16(m[2], m[3]));
+    *reinterpret_cast<uint2 *>(p + 2 * PLANE) = make_uint2(pack_hi16(l[0], l[1]), pack_hi16(l[2], l[3]));
 }
 
 // Four consecutive elements at p[off..off+3] (position c of a row that ends at clim).  Branch
