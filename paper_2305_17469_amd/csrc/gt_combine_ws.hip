@@ -22,8 +22,6 @@
 // step; a lane instead reads four consecutive k (16 bytes) and feeds them to four consecutive
 // steps, i.e. step 4 c + j multiplies k = 8 c + 4 h + j; the weight fragment is read from LDS
 // with the same assignment, so every k is used exactly once.
-#include <mutex>
-
 #include "gt_internal.h"
 #include "gt_combine.h"
 
@@ -268,14 +266,13 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
 template <typename T, int NB, int NS, bool EX>
 gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     constexpr size_t lds = ws_lds_bytes<T, NB, NS>();
-    // more than 64 KB of dynamic LDS has to be allowed per kernel, once
-    static std::once_flag once;
-    static hipError_t attr_err = hipSuccess;
-    std::call_once(once, [&] {
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    });
-    if (attr_err != hipSuccess) return gt_hip_fail(attr_err, "hipFuncSetAttribute(k_gemm_ws)");
+    // More than 64 KB of dynamic LDS has to be allowed per kernel.  Done on every launch that needs
+    // it (a host-side setting, no stream operation), so the first launch of an instance behaves
+    // like any other, also under stream capture.
+    if (lds > 64 * 1024) {
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    }
     const int64_t nrb = (g.M + 31) / 32;
     const int per_cu = ws_per_cu<T, NB, NS>();
     int64_t gx = (nrb + 3) / 4;

@@ -108,3 +108,31 @@ def test_step_replays_from_a_captured_graph(which):
             assert torch.equal(a, b), rep
         for a, b in zip(m.db, ref_db):
             assert torch.equal(a, b), rep
+
+
+def test_weight_stationary_combination_replays_from_a_captured_graph():
+    """The tall-product kernel needs more than 64 KB of LDS for a 256 x 256 bf16 weight matrix,
+    which has to be allowed per kernel on the host; that must also work when the launch is
+    captured, and every replay must reproduce the eager result bit for bit."""
+    from paper_2305_17469_amd import binding as B
+    announce("graph capture of the weight-stationary combination (154 KB of LDS)")
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev).manual_seed(3)
+    A = torch.randn((8200, 256), device=dev, generator=g).to(torch.bfloat16)
+    W = torch.randn((256, 256), device=dev, generator=g).to(torch.bfloat16)
+    bias = torch.randn(256, device=dev, generator=g)
+    ref = B.gt_combine(A, W, bias, relu=True)
+    torch.cuda.synchronize()
+    out = torch.zeros_like(ref)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.gt_combine(A, W, bias, relu=True, out=out)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out.fill_(float(rep))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), rep
