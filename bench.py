@@ -461,7 +461,7 @@ def main():
         traffic = None
         # byte counters cannot be read from inside the run: the figure measured with rocprofv3 --pmc
         # for this workload and kernel width is kept beside the other profile summaries
-        tpath = os.path.join(ROOT, "profiles", "k_aggregate_%s_traffic.json" % args.config)
+        tpath = os.path.join(ROOT, "profiles", "k_aggregate_%s_traffic.txt" % args.config)
         if os.path.exists(tpath):
             tj = json.load(open(tpath))
             if ("width %d)" % wdom) in tj.get("kernel", ""):
