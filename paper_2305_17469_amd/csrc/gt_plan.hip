@@ -113,13 +113,23 @@ __global__ void k_transposed_entries(const int32_t *rowptr, int64_t n_dst, const
 __global__ void k_item_counts(const int32_t *rowptr, int64_t n_rows, int chunk, int32_t *c_items, int32_t *c_parts,
                               int32_t *c_splits) {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= n_rows) return;
+    if (r > n_rows) return;
+    if (r == n_rows) {   // the extra entry makes the exclusive scans end with the totals
+        c_items[r] = 0; c_parts[r] = 0; c_splits[r] = 0;
+        return;
+    }
     const int32_t d = rowptr[r + 1] - rowptr[r];
     const bool split = d > chunk + chunk / 2;
     const int32_t chunks = (d + chunk - 1) / chunk;
     c_items[r] = split ? chunks : 1;
     c_parts[r] = split ? chunks : 0;
     c_splits[r] = split ? 1 : 0;
+}
+
+__global__ void k_collect_counts(const int32_t *ca, const int32_t *cb, const int32_t *cc, int64_t n_rows, int32_t *cnt3) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        cnt3[0] = ca[n_rows]; cnt3[1] = cb[n_rows]; cnt3[2] = cc[n_rows];
+    }
 }
 
 __device__ inline uint32_t length_key(int32_t len) {
@@ -255,24 +265,19 @@ gt_status count_direction(const int32_t *rowptr, int64_t n_rows, int chunk, void
                           int32_t *cnt3, hipStream_t st) {
     int32_t *ca = at<int32_t>(ws, L.ca), *cb = at<int32_t>(ws, L.cb), *cc = at<int32_t>(ws, L.cc);
     int32_t *stmp = at<int32_t>(ws, L.scan_tmp);
-    GT_HIP(hipMemsetAsync(ca + n_rows, 0, 4, st));
-    GT_HIP(hipMemsetAsync(cb + n_rows, 0, 4, st));
-    GT_HIP(hipMemsetAsync(cc + n_rows, 0, 4, st));
-    if (n_rows > 0) {
-        k_item_counts<<<nblocks(n_rows), PT, 0, st>>>(rowptr, n_rows, chunk, ca, cb, cc);
-        GT_LAUNCH_CHECK("k_item_counts");
-    }
+    k_item_counts<<<nblocks(n_rows + 1), PT, 0, st>>>(rowptr, n_rows, chunk, ca, cb, cc);
+    GT_LAUNCH_CHECK("k_item_counts");
     gt_status s;
     if ((s = scan_exclusive(ca, ca, n_rows + 1, stmp, st)) != GT_OK) return s;
     if ((s = scan_exclusive(cb, cb, n_rows + 1, stmp, st)) != GT_OK) return s;
     if ((s = scan_exclusive(cc, cc, n_rows + 1, stmp, st)) != GT_OK) return s;
-    GT_HIP(hipMemcpyAsync(cnt3 + 0, ca + n_rows, 4, hipMemcpyDeviceToDevice, st));
-    GT_HIP(hipMemcpyAsync(cnt3 + 1, cb + n_rows, 4, hipMemcpyDeviceToDevice, st));
-    GT_HIP(hipMemcpyAsync(cnt3 + 2, cc + n_rows, 4, hipMemcpyDeviceToDevice, st));
+    k_collect_counts<<<1, 64, 0, st>>>(ca, cb, cc, n_rows, cnt3);
+    GT_LAUNCH_CHECK("k_collect_counts");
     return GT_OK;
 }
 
 // items of one direction, sorted longest first (stable, so equal lengths keep row order).
+constexpr int64_t GT_SORT_ITEMS_MIN = 16384;
 gt_status build_direction(const int32_t *rowptr, const int32_t *nbr, int64_t n_in, int64_t n_rows, int chunk,
                           int64_t n_items, void *ws, const PlanLayout &L, gt_item *items_out, gt_split *splits_out,
                           hipStream_t st) {
@@ -281,8 +286,13 @@ gt_status build_direction(const int32_t *rowptr, const int32_t *nbr, int64_t n_i
     gt_item *tmp = at<gt_item>(ws, L.items_tmp);
     uint32_t *keys = at<uint32_t>(ws, L.item_keys), *keys2 = at<uint32_t>(ws, L.item_keys2);
     uint32_t *idx = at<uint32_t>(ws, L.item_idx), *idx2 = at<uint32_t>(ws, L.item_idx2);
-    k_fill_items<<<nblocks(n_rows), PT, 0, st>>>(rowptr, nbr, n_in, n_rows, chunk, ca, cb, cc, tmp, keys, splits_out);
+    // A small graph is bound by launch latency, not by load balance or locality: its items stay in
+    // row order and the two sort passes and the gather are saved.
+    const bool sorted = n_items > GT_SORT_ITEMS_MIN;
+    k_fill_items<<<nblocks(n_rows), PT, 0, st>>>(rowptr, nbr, n_in, n_rows, chunk, ca, cb, cc, sorted ? tmp : items_out, keys,
+                                                 splits_out);
     GT_LAUNCH_CHECK("k_fill_items");
+    if (!sorted) return GT_OK;
     SortTmp t{at<int32_t>(ws, L.hist), at<int32_t>(ws, L.scan_tmp)};
     gt_status s = radix_pass(keys, nullptr, keys2, idx, n_items, 0, t, st);      // neighbour range
     if (s != GT_OK) return s;
