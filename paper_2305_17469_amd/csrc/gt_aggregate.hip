@@ -2,6 +2,9 @@
 // host side of gt_aggregate_fwd / gt_aggregate_bwd.  The kernels live in gt_aggregate_kernel.h.
 #include "gt_aggregate_kernel.h"
 
+// tables above this size are gathered in column passes (the MI355X last-level cache holds 256 MiB)
+static const int64_t GT_COLUMN_PASS_TABLE_BYTES = (int64_t)256 << 20;
+
 size_t gt_aggregate_ws_bytes(const gt_graph *g, int64_t F) {
     const int64_t ldp = (F + 7) / 8 * 8;
     const int64_t parts = g->fwd.n_partials > g->bwd.n_partials ? g->fwd.n_partials : g->bwd.n_partials;
@@ -58,12 +61,29 @@ gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce,
     a.trace_kind = transposed ? GT_TRACE_AGG_BWD : GT_TRACE_AGG_FWD;
     a.n_rows = n_out; a.n_edges = g->n_edges;
 
-    if (in_dtype == GT_F32) {
-        const bool vec = aligned16(X) && aligned16(Y) && (ldx % 4 == 0) && (ldy % 4 == 0);
-        return vec ? dispatch<float, 4>(a, st) : dispatch<float, 1>(a, st);
+    const int ve = in_dtype == GT_F32 ? 4 : 8;
+    const bool vec = aligned16(X) && aligned16(Y) && (ldx % ve == 0) && (ldy % ve == 0);
+    // A gathered table far larger than the last-level cache, with rows of 512 bytes or more, is
+    // aggregated in column passes of 256 bytes, one launch each: every pass gathers from a table
+    // slice a fraction of the size, so more of the popular rows stay cached, and the narrow launch
+    // shape keeps more loads in flight (measured on MI355X: 1 GiB bf16 table, 512-byte rows,
+    // 3.93 -> 3.65 ms; 4.3 GB fp32 table, 4 KB rows, 12.0 -> 10.2 ms).  Results are unchanged:
+    // columns are independent.
+    int64_t pass = F;
+    if (vec && a.table_bytes > GT_COLUMN_PASS_TABLE_BYTES && F * (int64_t)es >= 512) pass = 256 / (int64_t)es;
+    for (int64_t c0 = 0; c0 < F; c0 += pass) {
+        const int64_t fp = F - c0 < pass ? F - c0 : pass;
+        a.X = static_cast<const char *>(X) + c0 * es;
+        a.Y = static_cast<char *>(Y) + c0 * es;
+        a.F = fp;
+        a.ldp = (fp + 7) / 8 * 8;
+        a.bias = bias ? bias + c0 : nullptr;
+        gt_status s;
+        if (in_dtype == GT_F32) s = vec ? dispatch<float, 4>(a, st) : dispatch<float, 1>(a, st);
+        else s = vec ? dispatch<bf16_t, 8>(a, st) : dispatch<bf16_t, 1>(a, st);
+        if (s != GT_OK) return s;
     }
-    const bool vec = aligned16(X) && aligned16(Y) && (ldx % 8 == 0) && (ldy % 8 == 0);
-    return vec ? dispatch<bf16_t, 8>(a, st) : dispatch<bf16_t, 1>(a, st);
+    return GT_OK;
 }
 
 extern "C" gt_status gt_aggregate_ws_size(const gt_graph *g, int64_t F, size_t *ws_bytes) {
