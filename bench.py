@@ -55,7 +55,7 @@ def agg_algorithmic_bytes(E, n_out, F, s, reduce, transposed, has_ew):
     return b
 
 
-def cpu_baseline(cfg, nominal_ef, budget_rows=1 << 16):
+def cpu_baseline(cfg, nominal_ef, budget_rows=1 << 18):
     """The oracle, as it stands, timed on a bounded sample: every kernel of the definitional
     (aggregation-first) fwd+bwd step runs on a strided sample of its rows and its time is scaled
     by the ratio of full to sampled work."""
