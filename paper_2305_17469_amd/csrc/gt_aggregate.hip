@@ -4,6 +4,9 @@
 
 // tables above this size are gathered in column passes (the MI355X last-level cache holds 256 MiB)
 static const int64_t GT_COLUMN_PASS_TABLE_BYTES = (int64_t)256 << 20;
+// ... and only when a pass gathers about a gigabyte or more: below that the extra launches cost more
+// than the passes save (a sampled block with 4,353-wide rows would run 68 launches of 11 MB each)
+static const int64_t GT_COLUMN_PASS_MIN_EDGES = (int64_t)4 << 20;
 
 size_t gt_aggregate_ws_bytes(const gt_graph *g, int64_t F) {
     const int64_t ldp = (F + 7) / 8 * 8;
@@ -70,7 +73,8 @@ gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce,
     // 3.93 -> 3.65 ms; 4.3 GB fp32 table, 4 KB rows, 12.0 -> 10.2 ms).  Results are unchanged:
     // columns are independent.
     int64_t pass = F;
-    if (vec && a.table_bytes > GT_COLUMN_PASS_TABLE_BYTES && F * (int64_t)es >= 512) pass = 256 / (int64_t)es;
+    if (vec && a.table_bytes > GT_COLUMN_PASS_TABLE_BYTES && F * (int64_t)es >= 512 && g->n_edges >= GT_COLUMN_PASS_MIN_EDGES)
+        pass = 256 / (int64_t)es;
     for (int64_t c0 = 0; c0 < F; c0 += pass) {
         const int64_t fp = F - c0 < pass ? F - c0 : pass;
         a.X = static_cast<const char *>(X) + c0 * es;

@@ -359,8 +359,12 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     if (p.splits > 1) { g.C = ws; g.ldc = N; } else { g.C = C; g.ldc = ldc; }
     const int tr = gt_trace_open(GT_TRACE_COMBINE, N, M, M * N * K, st);
     // fp32 shapes bound by matrix throughput go through the split-bf16 kernel (3/8 of the fp32
-    // MFMA cost at fp32-level accuracy); skinny, memory-bound shapes keep the plain fp32 MFMA
-    const bool x3 = dtype == GT_F32 && N > 64 && K >= 64 && (double)M * (double)N * (double)K >= 268435456.0;
+    // MFMA cost at fp32-level accuracy); skinny, memory-bound shapes keep the plain fp32 MFMA.
+    // A small weight gradient (at most 256 x 64 outputs over a long reduction) also goes there:
+    // the plain kernel's 256 x 64 tile is mostly padding for it and the slow fp32 MFMA makes that
+    // padding the bottleneck (config 2, 128 x 41: 0.093 -> 0.06 ms).
+    const bool big = (double)M * (double)N * (double)K >= 268435456.0;
+    const bool x3 = dtype == GT_F32 && K >= 64 && big && (N > 64 || (transA && N >= 32 && M <= 256));
     // tall products with a small weight matrix are bound by streaming A and C once: the
     // weight-stationary kernel does exactly that
     const bool ws_path = p.splits == 1 && c_dtype == dtype && !Cin && !rowscale &&

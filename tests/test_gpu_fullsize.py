@@ -170,9 +170,10 @@ def test_large_table_is_gathered_in_column_passes(dtype):
     dev = torch.device("cuda:0")
     F = 136 if dtype == "f32" else 264                      # 544 / 528 bytes per row: 2 full passes + 8 columns
     scale = 19 if dtype == "f32" else 20
-    rp, ci = graphs.rmat_csr(scale, 4, seed=12, self_loops=False)
+    rp, ci = graphs.rmat_csr(scale, 12 if dtype == "f32" else 6, seed=12, self_loops=False)
     n = rp.size - 1
-    assert n * F * (4 if dtype == "f32" else 2) > (256 << 20)
+    # both conditions of the column-pass path: table above 256 MiB, at least 4 Mi edges
+    assert n * F * (4 if dtype == "f32" else 2) > (256 << 20) and ci.size >= (4 << 20)
     announce("column passes:", dtype, "n", n, "F", F, "E", ci.size)
     g = B.Graph(torch.from_numpy(rp).to(dev), torch.from_numpy(ci).to(dev), n)
     X = tensors.normal((n, F), seed=13)
