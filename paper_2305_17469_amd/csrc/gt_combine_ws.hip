@@ -69,15 +69,17 @@ __device__ inline void ws_load_slice(uint4 (&r)[4], const T *A, int64_t lda, int
 // four consecutive columns per register quadruple, stored straight from registers.  The bias is
 // already in the accumulators (they start from it); only the activation is left to apply.
 // CB: C is bf16;  EX: bias and / or ReLU present.
-template <bool CB, bool EX, int NB>
+// FAST: every column group of the slice lies inside N and can be stored as one vector, so the
+// epilogue is straight-line code.
+template <bool CB, bool EX, bool FAST, int NB>
 __device__ inline void ws_epilogue(const GemmArgs &g, floatx16 (&acc)[NB], int64_t row, int64_t n0, int h, bool vec) {
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int64_t col = n0 + b * 32 + 8 * q + 4 * h;
-            if (col >= g.N) continue;
-            const bool whole = vec && col + 4 <= g.N;
+            if (!FAST && col >= g.N) continue;
+            const bool whole = FAST || (vec && col + 4 <= g.N);
             float v[4] = {acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]};
             if (EX) {
 #pragma unroll
@@ -119,7 +121,12 @@ constexpr int ws_per_cu() { return ws_lds_bytes<T, NB, NS>() <= 80 * 1024 ? 2 : 
 
 // EX: bias and / or ReLU present.  C has the element type of A; products with a row scale or an
 // addend stay on the tiled kernel.
-template <typename T, int NB, int NS, bool EX>
+// FAST: N is a multiple of the slice width and C allows vector stores.  Then the row loop is kept
+// free of branches (loads past the end re-read the last block, masks are always applied, rows past
+// M store the last row's values onto the last row): with control flow in the loop the compiler
+// waits for ALL outstanding memory operations before it touches a prefetched slice, i.e. also for
+// the previous block's stores, which costs a store round trip per block.
+template <typename T, int NB, int NS, bool EX, bool FAST>
 __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const GemmArgs g, const int transB) {
     constexpr int CK = WsGeom<T>::CK, HK = WsGeom<T>::HK, SK = WsGeom<T>::SK;
     constexpr int KP = NS * SK;                 // K capacity of this instance
@@ -145,29 +152,51 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
     // cost a load latency each).
     constexpr int VE = 16 / (int)sizeof(T);
     if (g.vecB && transB) {          // B[n][k]: vectors along k go straight to the LDS row
-        constexpr int VPR = KP / VE;
-#pragma unroll 8
-        for (int idx = threadIdx.x; idx < BN * VPR; idx += 256) {
-            const int n = idx / VPR, k = (idx % VPR) * VE;
-            const bool ok = n0 + n < g.N && k < g.K;
-            uint4 v = *reinterpret_cast<const uint4 *>(B + (ok ? (n0 + n) * g.ldb + k : 0));
-            const int64_t left = g.K - k;
-            v = ws_mask<T>(v, ok ? (left < VE ? (int)left : VE) : 0);
-            *reinterpret_cast<uint4 *>(Ws + n * WSTR + k) = v;
+        constexpr int VPR = KP / VE, TOTAL = BN * VPR;
+        for (int base = threadIdx.x; base < TOTAL; base += 256 * 8) {
+            uint4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {   // eight loads in flight, then eight stores
+                const int idx = base + u * 256;
+                const int n = idx / VPR, k = (idx % VPR) * VE;
+                const bool ok = idx < TOTAL && n0 + n < g.N && k < g.K;
+                v[u] = *reinterpret_cast<const uint4 *>(B + (ok ? (n0 + n) * g.ldb + k : 0));
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256;
+                const int n = idx / VPR, k = (idx % VPR) * VE;
+                const bool ok = n0 + n < g.N && k < g.K;
+                const int64_t left = g.K - k;
+                if (idx < TOTAL)
+                    *reinterpret_cast<uint4 *>(Ws + n * WSTR + k) = ws_mask<T>(v[u], ok ? (left < VE ? (int)left : VE) : 0);
+            }
         }
     } else if (g.vecB) {             // B[k][n]: a vector holds VE columns of one k, scattered to VE rows
-        constexpr int VPR = BN / VE;
-#pragma unroll 8
-        for (int idx = threadIdx.x; idx < KP * VPR; idx += 256) {
-            const int k = idx / VPR, n = (idx % VPR) * VE;
-            const bool ok = n0 + n < g.N && k < g.K;
-            uint4 v = *reinterpret_cast<const uint4 *>(B + (ok ? (int64_t)k * g.ldb + n0 + n : 0));
-            const int64_t left = g.N - (n0 + n);
-            v = ws_mask<T>(v, ok ? (left < VE ? (int)left : VE) : 0);
-            T e[VE];
-            __builtin_memcpy(e, &v, 16);
+        constexpr int VPR = BN / VE, TOTAL = KP * VPR;
+        for (int base = threadIdx.x; base < TOTAL; base += 256 * 8) {
+            uint4 v[8];
 #pragma unroll
-            for (int q = 0; q < VE; ++q) Ws[(n + q) * WSTR + k] = e[q];
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256;
+                const int k = idx / VPR, n = (idx % VPR) * VE;
+                const bool ok = idx < TOTAL && n0 + n < g.N && k < g.K;
+                v[u] = *reinterpret_cast<const uint4 *>(B + (ok ? (int64_t)k * g.ldb + n0 + n : 0));
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256;
+                const int k = idx / VPR, n = (idx % VPR) * VE;
+                const bool ok = n0 + n < g.N && k < g.K;
+                const int64_t left = g.N - (n0 + n);
+                const uint4 m = ws_mask<T>(v[u], ok ? (left < VE ? (int)left : VE) : 0);
+                T e[VE];
+                __builtin_memcpy(e, &m, 16);
+                if (idx < TOTAL) {
+#pragma unroll
+                    for (int q = 0; q < VE; ++q) Ws[(n + q) * WSTR + k] = e[q];
+                }
+            }
         }
     } else if (transB) {
         for (int idx = threadIdx.x; idx < BN * KP; idx += 256) {
@@ -194,9 +223,10 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
     uint4 R[NS][4];
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-        if (s < nslices) ws_load_slice<T>(R[s], A, g.lda, rb, s, g.M, g.K, lane);
+        if (FAST || s < nslices) ws_load_slice<T>(R[s], A, g.lda, rb, s, g.M, g.K, lane);
     for (; rb < nrb; rb += stride) {
         const bool more = rb + stride < nrb;
+        const int64_t rb_next = more ? rb + stride : rb;
         // accumulators start from the bias of their columns (register r of lane half h: column
         // 8 (r / 4) + 4 h + r % 4 of the group), so the epilogue has nothing to add
         floatx16 acc[NB];
@@ -215,7 +245,7 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
         }
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            if (s >= nslices) continue;   // uniform
+            if (!FAST && s >= nslices) continue;   // uniform
             // LDS operations of one wavefront execute in program order; the compiler must not move
             // this slice's stage writes above the previous slice's fragment reads
             __asm__ volatile("" ::: "memory");
@@ -225,13 +255,15 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 uint4 v = R[s][j];
-                if (nv < HK) v = ws_mask<T>(v, nv);
+                if (FAST) v = ws_mask<T>(v, nv);
+                else if (nv < HK) v = ws_mask<T>(v, nv);
                 *reinterpret_cast<uint4 *>(As + ((lane >> 3) + 8 * j) * ASTR + (lane & 7) * HK) = v;
             }
-            if (more) ws_load_slice<T>(R[s], A, g.lda, rb + stride, s, g.M, g.K, lane);
+            if (FAST) ws_load_slice<T>(R[s], A, g.lda, rb_next, s, g.M, g.K, lane);
+            else if (more) ws_load_slice<T>(R[s], A, g.lda, rb + stride, s, g.M, g.K, lane);
 #pragma unroll
             for (int c = 0; c < SK / CK; ++c) {
-                if ((int64_t)s * SK + c * CK >= g.K) continue;   // uniform: nothing left in this slice
+                if (!FAST && (int64_t)s * SK + c * CK >= g.K) continue;   // uniform: nothing left in this slice
                 const uint4 a = *reinterpret_cast<const uint4 *>(As + l32 * ASTR + c * CK + h * HK);
                 const T *wrow = Ws + l32 * WSTR + s * SK + c * CK + h * HK;
                 if constexpr (sizeof(T) == 4) {
@@ -259,18 +291,19 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
             }
         }
         const int64_t row = rb * 32 + l32;
-        if (row < g.M) ws_epilogue<sizeof(T) == 2, EX, NB>(g, acc, row, n0, h, out_vec);
+        if (FAST) ws_epilogue<sizeof(T) == 2, EX, true, NB>(g, acc, row < g.M ? row : g.M - 1, n0, h, true);
+        else if (row < g.M) ws_epilogue<sizeof(T) == 2, EX, false, NB>(g, acc, row, n0, h, out_vec);
     }
 }
 
-template <typename T, int NB, int NS, bool EX>
+template <typename T, int NB, int NS, bool EX, bool FAST>
 gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     constexpr size_t lds = ws_lds_bytes<T, NB, NS>();
     // More than 64 KB of dynamic LDS has to be allowed per kernel.  Done on every launch that needs
     // it (a host-side setting, no stream operation), so the first launch of an instance behaves
     // like any other, also under stream capture.
     if (lds > 64 * 1024) {
-        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX>),
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX, FAST>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     }
     const int64_t nrb = (g.M + 31) / 32;
@@ -278,7 +311,7 @@ gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     int64_t gx = (nrb + 3) / 4;
     if (gx > 256 * per_cu) gx = 256 * per_cu;
     dim3 grid((unsigned)gx, (unsigned)((g.N + NB * 32 - 1) / (NB * 32)), 1);
-    k_gemm_ws<T, NB, NS, EX><<<grid, 256, lds, st>>>(g, transB);
+    k_gemm_ws<T, NB, NS, EX, FAST><<<grid, 256, lds, st>>>(g, transB);
     GT_LAUNCH_CHECK("k_gemm_ws");
     return GT_OK;
 }
@@ -286,7 +319,14 @@ gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
 template <typename T, int NB, int NS>
 gt_status ws_launch(const GemmArgs &g, int transB, hipStream_t st) {
     const bool extras = g.bias || g.relu;
-    return extras ? ws_launch_ex<T, NB, NS, true>(g, transB, st) : ws_launch_ex<T, NB, NS, false>(g, transB, st);
+    if constexpr (NB >= 4) {   // the branch-free form exists for the wide slices, where the stores dominate
+        const bool fast = g.N % (NB * 32) == 0 && g.ldc % 4 == 0 && (((uintptr_t)g.C & 15) == 0);
+        if (fast)
+            return extras ? ws_launch_ex<T, NB, NS, true, true>(g, transB, st)
+                          : ws_launch_ex<T, NB, NS, false, true>(g, transB, st);
+    }
+    return extras ? ws_launch_ex<T, NB, NS, true, false>(g, transB, st)
+                  : ws_launch_ex<T, NB, NS, false, false>(g, transB, st);
 }
 
 template <typename T, int NB>
