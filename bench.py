@@ -406,13 +406,7 @@ def main():
             model.step(X, G, args.fwd_order, args.bwd_order)
         torch.cuda.synchronize()
         B.gt_trace_enable(False)
-        side = torch.cuda.Stream()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            model.step(X, G, args.fwd_order, args.bwd_order)
-            side.synchronize()
-            with torch.cuda.graph(graph, stream=side):
-                model.step(X, G, args.fwd_order, args.bwd_order)
+        graph = model.capture(X, G, args.fwd_order, args.bwd_order)
         for _ in range(args.warmup):
             graph.replay()
     torch.cuda.synchronize()

@@ -102,3 +102,20 @@ class LayerStack:
     def step(self, X, dOut, fwd_order="auto", bwd_order="auto"):
         self.forward(X, fwd_order)
         self.backward(dOut, bwd_order)
+
+    def capture(self, X, dOut, fwd_order="auto", bwd_order="auto"):
+        """One fwd+bwd step recorded into a HIP graph (for launch-bound workloads): the layer calls
+        allocate nothing and never synchronise, so the whole step is capturable.  Runs the step once
+        eagerly on a side stream first (placement decisions are taken there), then records it.
+        Returns the graph; `graph.replay()` re-runs the step on the same buffers (X, dOut, the
+        stack's outputs and gradients)."""
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.step(X, dOut, fwd_order, bwd_order)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                self.step(X, dOut, fwd_order, bwd_order)
+        torch.cuda.current_stream().wait_stream(side)
+        return graph

@@ -87,13 +87,7 @@ def test_step_replays_from_a_captured_graph(which):
     ref_out = m.H[-1].clone()
     ref_dW = [w.clone() for w in m.dW]
     ref_db = [b.clone() for b in m.db]
-    side = torch.cuda.Stream()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.stream(side):
-        m.step(X, G)                              # warm-up on the capture stream
-        side.synchronize()
-        with torch.cuda.graph(graph, stream=side):
-            m.step(X, G)
+    graph = m.capture(X, G)
     torch.cuda.synchronize()
     for rep in range(4):
         # eager work and a synchronisation between replays; outputs are clobbered first
