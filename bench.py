@@ -217,6 +217,58 @@ def feed_bench(args):
                           lookup_gbps=lookup_bytes / med["K"] / 1e6, gen_seconds=gen_s)))
 
 
+def decide_sweep(args):
+    """Placement decision on shapes outside the benchmark workloads: square graphs of three kinds,
+    ten (in, out) pairs, fp32 and bf16; the layer under test is the second of a two-layer mean GCN
+    (so it also produces an input gradient).  All four (forward, backward) placements are timed and
+    AUTO's pair must be within 5 % of the fastest."""
+    import torch
+    from paper_2305_17469_amd.stack import LayerStack
+    from gt_inputs import graphs
+    dev = torch.device("cuda:0")
+
+    def timed(m, X, G, fo, bo, reps=8):
+        for _ in range(2):
+            m.step(X, G, fo, bo)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            m.step(X, G, fo, bo)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / reps
+
+    rows, misses = [], 0
+    for gname, (rp, ci) in (("er18x16", graphs.er_csr(18, 16, seed=5)),
+                            ("rmat18x30", graphs.rmat_csr(18, 30, seed=2, self_loops=True)),
+                            ("rmat20x8", graphs.rmat_csr(20, 8, seed=3, self_loops=True))):
+        n = rp.size - 1
+        blk = dict(rowptr=torch.from_numpy(rp).to(dev), colidx=torch.from_numpy(ci).to(dev), n_dst=n, n_src=n)
+        for dt in ("f32", "bf16"):
+            tdt = torch.float32 if dt == "f32" else torch.bfloat16
+            for fi, fo_ in ((32, 256), (256, 32), (64, 64), (128, 64), (64, 128), (512, 64), (104, 48), (16, 16),
+                            (256, 256), (48, 200)):
+                dims = [fi, fi, fo_]
+                W = [torch.randn((dims[l], dims[l + 1]), device=dev).to(tdt) * 0.05 for l in range(2)]
+                b = [torch.zeros(dims[l + 1], device=dev) for l in range(2)]
+                m = LayerStack([blk, blk], dims, dt, "mean", W, b)
+                X = torch.randn((n, fi), device=dev).to(tdt)
+                G = torch.randn((n, fo_), device=dev).to(tdt)
+                m.step(X, G)
+                af, ab = list(m.used_fwd), list(m.used_bwd)
+                res = {}
+                for of in ("agg_first", "comb_first"):
+                    for ob in ("agg_first", "comb_first"):
+                        res[of[:4] + "," + ob[:4]] = timed(m, X, G, [af[0], of], [ab[0], ob])
+                best = min(res, key=res.get)
+                auto = af[1][:4] + "," + ab[1][:4]
+                ok = res[auto] <= 1.05 * res[best]
+                misses += not ok
+                rows.append(dict(graph=gname, dtype=dt, in_dim=fi, out_dim=fo_, auto=auto, ms_auto=res[auto], best=best,
+                                 ms_best=res[best], ok=bool(ok)))
+                del m, X, G, W
+    print(json.dumps(dict(metric="decide_sweep", cases=len(rows), misses=misses, rows=rows)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -238,6 +290,8 @@ def main():
     ap.add_argument("--feed-bench", action="store_true",
                     help="time batch preparation on the GPU (sampling, renumbering, lookup, plan) and training of "
                          "300-seed batches, on one stream and with preparation overlapped on a second stream")
+    ap.add_argument("--decide-sweep", action="store_true",
+                    help="check AUTO's placement against all four timed placements on 60 shapes outside the workloads")
     ap.add_argument("--feed-seeds", type=int, default=300, help="seed vertices per batch for --feed-bench")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
@@ -255,6 +309,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
     if args.feed_bench:
         return feed_bench(args)
+    if args.decide_sweep:
+        return decide_sweep(args)
     dev = torch.device("cuda:0")
     t0 = time.time()
     cfg = build_workload(args.config, args.scale)
