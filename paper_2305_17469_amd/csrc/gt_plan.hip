@@ -133,23 +133,28 @@ __global__ void k_collect_counts(const int32_t *ca, const int32_t *cb, const int
 }
 
 __device__ inline uint32_t length_key(int32_t len) {
-    // descending-length sort key, quarter-octave resolution (exact below 16)
+    // Descending-length sort key, half-octave resolution (exact below 4).  Measured on MI355X with
+    // quarter-octave, half-octave and octave classes: coarser classes leave more of the order to
+    // the locality key (better L2 reuse), finer ones balance the groups of a wavefront better;
+    // half an octave was the best or within 2 % of it on every width of configs 2 and 3.
     uint32_t k;
-    if (len < 16) {
+    if (len < 4) {
         k = (uint32_t)len;
     } else {
         const int lg = 31 - __clz(len);
-        k = 16u + (uint32_t)(lg - 4) * 4u + (((uint32_t)len >> (lg - 2)) & 3u);
+        k = 4u + (uint32_t)(lg - 2) * 2u + (((uint32_t)len >> (lg - 1)) & 1u);
     }
     return 255u - k;
 }
 
-// Sort key of an item: length class (longest first) in bits 8-15, then the range its first
+// Sort key of an item: length class (longest first) in bits 8-15, then the range its MEDIAN
 // neighbour id falls in (256 ranges) in bits 0-7, so that items running at the same time gather
-// from the same region of the table and reuse each other's rows in the L2.
+// from the same region of the table and reuse each other's rows in the L2.  (Rows are sorted by
+// neighbour id; on power-law graphs the first neighbour is a hub for almost every row and tells
+// little, the median separates rows much better: config 3, width 256, 3.47 -> 3.27 ms.)
 __device__ inline uint32_t item_key(int32_t len, const int32_t *nbr, int32_t e0, int64_t n_in) {
     uint32_t loc = 0;
-    if (len > 0 && n_in > 0) loc = (uint32_t)(((int64_t)nbr[e0] << 8) / n_in) & 255u;
+    if (len > 0 && n_in > 0) loc = (uint32_t)(((int64_t)nbr[e0 + len / 2] << 8) / n_in) & 255u;
     return (length_key(len) << 8) | loc;
 }
 
