@@ -198,6 +198,32 @@ __device__ inline void finish_row(const AggArgs &a, int row, int gl, int64_t col
     }
 }
 
+// Item block of this workgroup under the XCD-run order (run <= 1: plain order).  The remapping is
+// a bijection on the blocks of every complete group of 8 * run blocks; the ragged end of the grid
+// keeps the plain order.
+__device__ inline int64_t agg_item_block(int run) {
+    int64_t bx = blockIdx.x;
+    if (gridDim.y == 1 && run > 1) {
+        const int64_t super = 8 * (int64_t)run;
+        const int64_t full = (int64_t)gridDim.x / super * super;
+        if (bx < full) {
+            const int64_t w = bx % super;
+            bx = bx - w + (w & 7) * run + (w >> 3);
+        }
+    }
+    return bx;
+}
+
+// Run length for a grid of gx item blocks: as long as possible for L2 reuse, but at least 64 rounds
+// over the 8 XCDs so that the longest-first order stays balanced (measured on MI355X: 2^18-vertex
+// graph, 512-byte rows, 0.58 -> 0.50 ms at 64; narrow rows and small grids prefer 16-32; 256 was
+// slower than 64 on a 2^21-vertex graph).
+static inline int agg_xcd_run(int64_t gx) {
+    int run = 1;
+    while (run < 64 && (int64_t)run * 2 * 512 <= gx) run *= 2;
+    return run;
+}
+
 // One group of G lanes per work item; 64/G items per wavefront; 4 wavefronts per workgroup.
 // blockIdx.y selects a column tile of G*V*NP columns.
 template <typename T, int V, int G, int NP, int U, int VWM = VWM_NONE>
@@ -211,15 +237,7 @@ __global__ void __launch_bounds__(256) k_aggregate(const AggArgs a) {
     // sorted so that neighbours in the list gather from the same slice of the table; runs of
     // xcd_run consecutive item blocks are therefore handed to ONE XCD (the runs themselves still
     // rotate over the XCDs, which keeps the longest-first order balanced).
-    int64_t bx = blockIdx.x;
-    if (gridDim.y == 1 && a.xcd_run > 1) {
-        const int64_t RUN = a.xcd_run, SUPER = 8 * RUN;
-        const int64_t full = (int64_t)gridDim.x / SUPER * SUPER;
-        if (bx < full) {
-            const int64_t w = bx % SUPER;
-            bx = bx - w + (w & 7) * RUN + (w >> 3);
-        }
-    }
+    const int64_t bx = agg_item_block(a.xcd_run);
     const int64_t item_id = (bx * 4 + wave) * NG + grp;
     if (item_id >= a.n_items) return;   // whole groups leave together; no barriers are used below
     const int4 raw = reinterpret_cast<const int4 *>(a.items)[item_id];
@@ -380,13 +398,8 @@ gt_status launch(const AggArgs &a, hipStream_t st) {
     const unsigned gy = (unsigned)((a.F + tile - 1) / tile);
     if (a.n_items > 0) {
         const int64_t gx = (a.n_items + 4 * NG - 1) / (4 * NG);
-        // XCD runs: as long as possible for L2 reuse, but at least 64 rounds over the 8 XCDs so
-        // that the longest-first order stays balanced (measured on MI355X: 2^18-vertex graph,
-        // 512-byte rows, 0.58 -> 0.50 ms at 64; narrow rows and small grids prefer 16-32)
         AggArgs b = a;
-        int run = 1;
-        while (run < 64 && (int64_t)run * 2 * 512 <= gx) run *= 2;
-        b.xcd_run = run;
+        b.xcd_run = agg_xcd_run(gx);
         const int tr = gt_trace_open(a.trace_kind, a.F, a.n_rows, a.n_edges, st);
         k_aggregate<T, V, G, NP, U, VWM><<<dim3((unsigned)gx, gy), 256, 0, st>>>(b);
         gt_trace_close(tr, st);

@@ -28,6 +28,7 @@ struct EdgeArgs {
     void *W;              // output: [E][ldw] of T (edge-out) or float[E] (edge-dot)
     int64_t ldw;
     int64_t F;
+    int xcd_run;          // item blocks per XCD run (set at launch)
 };
 
 enum { EO_MUL = 0, EO_BCAST = 1 };
@@ -38,7 +39,7 @@ __global__ void __launch_bounds__(256) k_edge_out(const EdgeArgs a) {
     constexpr int NG = 64 / G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int gl = lane & (G - 1), grp = lane / G;
-    const int64_t item_id = ((int64_t)blockIdx.x * 4 + wave) * NG + grp;
+    const int64_t item_id = (agg_item_block(a.xcd_run) * 4 + wave) * NG + grp;
     if (item_id >= a.n_items) return;
     const int4 raw = reinterpret_cast<const int4 *>(a.items)[item_id];
     const int row = raw.x, e0 = raw.y, e1 = raw.z;
@@ -113,7 +114,7 @@ __global__ void __launch_bounds__(256) k_edge_dot(const EdgeArgs a) {
     constexpr int NG = 64 / G;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int gl = lane & (G - 1), grp = lane / G;
-    const int64_t item_id = ((int64_t)blockIdx.x * 4 + wave) * NG + grp;
+    const int64_t item_id = (agg_item_block(a.xcd_run) * 4 + wave) * NG + grp;
     if (item_id >= a.n_items) return;
     const int4 raw = reinterpret_cast<const int4 *>(a.items)[item_id];
     const int row = raw.x, e0 = raw.y, e1 = raw.z;
@@ -185,9 +186,11 @@ gt_status launch_edge(const EdgeArgs &a, int kind, hipStream_t st) {
     const unsigned gy = kind == 2 ? 1u : (unsigned)((a.F + tile - 1) / tile);
     const int64_t gx = (a.n_items + 4 * NG - 1) / (4 * NG);
     const dim3 grid((unsigned)gx, gy);
-    if (kind == 0) k_edge_out<T, V, G, NP, EO_MUL><<<grid, 256, 0, st>>>(a);
-    else if (kind == 1) k_edge_out<T, V, G, NP, EO_BCAST><<<grid, 256, 0, st>>>(a);
-    else k_edge_dot<T, V, G, NP><<<grid, 256, 0, st>>>(a);
+    EdgeArgs b = a;
+    b.xcd_run = agg_xcd_run(gx);
+    if (kind == 0) k_edge_out<T, V, G, NP, EO_MUL><<<grid, 256, 0, st>>>(b);
+    else if (kind == 1) k_edge_out<T, V, G, NP, EO_BCAST><<<grid, 256, 0, st>>>(b);
+    else k_edge_dot<T, V, G, NP><<<grid, 256, 0, st>>>(b);
     GT_LAUNCH_CHECK("k_edge");
     return GT_OK;
 }
