@@ -75,6 +75,8 @@ gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce,
     int64_t pass = F;
     if (vec && a.table_bytes > GT_COLUMN_PASS_TABLE_BYTES && F * (int64_t)es >= 512 && g->n_edges >= GT_COLUMN_PASS_MIN_EDGES)
         pass = 256 / (int64_t)es;
+    // what one launch gathers from: the slice of a pass, not the whole table (picks the unroll)
+    if (pass < F) a.table_bytes = n_in * pass * (int64_t)es;
     for (int64_t c0 = 0; c0 < F; c0 += pass) {
         const int64_t fp = F - c0 < pass ? F - c0 : pass;
         a.X = static_cast<const char *>(X) + c0 * es;

@@ -266,22 +266,41 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(const float *P, int split
     else static_cast<float *>(C)[row * ldc + col] = v;
 }
 
-int64_t pick_bn(int64_t N) { return N <= 32 ? 32 : (N <= 64 ? 64 : 128); }
-int64_t pick_bm(int64_t bn) { return bn == 128 ? 128 : 256; }
+// Workgroup tile.  Products with little work and so few 256- or 128-row tiles that most compute
+// units would idle (the layers of a sampled batch: a thousand rows, a 256 x 47 weight gradient) use
+// 64 x 64 tiles, one MFMA block per wavefront, and cut the reduction finer; they are bound by the
+// latency of one workgroup's k-loop, not by bytes or flops.
+struct TileShape { int64_t bm, bn; bool small; };
+
+TileShape pick_tile(int64_t M, int64_t N, int64_t K) {
+    const int64_t bn = N <= 32 ? 32 : (N <= 64 ? 64 : 128);
+    const int64_t bm = bn == 128 ? 128 : 256;
+    const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    const bool little = (double)M * (double)N * (double)K < 268435456.0;
+    if (little && tiles < 32) return TileShape{64, 64, true};
+    return TileShape{bm, bn, false};
+}
 
 struct SplitPlan { int splits; int64_t k_per_split; };
 
 SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
-    const int64_t bn = pick_bn(N), bm = pick_bm(bn);
-    const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+    const TileShape t = pick_tile(M, N, K);
+    const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
     SplitPlan p{1, (K + KT - 1) / KT * KT};
     if (K <= 0) { p.k_per_split = KT; return p; }
-    // The reduction is cut when the output has too few tiles to fill the chip: the weight-gradient
-    // shape (very long K), and a tall product over a very wide feature row with few rows
-    if (tiles >= 256 || K < 8 * KT) return p;
-    if (!transA && (tiles >= 128 || K < 1024)) return p;
-    int64_t want = (512 + tiles - 1) / tiles;                 // about two workgroups per CU
-    const int64_t max_by_len = K / (4 * KT);                  // at least 4 k-tiles per split
+    int64_t want, max_by_len;
+    if (t.small) {
+        if (tiles >= 128 || K < 2 * KT) return p;
+        want = (256 + tiles - 1) / tiles;                     // about one workgroup per CU
+        max_by_len = K / KT;                                  // at least one 64-wide k-range per split
+    } else {
+        // The reduction is cut when the output has too few tiles to fill the chip: the weight-gradient
+        // shape (very long K), and a tall product over a very wide feature row with few rows
+        if (tiles >= 256 || K < 8 * KT) return p;
+        if (!transA && (tiles >= 128 || K < 1024)) return p;
+        want = (512 + tiles - 1) / tiles;                     // about two workgroups per CU
+        max_by_len = K / (4 * KT);                            // at least 4 k-tiles per split
+    }
     if (want > max_by_len) want = max_by_len;
     if (want < 1) want = 1;
     int64_t kps = ((K + want - 1) / want + KT - 1) / KT * KT;
@@ -292,13 +311,15 @@ SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
 
 template <typename T, bool TA, bool TB>
 gt_status launch_gemm(GemmArgs g, int splits, hipStream_t st) {
-    const int64_t bn = pick_bn(g.N), bm = pick_bm(bn);
+    const TileShape t = pick_tile(g.M, g.N, g.K);
+    const int64_t bn = t.bn, bm = t.bm;
     g.ntn = (int)((g.N + bn - 1) / bn);
     g.ntm = (int)((g.M + bm - 1) / bm);
     dim3 grid(gemm_grid_x(g.ntm, g.ntn), 1, (unsigned)splits);
 #define GT_GEMM_CFG(VA_, VB_)                                                                         \
     do {                                                                                             \
-        if (bn == 128) k_gemm<T, TA, TB, 2, 2, 2, 2, VA_, VB_><<<grid, 256, 0, st>>>(g);             \
+        if (t.small) k_gemm<T, TA, TB, 2, 2, 1, 1, VA_, VB_><<<grid, 256, 0, st>>>(g);               \
+        else if (bn == 128) k_gemm<T, TA, TB, 2, 2, 2, 2, VA_, VB_><<<grid, 256, 0, st>>>(g);        \
         else if (bn == 64) k_gemm<T, TA, TB, 4, 1, 2, 2, VA_, VB_><<<grid, 256, 0, st>>>(g);         \
         else k_gemm<T, TA, TB, 4, 1, 2, 1, VA_, VB_><<<grid, 256, 0, st>>>(g);                       \
     } while (0)
