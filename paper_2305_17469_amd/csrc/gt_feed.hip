@@ -278,19 +278,24 @@ extern "C" gt_status gt_reindex(const int32_t *dst, int64_t n_dst, const int32_t
     while (bits < 32 && ((int64_t)1 << bits) < n_vertices) ++bits;
     const int passes = (bits + 7) / 8;
     const uint32_t *vin = nullptr;   // first pass: value = position
+    SortPasses sp{};
+    sp.passes = passes;
     for (int p = 0; p < passes; ++p) {
-        gt_status s = radix_pass(kA, vin, kB, vB, n, 8 * p, tmp, st);
-        if (s != GT_OK) return s;
+        sp.kin[p] = kA; sp.vin[p] = vin; sp.kout[p] = kB; sp.vout[p] = vB;
         uint32_t *t = kA; kA = kB; kB = t;
         t = vA; vA = vB; vB = t;
         vin = vA;
     }
+    {
+        const gt_status rs = radix_sort(sp, n, tmp, st);
+        if (rs != GT_OK) return rs;
+    }
     // kA / vA: ids ascending, positions ascending within equal ids
     k_mark_heads<<<nblocks(n + 1), PT, 0, st>>>(kA, vA, n, head, first);
     GT_LAUNCH_CHECK("k_mark_heads");
-    gt_status s = scan_exclusive(head, head, n + 1, tmp.scan_tmp, st);
-    if (s != GT_OK) return s;
-    s = scan_exclusive(first, first, n + 1, tmp.scan_tmp, st);
+    const int32_t *in2[2] = {head, first};
+    int32_t *out2[2] = {head, first};
+    gt_status s = scan_exclusive_batch(2, in2, out2, n + 1, tmp.scan_tmp, st);
     if (s != GT_OK) return s;
     if (n > 0) {
         k_group_ids<<<nblocks(n), PT, 0, st>>>(kA, vA, n, head, first, group, src_global);

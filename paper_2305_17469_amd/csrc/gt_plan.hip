@@ -211,7 +211,8 @@ struct PlanLayout {
     size_t in_deg, out_deg, rowptr_t, colidx_t, perm, ew_t, dinv, rdeg;
     size_t items_f, splits_f, items_b, splits_b;
     size_t counts;                       // 8 int32 read back by the host
-    size_t ca, cb, cc;                   // per-row count arrays (max(n_dst, n_src) + 1 each)
+    size_t ca, cb, cc;                   // per-row count arrays (max(n_dst, n_src) + 1 each), forward direction
+    size_t ca2, cb2, cc2;                // the same for the transposed direction
     size_t items_tmp, item_keys, item_keys2, item_idx, item_idx2;   // unsorted items, sort keys / indices
     size_t k0, v0, k1, v1;               // sort ping-pong (E each); k0, v0, v1 hold the coefficient arrays afterwards
     size_t hist, scan_tmp;
@@ -243,6 +244,9 @@ PlanLayout plan_layout(int64_t n_dst, int64_t n_src, int64_t E, bool has_ew) {
     L.ca = take((size_t)(nmax + 1) * 4);
     L.cb = take((size_t)(nmax + 1) * 4);
     L.cc = take((size_t)(nmax + 1) * 4);
+    L.ca2 = take((size_t)(nmax + 1) * 4);
+    L.cb2 = take((size_t)(nmax + 1) * 4);
+    L.cc2 = take((size_t)(nmax + 1) * 4);
     L.items_tmp = take((size_t)imax * sizeof(gt_item));
     L.item_keys = take((size_t)imax * 4);
     L.item_keys2 = take((size_t)imax * 4);
@@ -267,15 +271,16 @@ T *at(void *ws, size_t off) { return reinterpret_cast<T *>(static_cast<char *>(w
 // counts of one direction into cnt[0..2] (items, partials, splits): scans of the per-row counts;
 // the exclusive scan over n_rows + 1 entries (last input 0) leaves the total in element n_rows.
 gt_status count_direction(const int32_t *rowptr, int64_t n_rows, int chunk, void *ws, const PlanLayout &L,
-                          int32_t *cnt3, hipStream_t st) {
-    int32_t *ca = at<int32_t>(ws, L.ca), *cb = at<int32_t>(ws, L.cb), *cc = at<int32_t>(ws, L.cc);
+                          bool transposed, int32_t *cnt3, hipStream_t st) {
+    int32_t *ca = at<int32_t>(ws, transposed ? L.ca2 : L.ca), *cb = at<int32_t>(ws, transposed ? L.cb2 : L.cb);
+    int32_t *cc = at<int32_t>(ws, transposed ? L.cc2 : L.cc);
     int32_t *stmp = at<int32_t>(ws, L.scan_tmp);
     k_item_counts<<<nblocks(n_rows + 1), PT, 0, st>>>(rowptr, n_rows, chunk, ca, cb, cc);
     GT_LAUNCH_CHECK("k_item_counts");
     gt_status s;
-    if ((s = scan_exclusive(ca, ca, n_rows + 1, stmp, st)) != GT_OK) return s;
-    if ((s = scan_exclusive(cb, cb, n_rows + 1, stmp, st)) != GT_OK) return s;
-    if ((s = scan_exclusive(cc, cc, n_rows + 1, stmp, st)) != GT_OK) return s;
+    const int32_t *in3[3] = {ca, cb, cc};
+    int32_t *out3[3] = {ca, cb, cc};
+    if ((s = scan_exclusive_batch(3, in3, out3, n_rows + 1, stmp, st)) != GT_OK) return s;
     k_collect_counts<<<1, 64, 0, st>>>(ca, cb, cc, n_rows, cnt3);
     GT_LAUNCH_CHECK("k_collect_counts");
     return GT_OK;
@@ -284,10 +289,11 @@ gt_status count_direction(const int32_t *rowptr, int64_t n_rows, int chunk, void
 // items of one direction, sorted longest first (stable, so equal lengths keep row order).
 constexpr int64_t GT_SORT_ITEMS_MIN = 16384;
 gt_status build_direction(const int32_t *rowptr, const int32_t *nbr, int64_t n_in, int64_t n_rows, int chunk,
-                          int64_t n_items, void *ws, const PlanLayout &L, gt_item *items_out, gt_split *splits_out,
-                          hipStream_t st) {
+                          int64_t n_items, void *ws, const PlanLayout &L, bool transposed, gt_item *items_out,
+                          gt_split *splits_out, hipStream_t st) {
     if (n_rows <= 0 || n_items <= 0) return GT_OK;
-    int32_t *ca = at<int32_t>(ws, L.ca), *cb = at<int32_t>(ws, L.cb), *cc = at<int32_t>(ws, L.cc);
+    int32_t *ca = at<int32_t>(ws, transposed ? L.ca2 : L.ca), *cb = at<int32_t>(ws, transposed ? L.cb2 : L.cb);
+    int32_t *cc = at<int32_t>(ws, transposed ? L.cc2 : L.cc);
     gt_item *tmp = at<gt_item>(ws, L.items_tmp);
     uint32_t *keys = at<uint32_t>(ws, L.item_keys), *keys2 = at<uint32_t>(ws, L.item_keys2);
     uint32_t *idx = at<uint32_t>(ws, L.item_idx), *idx2 = at<uint32_t>(ws, L.item_idx2);
@@ -374,12 +380,15 @@ extern "C" gt_status gt_graph_create(gt_graph **out, int64_t n_dst, int64_t n_sr
         const int passes = (bits + 7) / 8;
         const uint32_t *kin = reinterpret_cast<const uint32_t *>(colidx);
         const uint32_t *vin = nullptr;
+        SortPasses sp{};
+        sp.passes = passes;
         for (int p = 0; p < passes; ++p) {
             uint32_t *ko = (p & 1) ? k1 : k0;
             uint32_t *vo = (p == passes - 1) ? reinterpret_cast<uint32_t *>(g->perm) : ((p & 1) ? v1 : v0);
-            if ((s = radix_pass(kin, vin, ko, vo, E, 8 * p, t, st)) != GT_OK) return fail(s);
+            sp.kin[p] = kin; sp.vin[p] = vin; sp.kout[p] = ko; sp.vout[p] = vo;
             kin = ko; vin = vo;
         }
+        if ((s = radix_sort(sp, E, t, st)) != GT_OK) return fail(s);
         sorted_keys = kin;
     }
     if (n_src >= 0) {
@@ -403,11 +412,10 @@ extern "C" gt_status gt_graph_create(gt_graph **out, int64_t n_dst, int64_t n_sr
     // work-list sizes of both directions, read back once
     int32_t *d_counts = at<int32_t>(ws, L.counts);
     int32_t h_counts[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    // forward counts are consumed (scanned arrays) before the transposed direction reuses them,
-    // so the forward items are filled between the two counting steps.
     g->chunk = gt_chunk_for(E);
-    if ((s = count_direction(rowptr, n_dst, g->chunk, ws, L, d_counts, st)) != GT_OK) return fail(s);
-    PLAN_HIP(hipMemcpyAsync(h_counts, d_counts, 3 * 4, hipMemcpyDeviceToHost, st));
+    if ((s = count_direction(rowptr, n_dst, g->chunk, ws, L, false, d_counts, st)) != GT_OK) return fail(s);
+    if ((s = count_direction(g->rowptr_t, n_src, g->chunk, ws, L, true, d_counts + 4, st)) != GT_OK) return fail(s);
+    PLAN_HIP(hipMemcpyAsync(h_counts, d_counts, 8 * 4, hipMemcpyDeviceToHost, st));
     PLAN_HIP(hipStreamSynchronize(st));
     g->fwd.rowptr = rowptr; g->fwd.nbr = colidx; g->fwd.wt = ew; g->fwd.n_rows = n_dst;
     g->fwd.coef_sym = g->coef_sym_f;
@@ -415,20 +423,16 @@ extern "C" gt_status gt_graph_create(gt_graph **out, int64_t n_dst, int64_t n_sr
     g->fwd.items = at<gt_item>(ws, L.items_f); g->fwd.splits = at<gt_split>(ws, L.splits_f);
     if (g->fwd.n_items > max_items(n_dst, E) || g->fwd.n_splits > max_splits(E))
         return fail(gt_fail(GT_ERR_INTERNAL, "gt_graph_create: forward work list exceeds its bound (is rowptr valid?)"));
-    if ((s = build_direction(rowptr, colidx, n_src, n_dst, g->chunk, g->fwd.n_items, ws, L, at<gt_item>(ws, L.items_f),
-                             at<gt_split>(ws, L.splits_f), st)) != GT_OK) return fail(s);
-
-    if ((s = count_direction(g->rowptr_t, n_src, g->chunk, ws, L, d_counts + 4, st)) != GT_OK) return fail(s);
-    PLAN_HIP(hipMemcpyAsync(h_counts + 4, d_counts + 4, 3 * 4, hipMemcpyDeviceToHost, st));
-    PLAN_HIP(hipStreamSynchronize(st));
     g->bwd.rowptr = g->rowptr_t; g->bwd.nbr = g->colidx_t; g->bwd.wt = g->ew_t; g->bwd.n_rows = n_src;
     g->bwd.coef_sym = g->coef_sym_b; g->bwd.coef_mean = g->coef_mean_b;
     g->bwd.n_items = h_counts[4]; g->bwd.n_partials = h_counts[5]; g->bwd.n_splits = h_counts[6];
     g->bwd.items = at<gt_item>(ws, L.items_b); g->bwd.splits = at<gt_split>(ws, L.splits_b);
     if (g->bwd.n_items > max_items(n_src, E) || g->bwd.n_splits > max_splits(E))
         return fail(gt_fail(GT_ERR_INTERNAL, "gt_graph_create: transposed work list exceeds its bound"));
-    if ((s = build_direction(g->rowptr_t, g->colidx_t, n_dst, n_src, g->chunk, g->bwd.n_items, ws, L, at<gt_item>(ws, L.items_b),
-                             at<gt_split>(ws, L.splits_b), st)) != GT_OK) return fail(s);
+    if ((s = build_direction(rowptr, colidx, n_src, n_dst, g->chunk, g->fwd.n_items, ws, L, false,
+                             at<gt_item>(ws, L.items_f), at<gt_split>(ws, L.splits_f), st)) != GT_OK) return fail(s);
+    if ((s = build_direction(g->rowptr_t, g->colidx_t, n_dst, n_src, g->chunk, g->bwd.n_items, ws, L, true,
+                             at<gt_item>(ws, L.items_b), at<gt_split>(ws, L.splits_b), st)) != GT_OK) return fail(s);
     PLAN_HIP(hipStreamSynchronize(st));
 #undef PLAN_HIP
 #undef PLAN_LAUNCH

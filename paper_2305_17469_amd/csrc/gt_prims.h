@@ -76,9 +76,81 @@ size_t scan_tmp_ints(int64_t n) {
     return t + 64;
 }
 
+// Up to three arrays of the same short length in one launch: one workgroup of 1,024 threads per
+// array walks it in steps of 8,192 elements and carries the running total.  A sampled batch's scans
+// (a few thousand rows) are bound by launch latency; this takes one launch where the tiled form
+// takes three per array.
+constexpr int SCAN_SMALL_THREADS = 1024;
+constexpr int64_t SCAN_SMALL_MAX = 65536;
+struct ScanBatch { const int32_t *in[3]; int32_t *out[3]; };
+
+__global__ void __launch_bounds__(SCAN_SMALL_THREADS) k_scan_small(const ScanBatch b, int64_t n) {
+    __shared__ int32_t wave_sums[SCAN_SMALL_THREADS / 64];
+    const int32_t *in = b.in[blockIdx.x];
+    int32_t *out = b.out[blockIdx.x];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t carry = 0;
+    for (int64_t t0 = 0; t0 < n; t0 += (int64_t)SCAN_SMALL_THREADS * SCAN_PER_THREAD) {
+        const int64_t base = t0 + (int64_t)threadIdx.x * SCAN_PER_THREAD;
+        int32_t v[SCAN_PER_THREAD];
+        int32_t s = 0;
+#pragma unroll
+        for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+            v[i] = (base + i < n) ? in[base + i] : 0;
+            s += v[i];
+        }
+        int32_t inc = s;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int32_t o = __shfl_up(inc, d, 64);
+            if (lane >= d) inc += o;
+        }
+        if (lane == 63) wave_sums[wave] = inc;
+        __syncthreads();
+        int32_t before = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < SCAN_SMALL_THREADS / 64; ++w) {
+            const int32_t ws = wave_sums[w];
+            if (w < wave) before += ws;
+            total += ws;
+        }
+        __syncthreads();   // wave_sums is rewritten in the next step
+        int32_t ex = carry + before + inc - s;
+#pragma unroll
+        for (int i = 0; i < SCAN_PER_THREAD; ++i) {
+            if (base + i < n) out[base + i] = ex;
+            ex += v[i];
+        }
+        carry += total;
+    }
+}
+
+gt_status scan_exclusive(const int32_t *in, int32_t *out, int64_t n, int32_t *tmp, hipStream_t st);
+
+// out[k][i] = sum_{j<i} in[k][j] for `count` (1..3) arrays of n elements each (in == out allowed).
+// tmp: scan_tmp_ints(n) int32.
+gt_status scan_exclusive_batch(int count, const int32_t *const *in, int32_t *const *out, int64_t n, int32_t *tmp,
+                               hipStream_t st) {
+    if (n <= 0 || count <= 0) return GT_OK;
+    if (count > 3) return gt_fail(GT_ERR_INTERNAL, "scan_exclusive_batch: more than three arrays");
+    if (n <= SCAN_SMALL_MAX) {
+        ScanBatch b{};
+        for (int k = 0; k < count; ++k) { b.in[k] = in[k]; b.out[k] = out[k]; }
+        k_scan_small<<<count, SCAN_SMALL_THREADS, 0, st>>>(b, n);
+        GT_LAUNCH_CHECK("k_scan_small");
+        return GT_OK;
+    }
+    for (int k = 0; k < count; ++k) {
+        const gt_status s = scan_exclusive(in[k], out[k], n, tmp, st);
+        if (s != GT_OK) return s;
+    }
+    return GT_OK;
+}
+
 // out[i] = sum_{j<i} in[j] for i < n (in == out allowed).  tmp: scan_tmp_ints(n) int32.
 gt_status scan_exclusive(const int32_t *in, int32_t *out, int64_t n, int32_t *tmp, hipStream_t st) {
     if (n <= 0) return GT_OK;
+    if (n <= SCAN_SMALL_MAX) return scan_exclusive_batch(1, &in, &out, n, tmp, st);
     const int64_t tiles = (n + SCAN_TILE - 1) / SCAN_TILE;
     if (tiles == 1) {
         k_scan_tiles<<<1, SCAN_THREADS, 0, st>>>(in, out, n, nullptr);
@@ -229,6 +301,103 @@ __global__ void __launch_bounds__(RS_THREADS) k_rs_pass_small(const uint32_t *ke
     rs_scatter_tile(keys_in, vals_in, keys_out, vals_out, n, shift, digit_base + before);
 }
 
+// All passes of a sort of at most 16,384 pairs in one launch: a single workgroup of 16 wavefronts,
+// each owning 1,024 consecutive items, runs the passes back to back through the caller's ping-pong
+// buffers (a workgroup barrier orders one pass's stores before the next pass's loads).  The ranks
+// are built exactly as in rs_scatter_tile, so the order is the same stable one.  A sampled batch
+// sorts a few thousand keys in 2-3 passes; this takes one launch instead of one per pass.
+constexpr int RS_ONE_THREADS = 1024;
+constexpr int RS_ONE_WAVES = RS_ONE_THREADS / 64;
+constexpr int64_t RS_ONE_MAX = (int64_t)RS_ONE_WAVES * RS_WAVE_ITEMS;
+constexpr int RS_MAX_PASSES = 4;
+
+struct SortPasses {
+    const uint32_t *kin[RS_MAX_PASSES];
+    const uint32_t *vin[RS_MAX_PASSES];   // null: value = position
+    uint32_t *kout[RS_MAX_PASSES];
+    uint32_t *vout[RS_MAX_PASSES];
+    int passes;                           // pass p sorts by bits [8p, 8p + 8)
+};
+
+__global__ void __launch_bounds__(RS_ONE_THREADS) k_rs_sort_one(const SortPasses a, int64_t n) {
+    __shared__ int32_t cnt[RS_ONE_WAVES][256];
+    __shared__ int32_t wbase[RS_ONE_WAVES][256];
+    __shared__ int32_t wsum[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint64_t lt_mask = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+    const int64_t wstart = (int64_t)wave * RS_WAVE_ITEMS;
+    for (int p = 0; p < a.passes; ++p) {
+        const uint32_t *keys_in = a.kin[p], *vals_in = a.vin[p];
+        uint32_t *keys_out = a.kout[p], *vals_out = a.vout[p];
+        const int shift = 8 * p;
+        for (int i = threadIdx.x; i < RS_ONE_WAVES * 256; i += RS_ONE_THREADS) (&cnt[0][0])[i] = 0;
+        __syncthreads();
+        uint32_t key[RS_CHUNKS];
+        int32_t rank[RS_CHUNKS];
+#pragma unroll
+        for (int c = 0; c < RS_CHUNKS; ++c) {
+            const int64_t q = wstart + (int64_t)c * 64 + lane;
+            key[c] = q < n ? keys_in[q] : 0u;
+        }
+#pragma unroll
+        for (int c = 0; c < RS_CHUNKS; ++c) {
+            rank[c] = 0;
+            if (wstart + (int64_t)c * 64 >= n) continue;   // wavefront-uniform: the chunk is empty
+            const bool valid = wstart + (int64_t)c * 64 + lane < n;
+            const uint32_t digit = (key[c] >> shift) & 255u;
+            uint64_t m = __ballot(valid);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const bool bit = (digit >> b) & 1u;
+                const uint64_t bal = __ballot(valid && bit);
+                m &= bit ? bal : ~bal;
+            }
+            const int before = __popcll(m & lt_mask);
+            int32_t prev = 0;
+            if (valid) prev = cnt[wave][digit];
+            rank[c] = prev + before;
+            if (valid && before == 0) cnt[wave][digit] = prev + __popcll(m);
+        }
+        __syncthreads();
+        // threads 0..255 <-> digits: per-wavefront bases within the digit, then the digits' starts
+        const int d = threadIdx.x & 255;
+        int32_t tot = 0;
+        if (threadIdx.x < 256) {
+#pragma unroll
+            for (int w = 0; w < RS_ONE_WAVES; ++w) {
+                wbase[w][d] = tot;
+                tot += cnt[w][d];
+            }
+        }
+        int32_t inc = tot;
+#pragma unroll
+        for (int s = 1; s < 64; s <<= 1) {
+            const int32_t o = __shfl_up(inc, s, 64);
+            if (lane >= s) inc += o;
+        }
+        if (threadIdx.x < 256 && lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            int32_t start = inc - tot;
+            for (int w = 0; w < wave; ++w) start += wsum[w];
+#pragma unroll
+            for (int w = 0; w < RS_ONE_WAVES; ++w) wbase[w][d] += start;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < RS_CHUNKS; ++c) {
+            const int64_t q = wstart + (int64_t)c * 64 + lane;
+            if (q < n) {
+                const uint32_t digit = (key[c] >> shift) & 255u;
+                const int64_t dst = (int64_t)wbase[wave][digit] + rank[c];
+                keys_out[dst] = key[c];
+                vals_out[dst] = vals_in ? vals_in[q] : (uint32_t)q;
+            }
+        }
+        __syncthreads();   // this pass's stores are visible to the whole workgroup before the next pass loads
+    }
+}
+
 struct SortTmp {
     int32_t *hist;      // 256 * nblk
     int32_t *scan_tmp;  // scan_tmp_ints(256 * nblk)
@@ -251,6 +420,22 @@ gt_status radix_pass(const uint32_t *kin, const uint32_t *vin, uint32_t *kout, u
     if (s != GT_OK) return s;
     k_rs_scatter<<<nblk, RS_THREADS, 0, st>>>(kin, vin, kout, vout, n, shift, t.hist, nblk);
     GT_LAUNCH_CHECK("k_rs_scatter");
+    return GT_OK;
+}
+
+// Runs the passes of `a` in order: one launch when the input is short, one pass at a time otherwise.
+gt_status radix_sort(const SortPasses &a, int64_t n, const SortTmp &t, hipStream_t st) {
+    if (n <= 0 || a.passes <= 0) return GT_OK;
+    if (a.passes > RS_MAX_PASSES) return gt_fail(GT_ERR_INTERNAL, "radix_sort: too many passes");
+    if (n <= RS_ONE_MAX) {
+        k_rs_sort_one<<<1, RS_ONE_THREADS, 0, st>>>(a, n);
+        GT_LAUNCH_CHECK("k_rs_sort_one");
+        return GT_OK;
+    }
+    for (int p = 0; p < a.passes; ++p) {
+        const gt_status s = radix_pass(a.kin[p], a.vin[p], a.kout[p], a.vout[p], n, 8 * p, t, st);
+        if (s != GT_OK) return s;
+    }
     return GT_OK;
 }
 
