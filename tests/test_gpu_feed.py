@@ -68,7 +68,11 @@ def test_sampling_edge_cases():
 
 
 @pytest.mark.parametrize("n_dst,n_picked,universe", [(0, 0, 10), (1, 0, 10), (0, 50, 20), (5, 40, 12), (300, 9000, 4000),
-                                                       (5000, 120000, 1 << 20), (70000, 500000, 1 << 17)])
+                                                       (5000, 120000, 1 << 20), (70000, 500000, 1 << 17),
+                                                       # around the single-launch sort's capacity of 16,384 pairs,
+                                                       # ids of one to four bytes, and the one-launch pass (<= 32 K)
+                                                       (150, 16234, 200), (384, 16000, 1 << 30), (1000, 15384, 70000),
+                                                       (1000, 15385, 70000), (2000, 30000, 1 << 25), (1, 1023, 1 << 16)])
 def test_reindex_matches_oracle(n_dst, n_picked, universe):
     from paper_2305_17469_amd import binding as B
     rng = np.random.default_rng(n_dst + n_picked)

@@ -30,6 +30,14 @@ def _cases():
     out.append(("rmat13_deg50", c["rowptr"], c["colidx"], c["n_src"]))
     for b in configs.sage_minibatch(12, 64)["blocks"]:
         out.append(("sage_block_%d" % b["n_dst"], b["rowptr"], b["colidx"], b["n_src"]))
+    # around the single-launch sort's capacity of 16,384 entries, source ids of one to four bytes
+    # (unsorted rows with repeats: the plan takes any CSR)
+    for E, n_src in ((16384, 200), (16384, 70000), (16385, 70000), (9000, 1 << 25), (30000, 300)):
+        rng = np.random.default_rng(E + n_src)
+        deg = rng.multinomial(E, np.ones(700) / 700)
+        rp = np.concatenate([[0], np.cumsum(deg)]).astype(np.int32)
+        ci = rng.integers(0, n_src, E).astype(np.int32)
+        out.append(("random_E%d_src%d" % (E, n_src), rp, ci, n_src))
     return out
 
 
