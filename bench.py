@@ -269,6 +269,50 @@ def decide_sweep(args):
     print(json.dumps(dict(metric="decide_sweep", cases=len(rows), misses=misses, rows=rows)))
 
 
+def uniform_sweep(args):
+    """The aggregation kernel alone on graphs without skew: every destination has exactly `deg`
+    in-neighbours drawn uniformly (seeded) from the sources, so no source row is reused from cache
+    and the gather model's algorithmic bytes are what the memory system really moves.  Three tables:
+    1 GiB of 512-byte bf16 rows, 134 MB of 512-byte fp32 rows (fits the last-level cache), 4.3 GB of
+    4 KB fp32 rows; 2^25 edges each.  Timed with HIP events around the launches of each case."""
+    import numpy as np
+    import torch
+    from paper_2305_17469_amd import binding as B
+    dev = torch.device("cuda:0")
+    E = 1 << 25
+    rows = []
+    for n_src, F, tdt, degs in ((1 << 21, 256, torch.bfloat16, (1, 4, 16, 64, 512)),
+                                (1 << 18, 128, torch.float32, (4, 16, 64, 512)),
+                                (1 << 20, 1024, torch.float32, (4, 16, 64, 512))):
+        X = torch.randn((n_src, F), device=dev, dtype=torch.float32).to(tdt)
+        s = X.element_size()
+        for deg in degs:
+            n_dst = E // deg
+            rp = torch.arange(0, E + 1, deg, dtype=torch.int32, device=dev)
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(1000 + deg)
+            ci = torch.randint(0, n_src, (E,), dtype=torch.int32, device=dev, generator=gen)
+            g = B.Graph(rp, ci, n_src)
+            Y = torch.empty((n_dst, F), device=dev, dtype=tdt)
+            reps = 3 if F >= 1024 else 10
+            for _ in range(2):
+                B.gt_aggregate_fwd(g, "sum", X, out=Y)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                B.gt_aggregate_fwd(g, "sum", X, out=Y)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            alg = E * F * s + n_dst * F * s + 4 * E + 4 * (n_dst + 1)
+            rows.append(dict(n_src=n_src, F=F, dtype=str(tdt)[6:], deg=deg, n_dst=n_dst, ms=ms, alg_gb=alg / 1e9,
+                             tb_per_s=alg / ms / 1e9, frac_of_8tb=alg / ms / 1e9 / 8.0))
+            del g, Y, rp, ci
+        del X
+    print(json.dumps(dict(metric="aggregation on uniform graphs, algorithmic TB/s", edges=E, rows=rows)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -293,6 +337,8 @@ def main():
     ap.add_argument("--decide-sweep", action="store_true",
                     help="check AUTO's placement against all four timed placements on 60 shapes outside the workloads")
     ap.add_argument("--feed-seeds", type=int, default=300, help="seed vertices per batch for --feed-bench")
+    ap.add_argument("--uniform-sweep", action="store_true",
+                    help="aggregation alone on graphs with uniform degrees and uniform sources (no cache reuse)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
     args = ap.parse_args()
@@ -311,6 +357,8 @@ def main():
         return feed_bench(args)
     if args.decide_sweep:
         return decide_sweep(args)
+    if args.uniform_sweep:
+        return uniform_sweep(args)
     dev = torch.device("cuda:0")
     t0 = time.time()
     cfg = build_workload(args.config, args.scale)
