@@ -218,8 +218,16 @@ typedef struct {
     double alpha_bwd, beta_bwd, gamma_bwd, delta_bwd;
 } gt_cost_coeffs;
 
-gt_status gt_cost_get(gt_cost_coeffs *c /* host */);
-gt_status gt_cost_set(const gt_cost_coeffs *c /* host */);
+gt_status gt_cost_get(gt_cost_coeffs *c /* host */);          /* the fp32 set */
+gt_status gt_cost_set(const gt_cost_coeffs *c /* host */);    /* installs c for every data type */
+
+/* One coefficient set per data type (the paper fits one set per system; bf16 kernels move half
+ * the bytes and use a faster matrix pipe, so their times scale differently from fp32 ones).
+ * gt_layer_decide and the GT_AUTO orders use the set of the layer's dtype.  Coefficients must be
+ * finite and >= 0 (GT_ERR_INVALID_ARG otherwise).  The sets are process-wide and not locked:
+ * set or calibrate them before layers are decided on other threads. */
+gt_status gt_cost_get_dtype(gt_dtype dtype, gt_cost_coeffs *c /* host */);
+gt_status gt_cost_set_dtype(gt_dtype dtype, const gt_cost_coeffs *c /* host */);
 
 /* The four benefit values of the paper's cost-model table for the given sizes and coefficients
  * (pure host arithmetic): aggr-first FWP/BWP, comb-first FWP/BWP.  first_layer != 0 uses n_src
@@ -260,9 +268,13 @@ gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_order fwd_u
 /* Refit the cost coefficients by least squares from kernel times measured on this device
  * (paper: coefficients are fitted from measured kernel times at the start of training).  Runs
  * synthetic aggregations and combinations inside `ws` (device, >= gt_calibrate_ws_size bytes);
- * synchronises.  The fitted values are installed (as by gt_cost_set) and returned in *fitted. */
+ * synchronises.  gt_calibrate_dtype fits and installs the set of one data type (as by
+ * gt_cost_set_dtype) and returns it in *fitted; gt_calibrate does so for bf16 and then fp32 and
+ * returns the fp32 set. */
 gt_status gt_calibrate_ws_size(size_t *ws_bytes /* host */);
 gt_status gt_calibrate(void *ws, size_t ws_bytes, gt_cost_coeffs *fitted /* host, may be NULL */, void *stream);
+gt_status gt_calibrate_dtype(gt_dtype dtype, void *ws, size_t ws_bytes, gt_cost_coeffs *fitted /* host, may be NULL */,
+                             void *stream);
 
 /* ------------------------------------------------------------------------------------------
  * Batch preparation on the GPU: neighbour sampling (S), renumbering (R) and embedding lookup (K)

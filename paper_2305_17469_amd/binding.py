@@ -49,8 +49,8 @@ class GtError(RuntimeError):
 
 EXPORTS = ["gt_graph_plan_size", "gt_graph_create", "gt_graph_destroy", "gt_graph_outputs", "gt_graph_info",
            "gt_graph_validate", "gt_aggregate_ws_size", "gt_aggregate_fwd", "gt_aggregate_bwd", "gt_combine_ws_size",
-           "gt_combine", "gt_neighbor_apply_fwd", "gt_neighbor_apply_bwd", "gt_pull_fwd", "gt_pull_bwd", "gt_cost_get", "gt_cost_set", "gt_cost_benefits", "gt_layer_decide", "gt_layer_ws_size",
-           "gt_layer_fwd", "gt_layer_bwd", "gt_calibrate_ws_size", "gt_calibrate", "gt_trace_enable", "gt_trace_reset",
+           "gt_combine", "gt_neighbor_apply_fwd", "gt_neighbor_apply_bwd", "gt_pull_fwd", "gt_pull_bwd", "gt_cost_get", "gt_cost_set", "gt_cost_get_dtype", "gt_cost_set_dtype", "gt_cost_benefits", "gt_layer_decide", "gt_layer_ws_size",
+           "gt_layer_fwd", "gt_layer_bwd", "gt_calibrate_ws_size", "gt_calibrate", "gt_calibrate_dtype", "gt_trace_enable", "gt_trace_reset",
            "gt_trace_count", "gt_trace_get", "gt_sample_ws_size", "gt_sample_neighbors", "gt_reindex_ws_size",
            "gt_reindex", "gt_lookup", "gt_status_string",
            "gt_last_error", "gt_version"]
@@ -84,6 +84,8 @@ lib.gt_pull_bwd.argtypes = [c_void_p, c_int, c_int, c_int, c_int64, c_void_p, c_
                             c_int64, c_void_p, c_int64, c_void_p, c_int64, c_void_p, c_size_t, c_void_p]
 lib.gt_cost_get.argtypes = [POINTER(gt_cost_coeffs)]
 lib.gt_cost_set.argtypes = [POINTER(gt_cost_coeffs)]
+lib.gt_cost_get_dtype.argtypes = [c_int, POINTER(gt_cost_coeffs)]
+lib.gt_cost_set_dtype.argtypes = [c_int, POINTER(gt_cost_coeffs)]
 lib.gt_cost_benefits.argtypes = [POINTER(gt_cost_coeffs), c_int64, c_int64, c_int64, c_int64, c_int64, c_int] + \
     [POINTER(c_double)] * 4
 lib.gt_layer_decide.argtypes = [c_void_p, POINTER(gt_layer_desc), POINTER(c_int), POINTER(c_int)]
@@ -100,6 +102,7 @@ lib.gt_trace_get.argtypes = [c_int64, POINTER(c_int), POINTER(c_int64), POINTER(
                              POINTER(c_double)]
 lib.gt_calibrate_ws_size.argtypes = [POINTER(c_size_t)]
 lib.gt_calibrate.argtypes = [c_void_p, c_size_t, POINTER(gt_cost_coeffs), c_void_p]
+lib.gt_calibrate_dtype.argtypes = [c_int, c_void_p, c_size_t, POINTER(gt_cost_coeffs), c_void_p]
 
 
 lib.gt_sample_ws_size.argtypes = [c_int64, POINTER(c_size_t)]
@@ -359,6 +362,24 @@ def gt_cost_set(c):
     _check(lib.gt_cost_set(byref(c)))
 
 
+def _dtype_code(dtype):
+    if dtype in (torch.bfloat16, "bf16"):
+        return 1
+    if dtype in (torch.float32, "f32"):
+        return 0
+    raise ValueError("dtype must be f32 or bf16")
+
+
+def gt_cost_get_dtype(dtype):
+    c = gt_cost_coeffs()
+    _check(lib.gt_cost_get_dtype(_dtype_code(dtype), byref(c)))
+    return c
+
+
+def gt_cost_set_dtype(dtype, c):
+    _check(lib.gt_cost_set_dtype(_dtype_code(dtype), byref(c)))
+
+
 def gt_cost_benefits(c, n_src, n_dst, n_edge, n_feat, n_hid, first_layer=False):
     v = [c_double() for _ in range(4)]
     _check(lib.gt_cost_benefits(byref(c), n_src, n_dst, n_edge, n_feat, n_hid, int(first_layer), *[byref(x) for x in v]))
@@ -371,6 +392,15 @@ def gt_calibrate(device="cuda"):
     ws = _ws(need.value, device)
     c = gt_cost_coeffs()
     _check(lib.gt_calibrate(_ptr(ws), ws.numel(), byref(c), _stream()))
+    return c
+
+
+def gt_calibrate_dtype(dtype, device="cuda"):
+    need = c_size_t()
+    _check(lib.gt_calibrate_ws_size(byref(need)))
+    ws = _ws(need.value, device)
+    c = gt_cost_coeffs()
+    _check(lib.gt_calibrate_dtype(_dtype_code(dtype), _ptr(ws), ws.numel(), byref(c), _stream()))
     return c
 
 

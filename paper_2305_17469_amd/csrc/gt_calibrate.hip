@@ -99,7 +99,9 @@ extern "C" gt_status gt_calibrate_ws_size(size_t *ws_bytes) {
     return GT_OK;
 }
 
-extern "C" gt_status gt_calibrate(void *ws, size_t ws_bytes, gt_cost_coeffs *fitted, void *stream) {
+extern "C" gt_status gt_calibrate_dtype(gt_dtype dtype, void *ws, size_t ws_bytes, gt_cost_coeffs *fitted,
+                                        void *stream) {
+    if (dtype != GT_F32 && dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "gt_calibrate_dtype: unknown dtype");
     CalLayout L;
     gt_status s = cal_layout(&L);
     if (s != GT_OK) return s;
@@ -109,12 +111,15 @@ extern "C" gt_status gt_calibrate(void *ws, size_t ws_bytes, gt_cost_coeffs *fit
     char *base = static_cast<char *>(ws);
     int32_t *rowptr = reinterpret_cast<int32_t *>(base + L.rowptr);
     int32_t *colidx = reinterpret_cast<int32_t *>(base + L.colidx);
-    float *X = reinterpret_cast<float *>(base + L.X), *Y = reinterpret_cast<float *>(base + L.Y);
-    float *W = reinterpret_cast<float *>(base + L.W);
+    // The buffers are sized for fp32 and filled with fp32 values in (-0.5, 0.5); read as bf16 the
+    // same bytes are finite values of the same range (the timing does not depend on them).
+    float *Xf = reinterpret_cast<float *>(base + L.X), *Yf = reinterpret_cast<float *>(base + L.Y);
+    float *Wf = reinterpret_cast<float *>(base + L.W);
+    void *X = Xf, *Y = Yf, *W = Wf;
     const int64_t nx = CAL_N * CAL_FMAX;
-    k_cal_fill<<<(unsigned)((nx + 255) / 256), 256, 0, st>>>(X, nx);
-    k_cal_fill<<<(unsigned)((nx + 255) / 256), 256, 0, st>>>(Y, nx);
-    k_cal_fill<<<(unsigned)((CAL_FMAX * CAL_FMAX + 255) / 256), 256, 0, st>>>(W, CAL_FMAX * CAL_FMAX);
+    k_cal_fill<<<(unsigned)((nx + 255) / 256), 256, 0, st>>>(Xf, nx);
+    k_cal_fill<<<(unsigned)((nx + 255) / 256), 256, 0, st>>>(Yf, nx);
+    k_cal_fill<<<(unsigned)((CAL_FMAX * CAL_FMAX + 255) / 256), 256, 0, st>>>(Wf, CAL_FMAX * CAL_FMAX);
     GT_LAUNCH_CHECK("k_cal_fill");
 
     Fit2 agg_f, agg_b, gemm_f, gemm_b;
@@ -129,11 +134,11 @@ extern "C" gt_status gt_calibrate(void *ws, size_t ws_bytes, gt_cost_coeffs *fit
         if (s != GT_OK) return s;
         for (int64_t F : widths) {
             double t = 0;
-            s = time_it([&] { return gt_aggregate_run(g, false, GT_SUM, GT_F32, GT_F32, F, X, CAL_FMAX, Y, CAL_FMAX, nullptr,
+            s = time_it([&] { return gt_aggregate_run(g, false, GT_SUM, dtype, dtype, F, X, CAL_FMAX, Y, CAL_FMAX, nullptr,
                                                       GT_ACT_NONE, base + L.agg_ws, (size_t)64 << 20, st); }, st, &t);
             if (s != GT_OK) { gt_graph_destroy(g); return s; }
             agg_f.add((double)F * E, (double)F * CAL_N, t);
-            s = time_it([&] { return gt_aggregate_run(g, true, GT_SUM, GT_F32, GT_F32, F, Y, CAL_FMAX, X, CAL_FMAX, nullptr,
+            s = time_it([&] { return gt_aggregate_run(g, true, GT_SUM, dtype, dtype, F, Y, CAL_FMAX, X, CAL_FMAX, nullptr,
                                                       GT_ACT_NONE, base + L.agg_ws, (size_t)64 << 20, st); }, st, &t);
             if (s != GT_OK) { gt_graph_destroy(g); return s; }
             agg_b.add((double)F * E, (double)F * CAL_N, t);
@@ -144,12 +149,12 @@ extern "C" gt_status gt_calibrate(void *ws, size_t ws_bytes, gt_cost_coeffs *fit
     for (auto &sh : shapes) {
         const int64_t in = sh[0], out = sh[1];
         double t = 0;
-        s = time_it([&] { return gt_gemm_run("gt_calibrate", GT_F32, 0, 0, CAL_N, out, in, X, CAL_FMAX, W, out, nullptr, nullptr,
-                                             GT_ACT_NONE, nullptr, 0, Y, CAL_FMAX, GT_F32, nullptr, 0, st); }, st, &t);
+        s = time_it([&] { return gt_gemm_run("gt_calibrate", dtype, 0, 0, CAL_N, out, in, X, CAL_FMAX, W, out, nullptr, nullptr,
+                                             GT_ACT_NONE, nullptr, 0, Y, CAL_FMAX, dtype, nullptr, 0, st); }, st, &t);
         if (s != GT_OK) return s;
         gemm_f.add((double)CAL_N * in * out, (double)CAL_N * out, t);
-        s = time_it([&] { return gt_gemm_run("gt_calibrate", GT_F32, 0, 1, CAL_N, in, out, Y, CAL_FMAX, W, out, nullptr, nullptr,
-                                             GT_ACT_NONE, nullptr, 0, X, CAL_FMAX, GT_F32, nullptr, 0, st); }, st, &t);
+        s = time_it([&] { return gt_gemm_run("gt_calibrate", dtype, 0, 1, CAL_N, in, out, Y, CAL_FMAX, W, out, nullptr, nullptr,
+                                             GT_ACT_NONE, nullptr, 0, X, CAL_FMAX, dtype, nullptr, 0, st); }, st, &t);
         if (s != GT_OK) return s;
         gemm_b.add((double)CAL_N * in * out, (double)CAL_N * in, t);
     }
@@ -158,8 +163,14 @@ extern "C" gt_status gt_calibrate(void *ws, size_t ws_bytes, gt_cost_coeffs *fit
     gemm_b.solve(&c.alpha_bwd, &c.beta_bwd);
     agg_f.solve(&c.gamma_fwd, &c.delta_fwd);
     agg_b.solve(&c.gamma_bwd, &c.delta_bwd);
-    s = gt_cost_set(&c);
+    s = gt_cost_set_dtype(dtype, &c);
     if (s != GT_OK) return s;
     if (fitted) *fitted = c;
     return GT_OK;
+}
+
+extern "C" gt_status gt_calibrate(void *ws, size_t ws_bytes, gt_cost_coeffs *fitted, void *stream) {
+    gt_status s = gt_calibrate_dtype(GT_BF16, ws, ws_bytes, nullptr, stream);
+    if (s != GT_OK) return s;
+    return gt_calibrate_dtype(GT_F32, ws, ws_bytes, fitted, stream);
 }

@@ -23,15 +23,26 @@ namespace {
 
 typedef uint16_t bf16_t;
 
-// Coefficients in seconds.  Defaults are the values gt_calibrate fitted on an MI355X (fp32);
-// gt_calibrate replaces them with values fitted on the device at hand.
-gt_cost_coeffs g_cost = {1.2e-14, 2.0e-12, 5.1e-13, 8.4e-13, 1.1e-14, 2.1e-12, 4.6e-13, 1.26e-12};
+// Coefficients in seconds, one set per data type (index: gt_dtype).  Defaults are the values
+// gt_calibrate fitted on an MI355X; gt_calibrate replaces them with values fitted on the device
+// at hand.
+gt_cost_coeffs g_cost[2] = {{1.1e-14, 1.3e-12, 4.9e-13, 9.2e-13, 1.07e-14, 1.25e-12, 4.5e-13, 1.3e-12},
+                            {7.4e-15, 1.28e-12, 2.3e-13, 7.2e-13, 3.6e-15, 9.2e-13, 1.9e-13, 1.14e-12}};
+const gt_cost_coeffs &cost_of(gt_dtype t) { return g_cost[t == GT_BF16 ? 1 : 0]; }
+
+// An aggregation launch cannot finish faster than the chain of dependent loads of one work item
+// (descriptor, neighbour ids, rows, a chunk of them for a hub row) however narrow the rows are:
+// below this floor a narrower aggregation is not a faster one, so the model must not prefer it.
+// (4,096-vertex graph, 64 -> 16: both orders measure the same within launch jitter; without the
+// floor the model picked the order that measured 9 % slower.)
+constexpr double GT_AGGR_FLOOR_S = 4e-6;
 
 double t_comb(const gt_cost_coeffs &c, bool bwd, double rows, double in, double out) {
     return bwd ? rows * (c.alpha_bwd * in * out + c.beta_bwd * in) : rows * (c.alpha_fwd * in * out + c.beta_fwd * out);
 }
 double t_aggr(const gt_cost_coeffs &c, bool bwd, double E, double n_out, double F) {
-    return bwd ? F * (c.gamma_bwd * E + c.delta_bwd * n_out) : F * (c.gamma_fwd * E + c.delta_fwd * n_out);
+    const double t = bwd ? F * (c.gamma_bwd * E + c.delta_bwd * n_out) : F * (c.gamma_fwd * E + c.delta_fwd * n_out);
+    return t > GT_AGGR_FLOOR_S ? t : GT_AGGR_FLOOR_S;
 }
 
 __device__ inline float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
@@ -261,7 +272,7 @@ gt_status check_desc(const char *fn, const gt_graph *g, const gt_layer_desc *d) 
 void *at(void *base, size_t off) { return static_cast<char *>(base) + off; }
 
 void decide(const gt_graph *g, const gt_layer_desc *d, gt_order *fwd, gt_order *bwd) {
-    const gt_cost_coeffs &c = g_cost;
+    const gt_cost_coeffs &c = cost_of(d->dtype);
     const double ns = (double)g->n_src, nd = (double)g->n_dst, E = (double)g->n_edges;
     const double fi = (double)d->in_dim, fo = (double)d->out_dim;
     // forward
@@ -334,19 +345,41 @@ gt_status mask_colsum(const void *dY, int64_t lddy, const void *Y, int64_t ldy, 
 
 }  // namespace
 
+static gt_status check_coeffs(const char *fn, const gt_cost_coeffs *c) {
+    if (!c) return gt_fail(GT_ERR_INVALID_ARG, "%s: null", fn);
+    const double v[8] = {c->alpha_fwd, c->beta_fwd, c->gamma_fwd, c->delta_fwd,
+                         c->alpha_bwd, c->beta_bwd, c->gamma_bwd, c->delta_bwd};
+    for (double x : v)
+        if (!(x >= 0.0) || !isfinite(x)) return gt_fail(GT_ERR_INVALID_ARG, "%s: coefficients must be finite and >= 0", fn);
+    return GT_OK;
+}
+
 extern "C" gt_status gt_cost_get(gt_cost_coeffs *c) {
     if (!c) return gt_fail(GT_ERR_INVALID_ARG, "gt_cost_get: null");
-    *c = g_cost;
+    *c = g_cost[0];
     return GT_OK;
 }
 
 extern "C" gt_status gt_cost_set(const gt_cost_coeffs *c) {
-    if (!c) return gt_fail(GT_ERR_INVALID_ARG, "gt_cost_set: null");
-    const double v[8] = {c->alpha_fwd, c->beta_fwd, c->gamma_fwd, c->delta_fwd,
-                         c->alpha_bwd, c->beta_bwd, c->gamma_bwd, c->delta_bwd};
-    for (double x : v)
-        if (!(x >= 0.0) || !isfinite(x)) return gt_fail(GT_ERR_INVALID_ARG, "gt_cost_set: coefficients must be finite and >= 0");
-    g_cost = *c;
+    const gt_status s = check_coeffs("gt_cost_set", c);
+    if (s != GT_OK) return s;
+    g_cost[0] = *c;
+    g_cost[1] = *c;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_cost_get_dtype(gt_dtype dtype, gt_cost_coeffs *c) {
+    if (!c) return gt_fail(GT_ERR_INVALID_ARG, "gt_cost_get_dtype: null");
+    if (dtype != GT_F32 && dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "gt_cost_get_dtype: unknown dtype");
+    *c = g_cost[dtype == GT_BF16 ? 1 : 0];
+    return GT_OK;
+}
+
+extern "C" gt_status gt_cost_set_dtype(gt_dtype dtype, const gt_cost_coeffs *c) {
+    if (dtype != GT_F32 && dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "gt_cost_set_dtype: unknown dtype");
+    const gt_status s = check_coeffs("gt_cost_set_dtype", c);
+    if (s != GT_OK) return s;
+    g_cost[dtype == GT_BF16 ? 1 : 0] = *c;
     return GT_OK;
 }
 
@@ -467,7 +500,7 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
         if (f2 == fwd_used) {
             order = b2;
         } else {
-            const gt_cost_coeffs &c = g_cost;
+            const gt_cost_coeffs &c = cost_of(d->dtype);
             const double ns = (double)g->n_src, nd = (double)g->n_dst, E = (double)g->n_edges;
             const double dx_agg = t_comb(c, true, nd, fi, fo) + t_aggr(c, true, E, ns, fi) +
                                   (fwd_used == GT_COMB_FIRST ? t_aggr(c, true, E, ns, fo) : 0.0);

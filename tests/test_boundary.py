@@ -84,18 +84,27 @@ def test_cost_benefit_formulas_with_the_papers_constants():
 
 
 def test_cost_set_get_roundtrip_and_validation():
-    old = B.gt_cost_get()
+    old = [B.gt_cost_get_dtype(d) for d in ("f32", "bf16")]
     try:
         c = B.gt_cost_coeffs(1, 2, 3, 4, 5, 6, 7, 8)
-        B.gt_cost_set(c)
+        B.gt_cost_set(c)                                   # installs the set for every data type
+        for g in (B.gt_cost_get(), B.gt_cost_get_dtype("f32"), B.gt_cost_get_dtype("bf16")):
+            assert [getattr(g, f[0]) for f in g._fields_] == [1, 2, 3, 4, 5, 6, 7, 8]
+        B.gt_cost_set_dtype("bf16", B.gt_cost_coeffs(8, 7, 6, 5, 4, 3, 2, 1))   # one data type only
+        g = B.gt_cost_get_dtype("bf16")
+        assert [getattr(g, f[0]) for f in g._fields_] == [8, 7, 6, 5, 4, 3, 2, 1]
         g = B.gt_cost_get()
         assert [getattr(g, f[0]) for f in g._fields_] == [1, 2, 3, 4, 5, 6, 7, 8]
         bad = B.gt_cost_coeffs(-1, 2, 3, 4, 5, 6, 7, 8)
         assert B.lib.gt_cost_set(byref(bad)) == 1
+        assert B.lib.gt_cost_set_dtype(1, byref(bad)) == 1
         bad = B.gt_cost_coeffs(float("nan"), 2, 3, 4, 5, 6, 7, 8)
         assert B.lib.gt_cost_set(byref(bad)) == 1
+        assert B.lib.gt_cost_set_dtype(7, byref(c)) == 1   # unknown data type
+        assert B.lib.gt_cost_get_dtype(7, byref(c)) == 1
     finally:
-        B.gt_cost_set(old)
+        B.gt_cost_set_dtype("f32", old[0])
+        B.gt_cost_set_dtype("bf16", old[1])
 
 
 def test_product_does_not_import_the_oracle():

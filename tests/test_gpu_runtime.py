@@ -30,24 +30,32 @@ def _stack(cfg, dev):
 def test_calibrate_fits_positive_coefficients_and_keeps_decisions():
     from paper_2305_17469_amd import binding as B
     announce("gt_calibrate")
-    old = B.gt_cost_get()
+    old = [B.gt_cost_get_dtype(d) for d in ("f32", "bf16")]
     try:
-        c = B.gt_calibrate()
-        vals = {f[0]: getattr(c, f[0]) for f in c._fields_}
-        print(vals)
-        assert all(np.isfinite(v) and v >= 0 for v in vals.values())
-        assert vals["gamma_fwd"] > 0 and vals["gamma_bwd"] > 0 and vals["alpha_fwd"] > 0 and vals["alpha_bwd"] > 0
-        # a gather of one fp32 feature takes between 0.05 and 50 ps on this class of device
-        assert 5e-14 < vals["gamma_fwd"] < 5e-11 and 5e-14 < vals["gamma_bwd"] < 5e-11
-        got = B.gt_cost_get()
-        assert got.gamma_fwd == c.gamma_fwd and got.alpha_bwd == c.alpha_bwd       # installed
+        c = B.gt_calibrate()                       # fits bf16, then fp32; returns the fp32 set
+        fitted = {"f32": B.gt_cost_get_dtype("f32"), "bf16": B.gt_cost_get_dtype("bf16")}
+        assert fitted["f32"].gamma_fwd == c.gamma_fwd and fitted["f32"].alpha_bwd == c.alpha_bwd   # installed
+        for dt, cc in fitted.items():
+            vals = {f[0]: getattr(cc, f[0]) for f in cc._fields_}
+            print(dt, vals)
+            assert all(np.isfinite(v) and v >= 0 for v in vals.values())
+            assert vals["gamma_fwd"] > 0 and vals["gamma_bwd"] > 0 and vals["alpha_fwd"] > 0 and vals["alpha_bwd"] > 0
+            # a gather of one feature takes between 0.05 and 50 ps on this class of device
+            assert 5e-14 < vals["gamma_fwd"] < 5e-11 and 5e-14 < vals["gamma_bwd"] < 5e-11
+        # bf16 rows are half as long: gathering one feature must not cost more than in fp32
+        assert fitted["bf16"].gamma_fwd <= 1.1 * fitted["f32"].gamma_fwd
+        one = B.gt_calibrate_dtype("bf16")         # one data type alone leaves the other set untouched
+        assert B.gt_cost_get_dtype("bf16").gamma_fwd == one.gamma_fwd
+        assert B.gt_cost_get_dtype("f32").gamma_fwd == c.gamma_fwd
         cfg = configs.reddit_like(11)
         blk = cfg["blocks"][0]
         g = B.Graph(up_i32(blk["rowptr"]), up_i32(blk["colidx"]), blk["n_src"])
-        assert B.gt_layer_decide(g, B.make_desc("symnorm", "f32", True, 602, 128, need_dx=False))[0] == "comb_first"
-        assert B.gt_layer_decide(g, B.make_desc("symnorm", "f32", True, 16, 1024))[0] == "agg_first"
+        for dt in ("f32", "bf16"):
+            assert B.gt_layer_decide(g, B.make_desc("symnorm", dt, True, 602, 128, need_dx=False))[0] == "comb_first"
+            assert B.gt_layer_decide(g, B.make_desc("symnorm", dt, True, 16, 1024))[0] == "agg_first"
     finally:
-        B.gt_cost_set(old)
+        B.gt_cost_set_dtype("f32", old[0])
+        B.gt_cost_set_dtype("bf16", old[1])
 
 
 def test_kernel_trace_records_every_gather_and_combine_launch():
