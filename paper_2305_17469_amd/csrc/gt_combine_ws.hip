@@ -296,6 +296,221 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// fp32 data on the bf16 matrix cores (three-way exact splitting, six products; see
+// gt_combine_x3.hip for the arithmetic).  v_mfma_f32_32x32x2f32 makes the fp32 form of the kernel
+// above matrix bound (128 x 64 weights: 8,192 MFMA cycles per 32-row block against 3,072 here), so
+// where the three weight planes fit in LDS the fp32 products run here instead.  The weights are
+// split once, while they are put into LDS ([plane][n][k] bf16, k contiguous); a lane reads its
+// eight consecutive k of A from the stage as fp32 and splits them in registers.
+// ---------------------------------------------------------------------------------------------
+__device__ inline void ws_split3(float x, uint32_t &hi, uint32_t &mid, uint32_t &lo) {
+    const uint32_t h = __float_as_uint(x) & 0xffff0000u;
+    const float r1 = x - __uint_as_float(h);
+    const uint32_t m = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(m);
+    hi = h; mid = m; lo = __float_as_uint(r2);
+}
+// upper halves of two words as one word: (b & 0xffff0000) | (a >> 16)
+__device__ inline uint32_t ws_pack_hi16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
+template <int NB, int NS>
+constexpr size_t ws_x3_lds_bytes() {
+    return (size_t)3 * NB * 32 * (NS * 32 + 8) * 2 + 4 * GEMM_STAGE_FLOATS(1) * 4 + (size_t)NB * 32 * 4;
+}
+template <int NB, int NS>
+constexpr int ws_x3_per_cu() { return ws_x3_lds_bytes<NB, NS>() <= 80 * 1024 ? 2 : 1; }
+
+template <int NB, int NS, bool EX, bool FAST>
+__global__ void __launch_bounds__(256, (ws_x3_per_cu<NB, NS>())) k_gemm_ws_x3(const GemmArgs g, const int transB) {
+    constexpr int SK = 32;                      // k per slice (128 bytes of fp32)
+    constexpr int KP = NS * SK;                 // K capacity of this instance
+    constexpr int WSTR = KP + 8;                // plane row stride in bf16 elements (16 bytes past a multiple of 64)
+    constexpr int ASTR = SK + 4;                // stage row stride in floats (144 bytes)
+    constexpr int BN = NB * 32;
+    constexpr int PLANE = BN * WSTR;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *Wp = reinterpret_cast<bf16_t *>(smem);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    float *As = reinterpret_cast<float *>(smem + (size_t)3 * PLANE * 2 + (size_t)wave * GEMM_STAGE_FLOATS(1) * 4);
+    float *bias_lds = reinterpret_cast<float *>(smem + (size_t)3 * PLANE * 2 + 4 * (size_t)GEMM_STAGE_FLOATS(1) * 4);
+    const float *A = static_cast<const float *>(g.A);
+    const float *B = static_cast<const float *>(g.B);
+    const int64_t n0 = (int64_t)blockIdx.y * BN;
+    for (int n = threadIdx.x; n < BN; n += 256) bias_lds[n] = (g.bias && n0 + n < g.N) ? g.bias[n0 + n] : 0.0f;
+    const int nslices = (int)((g.K + SK - 1) / SK);
+
+    // the weight slice, once, as three planes: Wp[plane][n][k] = piece of op(B)(k, n0 + n), zero
+    // outside (K, N).  A thread takes quads of four elements that are consecutive in memory, eight
+    // quads in flight.
+    {
+        constexpr int TOTAL = BN * KP / 4;
+        for (int base = threadIdx.x; base < TOTAL; base += 256 * 8) {
+            float4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256;
+                int n, k;
+                if (transB) { n = idx / (KP / 4); k = (idx % (KP / 4)) * 4; }     // B[n][k..k+3]
+                else { k = idx / (BN / 4); n = (idx % (BN / 4)) * 4; }            // B[k][n..n+3]
+                const bool ok = idx < TOTAL && n0 + n < g.N && k < g.K;
+                const int64_t off = transB ? (n0 + n) * g.ldb + k : (int64_t)k * g.ldb + n0 + n;
+                const int64_t lim = transB ? g.K - k : g.N - (n0 + n);            // elements of the quad inside
+                if (g.vecB) {
+                    v[u] = *reinterpret_cast<const float4 *>(B + (ok ? off : 0));
+                } else {
+                    v[u].x = B[ok ? off : 0];
+                    v[u].y = B[ok && lim > 1 ? off + 1 : 0];
+                    v[u].z = B[ok && lim > 2 ? off + 2 : 0];
+                    v[u].w = B[ok && lim > 3 ? off + 3 : 0];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + u * 256;
+                if (idx >= TOTAL) continue;
+                int n, k;
+                if (transB) { n = idx / (KP / 4); k = (idx % (KP / 4)) * 4; }
+                else { k = idx / (BN / 4); n = (idx % (BN / 4)) * 4; }
+                const bool ok = n0 + n < g.N && k < g.K;
+                const int64_t lim = transB ? g.K - k : g.N - (n0 + n);
+                const float x[4] = {ok ? v[u].x : 0.0f, ok && lim > 1 ? v[u].y : 0.0f, ok && lim > 2 ? v[u].z : 0.0f,
+                                    ok && lim > 3 ? v[u].w : 0.0f};
+                uint32_t hi[4], mi[4], lo[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) ws_split3(x[q], hi[q], mi[q], lo[q]);
+                if (transB) {    // four consecutive k of one row: one 8-byte run per plane
+                    bf16_t *d = Wp + n * WSTR + k;
+                    *reinterpret_cast<uint2 *>(d) = make_uint2(ws_pack_hi16(hi[0], hi[1]), ws_pack_hi16(hi[2], hi[3]));
+                    *reinterpret_cast<uint2 *>(d + PLANE) = make_uint2(ws_pack_hi16(mi[0], mi[1]), ws_pack_hi16(mi[2], mi[3]));
+                    *reinterpret_cast<uint2 *>(d + 2 * PLANE) = make_uint2(ws_pack_hi16(lo[0], lo[1]), ws_pack_hi16(lo[2], lo[3]));
+                } else {         // four consecutive n at one k: one element in each of four rows
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        bf16_t *d = Wp + (n + q) * WSTR + k;
+                        d[0] = (bf16_t)(hi[q] >> 16);
+                        d[PLANE] = (bf16_t)(mi[q] >> 16);
+                        d[2 * PLANE] = (bf16_t)(lo[q] >> 16);
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+
+    const bool out_vec = (g.ldc % 4 == 0) && (((uintptr_t)g.C & 15) == 0);
+    const int64_t nrb = (g.M + 31) / 32;
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    int64_t rb = (int64_t)blockIdx.x * 4 + wave;
+    if (rb >= nrb) return;   // no workgroup barrier below this point
+    uint4 R[NS][4];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        if (FAST || s < nslices) ws_load_slice<float>(R[s], A, g.lda, rb, s, g.M, g.K, lane);
+    for (; rb < nrb; rb += stride) {
+        const bool more = rb + stride < nrb;
+        const int64_t rb_next = more ? rb + stride : rb;
+        floatx16 acc[NB];
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            if (EX) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 c = *reinterpret_cast<const float4 *>(bias_lds + b * 32 + 8 * q + 4 * h);
+                    acc[b][4 * q] = c.x; acc[b][4 * q + 1] = c.y; acc[b][4 * q + 2] = c.z; acc[b][4 * q + 3] = c.w;
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (!FAST && s >= nslices) continue;   // uniform
+            __asm__ volatile("" ::: "memory");     // stage writes stay below the previous slice's fragment reads
+            const int64_t left = g.K - ((int64_t)s * SK + (lane & 7) * 4);
+            const int nv = left >= 4 ? 4 : (left > 0 ? (int)left : 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint4 v = R[s][j];
+                if (FAST) v = ws_mask<float>(v, nv);
+                else if (nv < 4) v = ws_mask<float>(v, nv);
+                *reinterpret_cast<uint4 *>(As + ((lane >> 3) + 8 * j) * ASTR + (lane & 7) * 4) = v;
+            }
+            if (FAST) ws_load_slice<float>(R[s], A, g.lda, rb_next, s, g.M, g.K, lane);
+            else if (more) ws_load_slice<float>(R[s], A, g.lda, rb + stride, s, g.M, g.K, lane);
+#pragma unroll
+            for (int t = 0; t < SK / 16; ++t) {    // MFMA steps of 16 k: lane half h supplies k = 16 t + 8 h .. + 7
+                if (!FAST && (int64_t)s * SK + t * 16 >= g.K) continue;   // uniform: nothing left in this slice
+                const float *ap = As + l32 * ASTR + t * 16 + h * 8;
+                const float4 a0 = *reinterpret_cast<const float4 *>(ap), a1 = *reinterpret_cast<const float4 *>(ap + 4);
+                const float x[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                uint32_t hi[8], mi[8], lo[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) ws_split3(x[q], hi[q], mi[q], lo[q]);
+                uint4 ph, pm, pl;
+                ph = make_uint4(ws_pack_hi16(hi[0], hi[1]), ws_pack_hi16(hi[2], hi[3]), ws_pack_hi16(hi[4], hi[5]), ws_pack_hi16(hi[6], hi[7]));
+                pm = make_uint4(ws_pack_hi16(mi[0], mi[1]), ws_pack_hi16(mi[2], mi[3]), ws_pack_hi16(mi[4], mi[5]), ws_pack_hi16(mi[6], mi[7]));
+                pl = make_uint4(ws_pack_hi16(lo[0], lo[1]), ws_pack_hi16(lo[2], lo[3]), ws_pack_hi16(lo[4], lo[5]), ws_pack_hi16(lo[6], lo[7]));
+                bf16x8 ah, am, al;
+                __builtin_memcpy(&ah, &ph, 16);
+                __builtin_memcpy(&am, &pm, 16);
+                __builtin_memcpy(&al, &pl, 16);
+                const bf16_t *wrow = Wp + l32 * WSTR + s * SK + t * 16 + h * 8;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const bf16x8 wh = *reinterpret_cast<const bf16x8 *>(wrow + b * 32 * WSTR);
+                    const bf16x8 wm = *reinterpret_cast<const bf16x8 *>(wrow + b * 32 * WSTR + PLANE);
+                    const bf16x8 wl = *reinterpret_cast<const bf16x8 *>(wrow + b * 32 * WSTR + 2 * PLANE);
+                    floatx16 cc = acc[b];
+                    // smallest terms first: lo*hi, hi*lo, mid*mid, then mid*hi, hi*mid, then hi*hi
+                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wl, ah, cc, 0, 0, 0);
+                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh, al, cc, 0, 0, 0);
+                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wm, am, cc, 0, 0, 0);
+                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wm, ah, cc, 0, 0, 0);
+                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh, am, cc, 0, 0, 0);
+                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh, ah, cc, 0, 0, 0);
+                    acc[b] = cc;
+                }
+            }
+        }
+        const int64_t row = rb * 32 + l32;
+        if (FAST) ws_epilogue<false, EX, true, NB>(g, acc, row < g.M ? row : g.M - 1, n0, h, true);
+        else if (row < g.M) ws_epilogue<false, EX, false, NB>(g, acc, row, n0, h, out_vec);
+    }
+}
+
+template <int NB, int NS, bool EX, bool FAST>
+gt_status ws_x3_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
+    constexpr size_t lds = ws_x3_lds_bytes<NB, NS>();
+    if (lds > 64 * 1024) {
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws_x3<NB, NS, EX, FAST>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    }
+    const int64_t nrb = (g.M + 31) / 32;
+    const int per_cu = ws_x3_per_cu<NB, NS>();
+    int64_t gx = (nrb + 3) / 4;
+    if (gx > 256 * per_cu) gx = 256 * per_cu;
+    dim3 grid((unsigned)gx, (unsigned)((g.N + NB * 32 - 1) / (NB * 32)), 1);
+    k_gemm_ws_x3<NB, NS, EX, FAST><<<grid, 256, lds, st>>>(g, transB);
+    GT_LAUNCH_CHECK("k_gemm_ws_x3");
+    return GT_OK;
+}
+
+template <int NB, int NS>
+gt_status ws_x3_launch(const GemmArgs &g, int transB, hipStream_t st) {
+    const bool extras = g.bias || g.relu;
+    if constexpr (NB >= 4) {
+        const bool fast = g.N % (NB * 32) == 0 && g.ldc % 4 == 0 && (((uintptr_t)g.C & 15) == 0);
+        if (fast)
+            return extras ? ws_x3_launch_ex<NB, NS, true, true>(g, transB, st)
+                          : ws_x3_launch_ex<NB, NS, false, true>(g, transB, st);
+    }
+    return extras ? ws_x3_launch_ex<NB, NS, true, false>(g, transB, st)
+                  : ws_x3_launch_ex<NB, NS, false, false>(g, transB, st);
+}
+
 template <typename T, int NB, int NS, bool EX, bool FAST>
 gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     constexpr size_t lds = ws_lds_bytes<T, NB, NS>();
@@ -332,9 +547,18 @@ gt_status ws_launch(const GemmArgs &g, int transB, hipStream_t st) {
 template <typename T, int NB>
 gt_status ws_pick_ns(const GemmArgs &g, int transB, hipStream_t st) {
     const int64_t slices = (g.K + WsGeom<T>::SK - 1) / WsGeom<T>::SK;
-    if (slices <= 1) return ws_launch<T, NB, 1>(g, transB, st);
-    if (slices <= 2) return ws_launch<T, NB, 2>(g, transB, st);
-    return ws_launch<T, NB, 4>(g, transB, st);
+    if constexpr (sizeof(T) == 4 && NB <= 4) {
+        // fp32 on the bf16 matrix cores for outputs of up to 128 columns (measured on MI355X, 2^18 rows:
+        // 128 -> 41 0.074 -> 0.052 ms, 41 -> 128 0.067 -> 0.053 ms); wider outputs are bound by their
+        // stores and ran slower this way (2^20 rows, 16 -> 1024: 1.15 -> 1.30 ms), they keep the fp32 MFMA
+        if (slices <= 1) return ws_x3_launch<NB, 1>(g, transB, st);
+        if (slices <= 2) return ws_x3_launch<NB, 2>(g, transB, st);
+        return ws_x3_launch<NB, 4>(g, transB, st);
+    } else {
+        if (slices <= 1) return ws_launch<T, NB, 1>(g, transB, st);
+        if (slices <= 2) return ws_launch<T, NB, 2>(g, transB, st);
+        return ws_launch<T, NB, 4>(g, transB, st);
+    }
 }
 
 template <typename T>

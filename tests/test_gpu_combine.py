@@ -77,12 +77,16 @@ def test_combine_all_transposes(shape, dtype):
                     _check(down(C32), ref_lin, absr, dtype, False, ("f32out", tA, tB))
 
 
-def test_split_bf16_path_keeps_fp32_accuracy_on_hard_inputs():
+@pytest.mark.parametrize("shape", [(1500, 192, 1024), (9000, 96, 128), (8500, 100, 61)],
+                         ids=["tiled", "weight_stationary", "weight_stationary_ragged"])
+def test_split_bf16_path_keeps_fp32_accuracy_on_hard_inputs(shape):
     """Inputs with a wide dynamic range and no cancellation: the relative error of every output
-    must stay at fp32 level (the three dropped cross products are below 2^-24 of each term)."""
+    must stay at fp32 level (the three dropped cross products are below 2^-24 of each term).
+    Both kernels that run fp32 data on the bf16 matrix cores: the tiled one and the tall,
+    weight-stationary one."""
     from paper_2305_17469_amd import binding as B
     rng = np.random.default_rng(9)
-    M, N, K = 1500, 192, 1024
+    M, N, K = shape
     A = (np.abs(tensors.normal((M, K), seed=1)) * np.exp2(rng.integers(-20, 20, (M, 1)))).astype(np.float32)
     Bm = (np.abs(tensors.normal((K, N), seed=2)) * np.exp2(rng.integers(-20, 20, (1, N)))).astype(np.float32)
     announce("combine split-bf16 accuracy", (M, N, K))
