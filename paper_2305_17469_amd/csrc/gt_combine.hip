@@ -379,13 +379,15 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     g.Cin = Cin; g.ldcin = ldcin;
     if (p.splits > 1) { g.C = ws; g.ldc = N; } else { g.C = C; g.ldc = ldc; }
     const int tr = gt_trace_open(GT_TRACE_COMBINE, N, M, M * N * K, st);
-    // fp32 shapes bound by matrix throughput go through the split-bf16 kernel (3/8 of the fp32
-    // MFMA cost at fp32-level accuracy); skinny, memory-bound shapes keep the plain fp32 MFMA.
-    // A small weight gradient (at most 256 x 64 outputs over a long reduction) also goes there:
-    // the plain kernel's 256 x 64 tile is mostly padding for it and the slow fp32 MFMA makes that
+    // fp32 products with enough work to be bound by matrix throughput go through the split-bf16 kernel
+    // (3/8 of the fp32 MFMA cost at fp32-level accuracy): 128 x 128 tiles in general, 256 x 64 tiles for
+    // outputs of 33..64 columns (a sampled block's 91 K x 602 -> 64 product: 111 -> 60 us; the plain kernel's
+    // 357 tiles of slow fp32 MFMA took two rounds over the SIMDs).  Narrower outputs keep the plain fp32
+    // MFMA (256 x 32 tiles), except a small weight gradient (at most 256 x 64 outputs over a long
+    // reduction), where the plain kernel's tile is mostly padding and the slow fp32 MFMA makes that
     // padding the bottleneck (config 2, 128 x 41: 0.093 -> 0.06 ms).
     const bool big = (double)M * (double)N * (double)K >= 268435456.0;
-    const bool x3 = dtype == GT_F32 && K >= 64 && big && (N > 64 || (transA && N >= 32 && M <= 256));
+    const bool x3 = dtype == GT_F32 && K >= 64 && big && (N > 32 || (transA && N >= 32 && M <= 256));
     // tall products with a small weight matrix are bound by streaming A and C once: the
     // weight-stationary kernel does exactly that
     const bool ws_path = p.splits == 1 && c_dtype == dtype && !Cin && !rowscale &&

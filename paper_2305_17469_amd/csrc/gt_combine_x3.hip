@@ -25,9 +25,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int KT = GEMM_KT;          // 32
-constexpr int BM = 128, BN = 128;
 constexpr int STR = KT + 8;          // LDS row stride in bf16 elements (80 bytes: 16-byte aligned, bank friendly)
-constexpr int PLANE = BM * STR;      // elements per plane
 
 // Three truncated bf16 pieces of x: x == hi + mid + lo exactly (barring underflow).  The pieces are
 // returned as fp32 bit patterns whose upper halves are the bf16 values (the lower halves of `hi`
@@ -44,6 +42,7 @@ __device__ inline void split3(float x, uint32_t &hi, uint32_t &mid, uint32_t &lo
 __device__ inline uint32_t pack_hi16(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
 // four consecutive-k values -> three 8-byte k-runs (one per plane) at lds[plane][row][k]
+template <int PLANE>
 __device__ inline void store_run4(gemm_bf16_t *lds, int row, int k, float x0, float x1, float x2, float x3) {
     uint32_t h[4], m[4], l[4];
     split3(x0, h[0], m[0], l[0]);
@@ -82,14 +81,17 @@ __device__ inline float4 mask4(float4 v, int nv) {
     return v;
 }
 
-// 128 rows x 32 k of an operand whose k direction is contiguous in memory: element (i, k) at
-// p[(i0 + i) * ld + k0 + k].  Four float4 per thread, lanes run along k first.
+// ROWS rows x 32 k of an operand whose k direction is contiguous in memory: element (i, k) at
+// p[(i0 + i) * ld + k0 + k].  ROWS / 32 float4 per thread, lanes run along k first.
+template <int ROWS>
 struct LoadKC {
-    float4 r[4];
-    int nv[4];
+    static constexpr int NV = ROWS / 32;
+    static constexpr int PLANE = ROWS * STR;
+    float4 r[NV];
+    int nv[NV];
     __device__ inline void load(const float *p, int64_t ld, int64_t i0, int64_t k0, int64_t ilim, int64_t klim, int vec) {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
+        for (int it = 0; it < NV; ++it) {
             const int u = threadIdx.x + 256 * it;
             const int i = u >> 3, kq = u & 7;
             const int64_t gi = i0 + i, gk = k0 + kq * 4;
@@ -98,46 +100,70 @@ struct LoadKC {
     }
     __device__ inline void store(gemm_bf16_t *lds) const {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
+        for (int it = 0; it < NV; ++it) {
             const int u = threadIdx.x + 256 * it;
             const float4 v = mask4(r[it], nv[it]);
-            store_run4(lds, u >> 3, (u & 7) * 4, v.x, v.y, v.z, v.w);
+            store_run4<PLANE>(lds, u >> 3, (u & 7) * 4, v.x, v.y, v.z, v.w);
         }
     }
 };
 
-// 32 k x 128 rows of an operand whose row direction is contiguous in memory: element (i, k) at
-// p[(k0 + k) * ld + i0 + i].  One 4(k) x 4(i) patch per thread, transposed in registers.
+// 32 k x ROWS rows of an operand whose row direction is contiguous in memory: element (i, k) at
+// p[(k0 + k) * ld + i0 + i].  4(k) x 4(i) patches, transposed in registers: one patch per thread
+// covers 128 rows (ROWS = 256: two patches; ROWS = 64: the upper half of the threads has none).
+template <int ROWS>
 struct LoadKM {
-    float4 r[4];   // r[dk] = rows i..i+3 at k + dk
-    int nv[4];
+    static constexpr int NPATCH = ROWS > 128 ? ROWS / 128 : 1;
+    static constexpr int PLANE = ROWS * STR;
+    float4 r[NPATCH][4];   // r[q][dk] = rows i..i+3 at k + dk
+    int nv[NPATCH][4];
     __device__ inline void load(const float *p, int64_t ld, int64_t i0, int64_t k0, int64_t ilim, int64_t klim, int vec) {
-        const int kq = threadIdx.x & 7, iq = threadIdx.x >> 3;
+        const int kq = threadIdx.x & 7;
 #pragma unroll
-        for (int dk = 0; dk < 4; ++dk) {
-            const int64_t gk = k0 + kq * 4 + dk, gi = i0 + iq * 4;
-            r[dk] = load4(p, gk * ld + gi, gi, ilim, gk < klim, vec, nv[dk]);
+        for (int q = 0; q < NPATCH; ++q) {
+            const int iq = (threadIdx.x >> 3) + 32 * q;
+            const bool mine = iq * 4 < ROWS;
+#pragma unroll
+            for (int dk = 0; dk < 4; ++dk) {
+                const int64_t gk = k0 + kq * 4 + dk, gi = i0 + iq * 4;
+                r[q][dk] = load4(p, gk * ld + gi, gi, ilim, mine && gk < klim, vec, nv[q][dk]);
+            }
         }
     }
     __device__ inline void store(gemm_bf16_t *lds) const {
-        const int kq = threadIdx.x & 7, iq = threadIdx.x >> 3;
-        const float4 a = mask4(r[0], nv[0]), b = mask4(r[1], nv[1]), c = mask4(r[2], nv[2]), d = mask4(r[3], nv[3]);
-        store_run4(lds, iq * 4 + 0, kq * 4, a.x, b.x, c.x, d.x);
-        store_run4(lds, iq * 4 + 1, kq * 4, a.y, b.y, c.y, d.y);
-        store_run4(lds, iq * 4 + 2, kq * 4, a.z, b.z, c.z, d.z);
-        store_run4(lds, iq * 4 + 3, kq * 4, a.w, b.w, c.w, d.w);
+        const int kq = threadIdx.x & 7;
+#pragma unroll
+        for (int q = 0; q < NPATCH; ++q) {
+            const int iq = (threadIdx.x >> 3) + 32 * q;
+            if (iq * 4 >= ROWS) continue;
+            const float4 a = mask4(r[q][0], nv[q][0]), b = mask4(r[q][1], nv[q][1]), c = mask4(r[q][2], nv[q][2]),
+                         d = mask4(r[q][3], nv[q][3]);
+            store_run4<PLANE>(lds, iq * 4 + 0, kq * 4, a.x, b.x, c.x, d.x);
+            store_run4<PLANE>(lds, iq * 4 + 1, kq * 4, a.y, b.y, c.y, d.y);
+            store_run4<PLANE>(lds, iq * 4 + 2, kq * 4, a.z, b.z, c.z, d.z);
+            store_run4<PLANE>(lds, iq * 4 + 3, kq * 4, a.w, b.w, c.w, d.w);
+        }
     }
 };
 
-template <bool TA, bool TB, bool VA, bool VB>
+// Workgroup tile: WGM x WGN wavefronts of 64 x 64 accumulators each: 128 x 128 (2 x 2) in general,
+// 256 x 64 (4 x 1) for outputs of at most 64 columns, where half of a 128-wide tile would be padding.
+template <int WGM, int WGN>
+constexpr size_t x3_lds_bytes() { return (size_t)3 * (WGM + WGN) * 64 * STR * 2; }
+
+template <bool TA, bool TB, bool VA, bool VB, int WGM, int WGN>
 __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
+    static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
+    constexpr int BM = WGM * 64, BN = WGN * 64;
+    constexpr int PLANE_A = BM * STR, PLANE_B = BN * STR;
     // one LDS buffer: operand planes during the k-loop, the per-wavefront output stages afterwards
-    __shared__ __attribute__((aligned(16))) gemm_bf16_t smem[6 * PLANE];
-    static_assert(6 * PLANE * 2 >= 4 * GEMM_STAGE_FLOATS(2) * 4, "output stages must fit");
-    gemm_bf16_t *As = smem, *Bs = smem + 3 * PLANE;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    gemm_bf16_t *smem = reinterpret_cast<gemm_bf16_t *>(smem_raw);
+    static_assert(x3_lds_bytes<WGM, WGN>() >= 4 * GEMM_STAGE_FLOATS(2) * 4, "output stages must fit");
+    gemm_bf16_t *As = smem, *Bs = smem + 3 * PLANE_A;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, h = lane >> 5;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     int tile_m, tile_n;
     if (!gemm_tile_of_block(g, tile_m, tile_n)) return;   // whole workgroup leaves before any barrier
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
@@ -155,8 +181,8 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
 
     // op(A)(i,k) = TA ? A[k*lda + i] : A[i*lda + k];  op(B)(k,j) = TB ? B[j*ldb + k] : B[k*ldb + j]
-    typename std::conditional<TA, LoadKM, LoadKC>::type la;
-    typename std::conditional<TB, LoadKC, LoadKM>::type lb;
+    typename std::conditional<TA, LoadKM<BM>, LoadKC<BM>>::type la;
+    typename std::conditional<TB, LoadKC<BN>, LoadKM<BN>>::type lb;
     if (kbeg < kend) {
         la.load(A, g.lda, m0, kbeg, g.M, kend, VA);
         lb.load(B, g.ldb, n0, kbeg, g.N, kend, VB);
@@ -181,14 +207,14 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
                 const int i = (wm * 2 + a) * 32 + l32;
 #pragma unroll
                 for (int p = 0; p < 3; ++p)
-                    af[a][p] = *reinterpret_cast<const bf16x8 *>(&As[p * PLANE + i * STR + kk]);
+                    af[a][p] = *reinterpret_cast<const bf16x8 *>(&As[p * PLANE_A + i * STR + kk]);
             }
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 const int j = (wn * 2 + b) * 32 + l32;
 #pragma unroll
                 for (int p = 0; p < 3; ++p)
-                    bf[b][p] = *reinterpret_cast<const bf16x8 *>(&Bs[p * PLANE + j * STR + kk]);
+                    bf[b][p] = *reinterpret_cast<const bf16x8 *>(&Bs[p * PLANE_B + j * STR + kk]);
             }
 #pragma unroll
             for (int a = 0; a < 2; ++a)
@@ -208,28 +234,49 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
     }
     __syncthreads();   // every wavefront is done reading the operand planes
     gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h,
-                        reinterpret_cast<float *>(smem) + wave * GEMM_STAGE_FLOATS(2));
+                        reinterpret_cast<float *>(smem_raw) + wave * GEMM_STAGE_FLOATS(2));
 }
 
-}  // namespace
 
-gt_status gt_gemm_x3_launch(const GemmArgs &g_in, int transA, int transB, int splits, hipStream_t st) {
+template <bool TA, bool TB, bool VA, bool VB, int WGM, int WGN>
+gt_status x3_launch_one(const GemmArgs &g, dim3 grid, hipStream_t st) {
+    constexpr size_t lds = x3_lds_bytes<WGM, WGN>();
+    if (lds > 64 * 1024) {   // host-side setting, no stream operation (also fine under stream capture)
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_x3<TA, TB, VA, VB, WGM, WGN>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    }
+    k_gemm_x3<TA, TB, VA, VB, WGM, WGN><<<grid, 256, lds, st>>>(g);
+    GT_LAUNCH_CHECK("k_gemm_x3");
+    return GT_OK;
+}
+
+template <int WGM, int WGN>
+gt_status x3_launch_shape(const GemmArgs &g_in, int transA, int transB, int splits, hipStream_t st) {
     GemmArgs g = g_in;
+    constexpr int BM = WGM * 64, BN = WGN * 64;
     g.ntn = (int)((g.N + BN - 1) / BN);
     g.ntm = (int)((g.M + BM - 1) / BM);
     dim3 grid(gemm_grid_x(g.ntm, g.ntn), 1, (unsigned)splits);
-#define GT_X3(TA_, TB_)                                                                       \
-    do {                                                                                      \
-        if (g.vecA && g.vecB) k_gemm_x3<TA_, TB_, true, true><<<grid, 256, 0, st>>>(g);       \
-        else if (g.vecA) k_gemm_x3<TA_, TB_, true, false><<<grid, 256, 0, st>>>(g);           \
-        else if (g.vecB) k_gemm_x3<TA_, TB_, false, true><<<grid, 256, 0, st>>>(g);           \
-        else k_gemm_x3<TA_, TB_, false, false><<<grid, 256, 0, st>>>(g);                      \
+#define GT_X3(TA_, TB_)                                                                                   \
+    do {                                                                                                  \
+        if (g.vecA && g.vecB) return x3_launch_one<TA_, TB_, true, true, WGM, WGN>(g, grid, st);          \
+        else if (g.vecA) return x3_launch_one<TA_, TB_, true, false, WGM, WGN>(g, grid, st);              \
+        else if (g.vecB) return x3_launch_one<TA_, TB_, false, true, WGM, WGN>(g, grid, st);              \
+        else return x3_launch_one<TA_, TB_, false, false, WGM, WGN>(g, grid, st);                         \
     } while (0)
     if (!transA && !transB) GT_X3(false, false);
     else if (!transA && transB) GT_X3(false, true);
     else if (transA && !transB) GT_X3(true, false);
     else GT_X3(true, true);
 #undef GT_X3
-    GT_LAUNCH_CHECK("k_gemm_x3");
-    return GT_OK;
+}
+
+}  // namespace
+
+int64_t gt_gemm_x3_tile_m(int64_t N) { return N <= 64 ? 256 : 128; }
+int64_t gt_gemm_x3_tile_n(int64_t N) { return N <= 64 ? 64 : 128; }
+
+gt_status gt_gemm_x3_launch(const GemmArgs &g, int transA, int transB, int splits, hipStream_t st) {
+    if (g.N <= 64) return x3_launch_shape<4, 1>(g, transA, transB, splits, st);
+    return x3_launch_shape<2, 2>(g, transA, transB, splits, st);
 }
