@@ -73,43 +73,6 @@ __device__ inline void ws_load_slice(uint4 (&r)[4], const T *A, int64_t lda, int
 // epilogue is straight-line code.
 template <bool CB, bool EX, bool FAST, int NB>
 __device__ inline void ws_epilogue(const GemmArgs &g, floatx16 (&acc)[NB], int64_t row, int64_t n0, int h, bool vec) {
-    if constexpr (CB && FAST) {
-        // bf16 output, whole column groups: the two lane halves of a row exchange one register
-        // quadruple each (v_permlane32_swap), after which a lane holds EIGHT consecutive columns per
-        // pair of quadruples and writes them as one 16-byte store: half the store instructions, and
-        // 32 contiguous bytes per row and instruction instead of 16.  `vec` says that the rows of C
-        // are 16-byte aligned for that.
-        if (vec) {
-#pragma unroll
-            for (int b = 0; b < NB; ++b) {
-#pragma unroll
-                for (int q = 0; q < 4; q += 2) {
-                    uint32_t lo4[4], hi4[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        float x = acc[b][4 * q + i], y = acc[b][4 * (q + 1) + i];
-                        if (EX) {
-                            x = (g.relu && !(x > 0.0f)) ? 0.0f : x;
-                            y = (g.relu && !(y > 0.0f)) ? 0.0f : y;
-                        }
-                        // lane half 0 keeps its quadruple q and receives half 1's quadruple q;
-                        // lane half 1 receives half 0's quadruple q + 1 and keeps its own q + 1
-                        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(y), false, false);
-                        lo4[i] = r[0];
-                        hi4[i] = r[1];
-                    }
-                    const int64_t col = n0 + b * 32 + 8 * q + 8 * h;
-                    uint4 o;
-                    o.x = gemm_f32_to_bf16(__uint_as_float(lo4[0])) | (gemm_f32_to_bf16(__uint_as_float(lo4[1])) << 16);
-                    o.y = gemm_f32_to_bf16(__uint_as_float(lo4[2])) | (gemm_f32_to_bf16(__uint_as_float(lo4[3])) << 16);
-                    o.z = gemm_f32_to_bf16(__uint_as_float(hi4[0])) | (gemm_f32_to_bf16(__uint_as_float(hi4[1])) << 16);
-                    o.w = gemm_f32_to_bf16(__uint_as_float(hi4[2])) | (gemm_f32_to_bf16(__uint_as_float(hi4[3])) << 16);
-                    *reinterpret_cast<uint4 *>(static_cast<gemm_bf16_t *>(g.C) + row * g.ldc + col) = o;
-                }
-            }
-            return;
-        }
-    }
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
 #pragma unroll
@@ -144,6 +107,81 @@ __device__ inline void ws_epilogue(const GemmArgs &g, floatx16 (&acc)[NB], int64
             }
         }
     }
+}
+
+// fp32 output, whole column groups, rows of C 16-byte aligned: each 32-column group of the block
+// passes through the wavefront's private stage (free at this point: every fragment of the block has
+// been read) and is written row-major, eight lanes per row, so a store instruction covers whole
+// 128-byte lines of 8 rows instead of 32-byte pieces of 32 rows.  Rows past M hold the last row's
+// values (their loads were clamped to it) and are written onto the last row.
+template <bool EX, int NB>
+__device__ inline void ws_epilogue_rows_f32(const GemmArgs &g, floatx16 (&acc)[NB], int64_t row0, int64_t n0, int lane,
+                                            float *stage) {
+    constexpr int SSTR = 36;   // 32 columns + 4: the stage holds 32 x 36 floats
+    const int l32 = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        __asm__ volatile("" ::: "memory");   // LDS operations of a wavefront run in program order; keep that order
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float4 v = make_float4(acc[b][4 * q], acc[b][4 * q + 1], acc[b][4 * q + 2], acc[b][4 * q + 3]);
+            if (EX) {
+                v.x = (g.relu && !(v.x > 0.0f)) ? 0.0f : v.x; v.y = (g.relu && !(v.y > 0.0f)) ? 0.0f : v.y;
+                v.z = (g.relu && !(v.z > 0.0f)) ? 0.0f : v.z; v.w = (g.relu && !(v.w > 0.0f)) ? 0.0f : v.w;
+            }
+            *reinterpret_cast<float4 *>(stage + l32 * SSTR + 8 * q + 4 * h) = v;
+        }
+        __asm__ volatile("" ::: "memory");
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int rr = it * 8 + (lane >> 3), c4 = (lane & 7) * 4;
+            const float4 v = *reinterpret_cast<const float4 *>(stage + rr * SSTR + c4);
+            int64_t row = row0 + rr;
+            if (row >= g.M) row = g.M - 1;
+            *reinterpret_cast<float4 *>(static_cast<float *>(g.C) + row * g.ldc + n0 + b * 32 + c4) = v;
+        }
+    }
+    __asm__ volatile("" ::: "memory");
+}
+
+// The same for a bf16 C whose rows are 16-byte aligned: two 32-column groups at a time are rounded
+// to bf16, staged as 32 rows x 64 columns (128 bytes + 16 of padding per row) and written eight lanes
+// per row, 16 bytes per lane: whole 128-byte lines again.
+template <bool EX, int NB>
+__device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[NB], int64_t row0, int64_t n0, int lane,
+                                             uint32_t *stage) {
+    static_assert(NB % 2 == 0, "column groups are staged in pairs");
+    constexpr int SSTR = 36;   // dwords per staged row: 64 bf16 + 16 bytes
+    const int l32 = lane & 31, h = lane >> 5;
+#pragma unroll
+    for (int bp = 0; bp < NB / 2; ++bp) {
+        __asm__ volatile("" ::: "memory");
+#pragma unroll
+        for (int bb = 0; bb < 2; ++bb) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float v[4] = {acc[2 * bp + bb][4 * q], acc[2 * bp + bb][4 * q + 1], acc[2 * bp + bb][4 * q + 2],
+                              acc[2 * bp + bb][4 * q + 3]};
+                if (EX) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = (g.relu && !(v[i] > 0.0f)) ? 0.0f : v[i];
+                }
+                *reinterpret_cast<uint2 *>(stage + l32 * SSTR + bb * 16 + 4 * q + 2 * h) =
+                    make_uint2(gemm_f32_to_bf16(v[0]) | (gemm_f32_to_bf16(v[1]) << 16),
+                               gemm_f32_to_bf16(v[2]) | (gemm_f32_to_bf16(v[3]) << 16));
+            }
+        }
+        __asm__ volatile("" ::: "memory");
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int rr = it * 8 + (lane >> 3);
+            const uint4 v = *reinterpret_cast<const uint4 *>(stage + rr * SSTR + (lane & 7) * 4);
+            int64_t row = row0 + rr;
+            if (row >= g.M) row = g.M - 1;
+            *reinterpret_cast<uint4 *>(static_cast<gemm_bf16_t *>(g.C) + row * g.ldc + n0 + bp * 64 + (lane & 7) * 8) = v;
+        }
+    }
+    __asm__ volatile("" ::: "memory");
 }
 
 // LDS bytes of an instance: the weight slice, four private A stages, the bias of the column slice
@@ -329,7 +367,9 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
             }
         }
         const int64_t row = rb * 32 + l32;
-        if (FAST) ws_epilogue<sizeof(T) == 2, EX, true, NB>(g, acc, row < g.M ? row : g.M - 1, n0, h, wide_rows);
+        if constexpr (FAST && sizeof(T) == 4) ws_epilogue_rows_f32<EX, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<float *>(As));
+        else if (FAST && wide_rows) ws_epilogue_rows_bf16<EX, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<uint32_t *>(As));
+        else if (FAST) ws_epilogue<sizeof(T) == 2, EX, true, NB>(g, acc, row < g.M ? row : g.M - 1, n0, h, false);
         else if (row < g.M) ws_epilogue<sizeof(T) == 2, EX, false, NB>(g, acc, row, n0, h, out_vec);
     }
 }
@@ -514,7 +554,7 @@ __global__ void __launch_bounds__(256, (ws_x3_per_cu<NB, NS>())) k_gemm_ws_x3(co
             }
         }
         const int64_t row = rb * 32 + l32;
-        if (FAST) ws_epilogue<false, EX, true, NB>(g, acc, row < g.M ? row : g.M - 1, n0, h, true);
+        if constexpr (FAST) ws_epilogue_rows_f32<EX, NB>(g, acc, rb * 32, n0, lane, As);
         else if (row < g.M) ws_epilogue<false, EX, false, NB>(g, acc, row, n0, h, out_vec);
     }
 }
