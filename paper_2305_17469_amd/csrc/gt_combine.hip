@@ -291,14 +291,17 @@ SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
     int64_t want, max_by_len;
     if (t.small) {
         if (tiles >= 128 || K < 2 * KT) return p;
-        want = (256 + tiles - 1) / tiles;                     // about one workgroup per CU
+        want = 256 / tiles;                                   // about one workgroup per CU, in one round
         max_by_len = K / KT;                                  // at least one 64-wide k-range per split
     } else {
         // The reduction is cut when the output has too few tiles to fill the chip: the weight-gradient
         // shape (very long K), and a tall product over a very wide feature row with few rows
         if (tiles >= 256 || K < 8 * KT) return p;
         if (!transA && (tiles >= 128 || K < 1024)) return p;
-        want = (512 + tiles - 1) / tiles;                     // about two workgroups per CU
+        // two workgroups per CU, and never more blocks than those 512 places: the blocks of a split
+        // reduction all run equally long, so a few left over for a second round double the kernel's
+        // time (5 tiles x 103 ranges = 515 blocks took 0.31 ms, 5 x 102 = 510 take 0.17 ms)
+        want = 512 / tiles;
         max_by_len = K / (4 * KT);                            // at least 4 k-tiles per split
     }
     if (want > max_by_len) want = max_by_len;
