@@ -214,7 +214,7 @@ __device__ inline int64_t agg_item_block(int run) {
     return bx;
 }
 
-// Run length for a grid of gx item blocks: as long as possible for L2 reuse, but at least 64 rounds
+// Run length for a grid of gx item blocks: as long as possible for L2 reuse, but at least 64 turns
 // over the 8 XCDs so that the longest-first order stays balanced (measured on MI355X: 2^18-vertex
 // graph, 512-byte rows, 0.58 -> 0.50 ms at 64; narrow rows and small grids prefer 16-32; 256 was
 // slower than 64 on a 2^21-vertex graph).

@@ -291,7 +291,7 @@ SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
     int64_t want, max_by_len;
     if (t.small) {
         if (tiles >= 128 || K < 2 * KT) return p;
-        want = 256 / tiles;                                   // about one workgroup per CU, in one round
+        want = 256 / tiles;                                   // about one workgroup per CU, all resident at once
         max_by_len = K / KT;                                  // at least one 64-wide k-range per split
     } else {
         // The reduction is cut when the output has too few tiles to fill the chip: the weight-gradient
@@ -299,7 +299,7 @@ SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
         if (tiles >= 256 || K < 8 * KT) return p;
         if (!transA && (tiles >= 128 || K < 1024)) return p;
         // two workgroups per CU, and never more blocks than those 512 places: the blocks of a split
-        // reduction all run equally long, so a few left over for a second round double the kernel's
+        // reduction all run equally long, so a few left over once the places are full double the kernel's
         // time (5 tiles x 103 ranges = 515 blocks took 0.31 ms, 5 x 102 = 510 take 0.17 ms)
         want = 512 / tiles;
         max_by_len = K / (4 * KT);                            // at least 4 k-tiles per split
@@ -385,7 +385,7 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     // fp32 products with enough work to be bound by matrix throughput go through the split-bf16 kernel
     // (3/8 of the fp32 MFMA cost at fp32-level accuracy): 128 x 128 tiles in general, 256 x 64 tiles for
     // outputs of 33..64 columns (a sampled block's 91 K x 602 -> 64 product: 111 -> 60 us; the plain kernel's
-    // 357 tiles of slow fp32 MFMA took two rounds over the SIMDs).  Narrower outputs keep the plain fp32
+    // 357 tiles of slow fp32 MFMA, four wavefronts each, passed over the 1,024 SIMDs twice).  Narrower outputs keep the plain fp32
     // MFMA (256 x 32 tiles), except a small weight gradient (at most 256 x 64 outputs over a long
     // reduction), where the plain kernel's tile is mostly padding and the slow fp32 MFMA makes that
     // padding the bottleneck (config 2, 128 x 41: 0.093 -> 0.06 ms).
