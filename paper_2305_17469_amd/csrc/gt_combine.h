@@ -156,6 +156,7 @@ __device__ inline void gemm_epilogue(const GemmArgs &g, floatx16 (&acc)[TM][TN],
 
 // fp32 GEMM through three-way bf16 splitting (gt_combine_x3.hip); 128 x 128 workgroup tiles.
 gt_status gt_gemm_x3_launch(const GemmArgs &g, int transA, int transB, int splits, hipStream_t st);
+void gt_gemm_x3_tile(int64_t M, int64_t N, int64_t *bm, int64_t *bn);
 
 // Weight-stationary kernel for tall products with small K and N (gt_combine_ws.hip).
 bool gt_gemm_ws_applicable(gt_dtype dtype, int transA, int64_t M, int64_t N, int64_t K, int vecA);

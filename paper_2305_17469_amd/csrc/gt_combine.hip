@@ -281,10 +281,24 @@ TileShape pick_tile(int64_t M, int64_t N, int64_t K) {
     return TileShape{bm, bn, false};
 }
 
+// fp32 products with enough work to be bound by matrix throughput go through the split-bf16 kernel
+// (3/8 of the fp32 MFMA cost at fp32-level accuracy): 128 x 128 tiles in general, 256 x 64 tiles for
+// outputs of 33..64 columns (a sampled block's 91 K x 602 -> 64 product: 111 -> 80 us; the plain kernel's
+// 357 tiles of slow fp32 MFMA, four wavefronts each, passed over the 1,024 SIMDs twice), 64 x 256 tiles
+// for outputs of at most 64 rows.  Narrower outputs keep the plain fp32 MFMA (256 x 32 tiles), except a
+// small weight gradient (at most 256 x 64 outputs over a long reduction), where the plain kernel's tile
+// is mostly padding and the slow fp32 MFMA makes that padding the bottleneck (config 2, 128 x 41:
+// 0.093 -> 0.06 ms).
+bool use_x3(gt_dtype dtype, int transA, int64_t M, int64_t N, int64_t K) {
+    const bool big = (double)M * (double)N * (double)K >= 268435456.0;
+    return dtype == GT_F32 && K >= 64 && big && (N > 32 || (transA && N >= 32 && M <= 256));
+}
+
 struct SplitPlan { int splits; int64_t k_per_split; };
 
-SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K) {
-    const TileShape t = pick_tile(M, N, K);
+SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K, bool x3) {
+    TileShape t = pick_tile(M, N, K);
+    if (x3) { gt_gemm_x3_tile(M, N, &t.bm, &t.bn); t.small = false; }
     const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
     SplitPlan p{1, (K + KT - 1) / KT * KT};
     if (K <= 0) { p.k_per_split = KT; return p; }
@@ -345,9 +359,12 @@ gt_status launch_gemm_t(const GemmArgs &g, int transA, int transB, int splits, h
 
 }  // namespace
 
+// the data type is not known here: the larger of the two plans
 size_t gt_gemm_ws_bytes(int transA, int64_t M, int64_t N, int64_t K) {
-    const SplitPlan p = plan_split(transA, M, N, K);
-    return p.splits > 1 ? gt_align_up((size_t)p.splits * (size_t)M * (size_t)N * 4) : 0;
+    const SplitPlan p = plan_split(transA, M, N, K, false);
+    const SplitPlan q = plan_split(transA, M, N, K, use_x3(GT_F32, transA, M, N, K));
+    const int splits = p.splits > q.splits ? p.splits : q.splits;
+    return splits > 1 ? gt_align_up((size_t)splits * (size_t)M * (size_t)N * 4) : 0;
 }
 
 gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
@@ -365,7 +382,8 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     const size_t es = gt_dtype_size(dtype), cs = gt_dtype_size(c_dtype);
     if (((uintptr_t)A % es) || ((uintptr_t)B % es) || ((uintptr_t)C % cs) || ((uintptr_t)Cin % cs))
         return gt_fail(GT_ERR_INVALID_ARG, "%s: pointer misaligned for dtype", fn);
-    const SplitPlan p = plan_split(transA, M, N, K);
+    const bool x3 = use_x3(dtype, transA, M, N, K);
+    const SplitPlan p = plan_split(transA, M, N, K, x3);
     const size_t need = p.splits > 1 ? gt_align_up((size_t)p.splits * (size_t)M * (size_t)N * 4) : 0;
     if (need) {
         if (!ws || ((uintptr_t)ws & 255)) return gt_fail(GT_ERR_WORKSPACE, "%s: ws null or not 256-byte aligned", fn);
@@ -382,15 +400,6 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     g.Cin = Cin; g.ldcin = ldcin;
     if (p.splits > 1) { g.C = ws; g.ldc = N; } else { g.C = C; g.ldc = ldc; }
     const int tr = gt_trace_open(GT_TRACE_COMBINE, N, M, M * N * K, st);
-    // fp32 products with enough work to be bound by matrix throughput go through the split-bf16 kernel
-    // (3/8 of the fp32 MFMA cost at fp32-level accuracy): 128 x 128 tiles in general, 256 x 64 tiles for
-    // outputs of 33..64 columns (a sampled block's 91 K x 602 -> 64 product: 111 -> 60 us; the plain kernel's
-    // 357 tiles of slow fp32 MFMA, four wavefronts each, passed over the 1,024 SIMDs twice).  Narrower outputs keep the plain fp32
-    // MFMA (256 x 32 tiles), except a small weight gradient (at most 256 x 64 outputs over a long
-    // reduction), where the plain kernel's tile is mostly padding and the slow fp32 MFMA makes that
-    // padding the bottleneck (config 2, 128 x 41: 0.093 -> 0.06 ms).
-    const bool big = (double)M * (double)N * (double)K >= 268435456.0;
-    const bool x3 = dtype == GT_F32 && K >= 64 && big && (N > 32 || (transA && N >= 32 && M <= 256));
     // tall products with a small weight matrix are bound by streaming A and C once: the
     // weight-stationary kernel does exactly that
     const bool ws_path = p.splits == 1 && c_dtype == dtype && !Cin && !rowscale &&

@@ -273,10 +273,17 @@ gt_status x3_launch_shape(const GemmArgs &g_in, int transA, int transB, int spli
 
 }  // namespace
 
-int64_t gt_gemm_x3_tile_m(int64_t N) { return N <= 64 ? 256 : 128; }
-int64_t gt_gemm_x3_tile_n(int64_t N) { return N <= 64 ? 64 : 128; }
+// Tile of the split-bf16 kernel for an M x N output: 256 x 64 for at most 64 columns, 64 x 256 for at
+// most 64 rows (the weight gradient of a layer with a narrow input: a 128-row tile would be mostly
+// padding, and the padding is multiplied like everything else), 128 x 128 otherwise.
+void gt_gemm_x3_tile(int64_t M, int64_t N, int64_t *bm, int64_t *bn) {
+    if (N <= 64) { *bm = 256; *bn = 64; }
+    else if (M <= 64) { *bm = 64; *bn = 256; }
+    else { *bm = 128; *bn = 128; }
+}
 
 gt_status gt_gemm_x3_launch(const GemmArgs &g, int transA, int transB, int splits, hipStream_t st) {
     if (g.N <= 64) return x3_launch_shape<4, 1>(g, transA, transB, splits, st);
+    if (g.M <= 64) return x3_launch_shape<1, 4>(g, transA, transB, splits, st);
     return x3_launch_shape<2, 2>(g, transA, transB, splits, st);
 }

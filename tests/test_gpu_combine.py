@@ -29,7 +29,9 @@ SHAPES = [(1, 1, 1), (300, 64, 64), (257, 16, 100), (515, 41, 128), (130, 47, 25
           (8192, 3, 5), (9000, 70, 250),
           # the layers of a sampled batch: few rows, 64 x 64 tiles with a finely cut reduction; and a shape just
           # large enough to keep the big tiles
-          (1024, 47, 256), (1100, 256, 47), (3000, 200, 300)]
+          (1024, 47, 256), (1100, 256, 47), (3000, 200, 300),
+          # at most 64 output rows over a long reduction: 64 x 256 tiles of the split-bf16 kernel
+          (48, 300, 20000)]
 
 
 def _check(got, ref, absr, dtype, c_bf16, what):
