@@ -7,7 +7,8 @@ Every workload is a dict:
   blocks : list (one per layer) of dict(rowptr, colidx, n_dst, n_src)
   dims   : [F_in, hidden..., F_out]
   X      : fp32 [n_src(layer 1), F_in]   (bf16-representable values when dtype == "bf16")
-  W, b   : per layer fp32 [F_l, F_{l+1}] / zeros[F_{l+1}];  W_root for "sage"
+  W, b   : per layer fp32 Glorot [F_l, F_{l+1}] / bias 0.1 N(0,1) [F_{l+1}] (non-zero, so that a
+           dropped or misplaced bias shows in every comparison);  W_root for "sage"
   G      : fp32 upstream gradient of the linear probe loss L = <G, Out>, shape of the output
 """
 from __future__ import annotations
@@ -29,7 +30,7 @@ def _dense(seed, n_rows, dims, dtype, sage=False, n_out=None):
             w = tensors.bf16_values(w)
         W.append(w)
         Wr.append(wr)
-        b.append(np.zeros(dims[l + 1], dtype=np.float32))
+        b.append((0.1 * tensors.normal((dims[l + 1],), seed, 50 + l)).astype(np.float32))
     if dtype == "bf16":
         X = tensors.bf16_values(X)
     G = tensors.normal((n_out if n_out is not None else n_rows, dims[-1]), seed, 30)

@@ -20,7 +20,7 @@
  *              all device memory (inputs, outputs, workspaces); the library never allocates or
  *              frees device memory and never keeps a pointer beyond what is stated.
  *   Streams    `stream` is a hipStream_t passed as void* (NULL = the default stream).  Compute
- *              calls only enqueue work and return; gt_graph_create synchronises the stream once.
+ *              calls only enqueue work and return; gt_graph_create synchronises the stream (twice).
  *   dtype      GT_F32: fp32 storage and arithmetic.  GT_BF16: bf16 storage (round-to-nearest-
  *              even on store), fp32 accumulation.
  *   Errors     every call returns a gt_status; nothing throws, aborts or prints.  Arguments
@@ -44,7 +44,7 @@ extern "C" {
 typedef enum {
     GT_OK = 0,
     GT_ERR_INVALID_ARG = 1,  /* null pointer, negative size, ld < width, aliasing in == out */
-    GT_ERR_UNSUPPORTED = 2,  /* e.g. symmetric norm on a non-square graph, E >= 2^31        */
+    GT_ERR_UNSUPPORTED = 2,  /* e.g. symmetric norm on a non-square graph, E >= 2^31 - 1024 */
     GT_ERR_WORKSPACE = 3,    /* workspace pointer null / misaligned / too small             */
     GT_ERR_HIP = 4,          /* a HIP runtime call failed (message in gt_last_error)        */
     GT_ERR_INTERNAL = 5
@@ -86,8 +86,9 @@ gt_status gt_graph_plan_size(int64_t n_dst, int64_t n_src, int64_t n_edges, int 
 /* rowptr[n_dst+1], colidx[n_edges] (source ids in [0, n_src)), edge_weight[n_edges] or NULL:
  * device, int32/fp32, borrowed until gt_graph_destroy.  ws: device, 256-byte aligned, at
  * least gt_graph_plan_size bytes, borrowed likewise (it holds the plan).  Enqueues the plan
- * kernels on `stream` and synchronises it once to read back the work-list sizes.
- * Errors: INVALID_ARG (null/negative), UNSUPPORTED (n_edges or n_* >= 2^31 - 1), WORKSPACE, HIP. */
+ * kernels on `stream` and synchronises it twice: once to read back the work-list sizes, once
+ * before returning, so that the finished plan may be used from any stream.
+ * Errors: INVALID_ARG (null/negative), UNSUPPORTED (n_edges or n_* >= 2^31 - 1024), WORKSPACE, HIP. */
 gt_status gt_graph_create(gt_graph **g /* host out */, int64_t n_dst, int64_t n_src, int64_t n_edges,
                           const int32_t *rowptr, const int32_t *colidx, const float *edge_weight,
                           void *ws, size_t ws_bytes, void *stream);
@@ -249,19 +250,27 @@ gt_status gt_layer_ws_size(const gt_graph *g, const gt_layer_desc *d,
 
 /* X[n_src,in_dim] (ldx), W[in_dim,out_dim] and W_root (dense, ld = out_dim; NULL iff !has_root)
  * in d->dtype, b[out_dim] fp32 or NULL, Y[n_dst,out_dim] (ldy) in d->dtype.  `req` forces an
- * order or GT_AUTO; *used (host, may be NULL) receives the order that ran. */
+ * order or GT_AUTO; *used (host, may be NULL) receives the order that ran.
+ * saved / scratch: device, 256-byte aligned, at least the sizes gt_layer_ws_size reports
+ * (saved_bytes / scratch_bytes are the callers' buffer sizes; GT_ERR_WORKSPACE when too small,
+ * before anything is launched).  `saved` is written only by an aggregation-first forward and
+ * may be NULL (saved_bytes 0) when GT_COMB_FIRST is forced.  X and Y must not overlap
+ * (GT_ERR_INVALID_ARG). */
 gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_order req,
                        const void *X, int64_t ldx, const void *W, const void *W_root, const float *b,
-                       void *Y, int64_t ldy, void *saved, void *scratch, gt_order *used, void *stream);
+                       void *Y, int64_t ldy, void *saved, size_t saved_bytes,
+                       void *scratch, size_t scratch_bytes, gt_order *used, void *stream);
 
 /* dY[n_dst,out_dim] in d->dtype; X, W, W_root, Y, saved as given to / produced by gt_layer_fwd
  * with forward order `fwd_used`.  Outputs: dX[n_src,in_dim] in d->dtype (NULL iff !need_dx),
  * dW[in_dim,out_dim], dW_root (NULL iff !has_root), db[out_dim] (may be NULL): always fp32,
- * overwritten (not accumulated).  `req` forces the backward order or GT_AUTO. */
+ * overwritten (not accumulated).  `req` forces the backward order or GT_AUTO.  saved / scratch
+ * and their sizes as for gt_layer_fwd (`saved` is read only after an aggregation-first forward);
+ * dX must not overlap dY or X. */
 gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_order fwd_used, gt_order req,
                        const void *dY, int64_t lddy, const void *X, int64_t ldx,
                        const void *W, const void *W_root, const void *Y, int64_t ldy,
-                       const void *saved, void *scratch,
+                       const void *saved, size_t saved_bytes, void *scratch, size_t scratch_bytes,
                        void *dX, int64_t lddx, float *dW, float *dW_root, float *db,
                        gt_order *used, void *stream);
 

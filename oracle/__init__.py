@@ -223,20 +223,17 @@ def layer_fwd(blk, reduce, X, W, b, relu, order="agg_first", W_root=None, ew=Non
     return dict(M=M, Z=Z, H=H)
 
 
-def layer_bwd(blk, reduce, X, W, Z, dH, relu, order="agg_first", W_root=None, ew=None, need_dx=True, mask=None):
-    """Gradients of one layer for upstream dH: dZ = dH * [Z > 0]; db = column sums of dZ;
-    dW = (A X)^T dZ; dX = A^T (dZ W^T) ["agg_first": the transposed aggregation runs at width
-    F_in] or (A^T dZ) W^T ["comb_first": at width F_out]; the root term adds X[:n_dst]^T dZ and
-    dZ W_root^T on the first n_dst rows.
-    `mask` (boolean, shape of Z) replaces the decision [Z > 0]: the ReLU derivative is a yes/no
-    decision taken from a floating-point value, so a parity test hands over the decision the
-    compared implementation took in its own precision (and checks separately that the two
-    decisions differ only where |Z| is at rounding level)."""
+def layer_bwd(blk, reduce, X, W, Z, dH, relu, order="agg_first", W_root=None, ew=None, need_dx=True):
+    """Gradients of one layer for upstream dH: dZ = dH * [Z > 0] (the activation's derivative,
+    "Training for GNNs"; ReLU'(0) = 0, always decided from this function's own Z); db = column
+    sums of dZ; dW = (A X)^T dZ; dX = A^T (dZ W^T) ["agg_first": the transposed aggregation runs
+    at width F_in] or (A^T dZ) W^T ["comb_first": at width F_out]; the root term adds
+    X[:n_dst]^T dZ and dZ W_root^T on the first n_dst rows."""
     rp, ci, ns, nd = blk["rowptr"], blk["colidx"], blk["n_src"], blk["n_dst"]
     X = np.asarray(X, dtype=np.float64)
     dZ = np.asarray(dH, dtype=np.float64)
     if relu:
-        dZ = dZ * ((np.asarray(Z) > 0.0) if mask is None else np.asarray(mask, dtype=bool))
+        dZ = dZ * (np.asarray(Z) > 0.0)
     db = dZ.sum(axis=0)
     out = dict(dZ=dZ, db=db, dW_root=None, dX=None)
     if order == "agg_first":
@@ -278,9 +275,13 @@ def model_fwd(cfg, order="agg_first", round_outputs=None):
     return states
 
 
-def model_bwd(cfg, states, order="agg_first", round_outputs=None, masks=None):
+def model_bwd(cfg, states, order="agg_first", round_outputs=None, stop=None):
     """Backward of the linear probe loss L = <G, Out>: dOut = G.  The first layer's dX is not
-    needed (only parameter gradients are; cf. the cost-model paragraph on the first layer)."""
+    needed (only parameter gradients are; cf. the cost-model paragraph on the first layer).
+    `stop` (optional, one boolean array or None per layer, shape of that layer's output) marks
+    output elements whose upstream gradient is taken as zero before the layer's backward: the
+    gradient of the same model with those elements cut out of the loss.  It is an input of the
+    computation like G; the ReLU decisions stay this function's own."""
     rnd = (cfg["dtype"] == "bf16") if round_outputs is None else round_outputs
     L = len(cfg["W"])
     orders = order if isinstance(order, (list, tuple)) else [order] * L
@@ -289,9 +290,10 @@ def model_bwd(cfg, states, order="agg_first", round_outputs=None, masks=None):
     for l in reversed(range(L)):
         relu = l < L - 1
         st = states[l]
+        if stop is not None and stop[l] is not None:
+            dH = np.where(np.asarray(stop[l], dtype=bool), 0.0, dH)
         g = layer_bwd(cfg["blocks"][l], cfg["reduce"], st["X"], cfg["W"][l], st["Z"], dH, relu, orders[l],
-                      cfg["W_root"][l], cfg.get("ew"), need_dx=(l > 0),
-                      mask=None if masks is None else masks[l])
+                      cfg["W_root"][l], cfg.get("ew"), need_dx=(l > 0))
         if l > 0 and rnd:
             g["dX"] = round_bf16(g["dX"])
         grads[l] = g

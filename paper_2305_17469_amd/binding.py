@@ -91,10 +91,10 @@ lib.gt_cost_benefits.argtypes = [POINTER(gt_cost_coeffs), c_int64, c_int64, c_in
 lib.gt_layer_decide.argtypes = [c_void_p, POINTER(gt_layer_desc), POINTER(c_int), POINTER(c_int)]
 lib.gt_layer_ws_size.argtypes = [c_void_p, POINTER(gt_layer_desc), POINTER(c_size_t), POINTER(c_size_t)]
 lib.gt_layer_fwd.argtypes = [c_void_p, POINTER(gt_layer_desc), c_int, c_void_p, c_int64, c_void_p, c_void_p, c_void_p,
-                             c_void_p, c_int64, c_void_p, c_void_p, POINTER(c_int), c_void_p]
+                             c_void_p, c_int64, c_void_p, c_size_t, c_void_p, c_size_t, POINTER(c_int), c_void_p]
 lib.gt_layer_bwd.argtypes = [c_void_p, POINTER(gt_layer_desc), c_int, c_int, c_void_p, c_int64, c_void_p, c_int64,
-                             c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_int64, c_void_p,
-                             c_void_p, c_void_p, POINTER(c_int), c_void_p]
+                             c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_size_t, c_void_p, c_size_t, c_void_p,
+                             c_int64, c_void_p, c_void_p, c_void_p, POINTER(c_int), c_void_p]
 lib.gt_trace_enable.argtypes = [c_int]
 lib.gt_trace_reset.argtypes = []
 lib.gt_trace_count.argtypes = [POINTER(c_int64)]
@@ -330,7 +330,8 @@ def gt_layer_fwd(g: Graph, desc, X, W, b, bufs: LayerBuffers, order="auto", W_ro
     Y = torch.empty((g.n_dst, desc.out_dim), dtype=tdt, device=X.device) if out is None else out
     used = c_int()
     _check(lib.gt_layer_fwd(g.handle, byref(desc), ORDER[order], _ptr(X), _rows2d(X), _ptr(W), _ptr(W_root), _ptr(b),
-                            _ptr(Y), _rows2d(Y), _ptr(bufs.saved), _ptr(bufs.scratch), byref(used), _stream()))
+                            _ptr(Y), _rows2d(Y), _ptr(bufs.saved), bufs.saved.numel(), _ptr(bufs.scratch),
+                            bufs.scratch.numel(), byref(used), _stream()))
     return Y, ORDER_NAME[used.value]
 
 
@@ -347,7 +348,8 @@ def gt_layer_bwd(g: Graph, desc, fwd_used, dY, X, W, Y, bufs: LayerBuffers, orde
     used = c_int()
     _check(lib.gt_layer_bwd(g.handle, byref(desc), ORDER[fwd_used], ORDER[order], _ptr(dY), _rows2d(dY), _ptr(X),
                             _rows2d(X), _ptr(W), _ptr(W_root), _ptr(Y), _rows2d(Y) if Y is not None else 0,
-                            _ptr(bufs.saved), _ptr(bufs.scratch), _ptr(dX), _rows2d(dX) if dX is not None else 0,
+                            _ptr(bufs.saved), bufs.saved.numel(), _ptr(bufs.scratch), bufs.scratch.numel(),
+                            _ptr(dX), _rows2d(dX) if dX is not None else 0,
                             _ptr(dW), _ptr(dWr), _ptr(db), byref(used), _stream()))
     return dict(dX=dX, dW=dW, dW_root=dWr, db=db, used=ORDER_NAME[used.value])
 

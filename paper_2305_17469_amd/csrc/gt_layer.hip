@@ -271,6 +271,11 @@ gt_status check_desc(const char *fn, const gt_graph *g, const gt_layer_desc *d) 
 
 void *at(void *base, size_t off) { return static_cast<char *>(base) + off; }
 
+bool ranges_overlap(const void *a, size_t a_elems, const void *b, size_t b_elems, size_t es) {
+    const char *a0 = static_cast<const char *>(a), *b0 = static_cast<const char *>(b);
+    return a0 < b0 + b_elems * es && b0 < a0 + a_elems * es;
+}
+
 void decide(const gt_graph *g, const gt_layer_desc *d, gt_order *fwd, gt_order *bwd) {
     const gt_cost_coeffs &c = cost_of(d->dtype);
     const double ns = (double)g->n_src, nd = (double)g->n_dst, E = (double)g->n_edges;
@@ -418,7 +423,8 @@ extern "C" gt_status gt_layer_ws_size(const gt_graph *g, const gt_layer_desc *d,
 
 extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_order req, const void *X, int64_t ldx,
                                   const void *W, const void *W_root, const float *b, void *Y, int64_t ldy, void *saved,
-                                  void *scratch, gt_order *used, void *stream) {
+                                  size_t saved_bytes, void *scratch, size_t scratch_bytes, gt_order *used,
+                                  void *stream) {
     const char *fn = "gt_layer_fwd";
     gt_status s = check_desc(fn, g, d);
     if (s != GT_OK) return s;
@@ -429,10 +435,17 @@ extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_
     if (!scratch || ((uintptr_t)scratch & 255)) return gt_fail(GT_ERR_WORKSPACE, "%s: scratch null or not 256-byte aligned", fn);
     hipStream_t st = (hipStream_t)stream;
     const LayerLayout L = layer_layout(g, d);
+    if (scratch_bytes < L.total)
+        return gt_fail(GT_ERR_WORKSPACE, "%s: scratch_bytes %zu < required %zu", fn, scratch_bytes, L.total);
+    if (ranges_overlap(X, (size_t)g->n_src * ldx, Y, (size_t)g->n_dst * ldy, gt_dtype_size(d->dtype)))
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: X and Y overlap", fn);
     gt_order order = req;
     if (order == GT_AUTO) { gt_order bw; decide(g, d, &order, &bw); }
-    if (order == GT_AGG_FIRST && (!saved || ((uintptr_t)saved & 255)))
-        return gt_fail(GT_ERR_WORKSPACE, "%s: saved null or not 256-byte aligned", fn);
+    if (order == GT_AGG_FIRST) {
+        if (!saved || ((uintptr_t)saved & 255)) return gt_fail(GT_ERR_WORKSPACE, "%s: saved null or not 256-byte aligned", fn);
+        if (saved_bytes < L.saved)
+            return gt_fail(GT_ERR_WORKSPACE, "%s: saved_bytes %zu < required %zu", fn, saved_bytes, L.saved);
+    }
     if (used) *used = order;
     const gt_dtype t = d->dtype;
     const int64_t fi = d->in_dim, fo = d->out_dim;
@@ -468,9 +481,9 @@ extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_
 
 extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_order fwd_used, gt_order req,
                                   const void *dY, int64_t lddy, const void *X, int64_t ldx, const void *W,
-                                  const void *W_root, const void *Y, int64_t ldy, const void *saved, void *scratch,
-                                  void *dX, int64_t lddx, float *dW, float *dW_root, float *db, gt_order *used,
-                                  void *stream) {
+                                  const void *W_root, const void *Y, int64_t ldy, const void *saved, size_t saved_bytes,
+                                  void *scratch, size_t scratch_bytes, void *dX, int64_t lddx, float *dW,
+                                  float *dW_root, float *db, gt_order *used, void *stream) {
     const char *fn = "gt_layer_bwd";
     gt_status s = check_desc(fn, g, d);
     if (s != GT_OK) return s;
@@ -488,6 +501,13 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
     if (!scratch || ((uintptr_t)scratch & 255)) return gt_fail(GT_ERR_WORKSPACE, "%s: scratch null or not 256-byte aligned", fn);
     hipStream_t st = (hipStream_t)stream;
     const LayerLayout L = layer_layout(g, d);
+    if (scratch_bytes < L.total)
+        return gt_fail(GT_ERR_WORKSPACE, "%s: scratch_bytes %zu < required %zu", fn, scratch_bytes, L.total);
+    if (fwd_used == GT_AGG_FIRST && saved_bytes < L.saved)
+        return gt_fail(GT_ERR_WORKSPACE, "%s: saved_bytes %zu < required %zu", fn, saved_bytes, L.saved);
+    if (dX && (ranges_overlap(dX, (size_t)g->n_src * lddx, dY, (size_t)g->n_dst * lddy, gt_dtype_size(d->dtype)) ||
+               ranges_overlap(dX, (size_t)g->n_src * lddx, X, (size_t)g->n_src * ldx, gt_dtype_size(d->dtype))))
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: dX overlaps dY or X", fn);
     const gt_dtype t = d->dtype;
     const int64_t fi = d->in_dim, fo = d->out_dim;
 

@@ -323,9 +323,11 @@ extern "C" gt_status gt_graph_plan_size(int64_t n_dst, int64_t n_src, int64_t n_
                                         size_t *ws_bytes) {
     if (!ws_bytes) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_plan_size: ws_bytes is null");
     if (n_dst < 0 || n_src < 0 || n_edges < 0) return gt_fail(GT_ERR_INVALID_ARG, "gt_graph_plan_size: negative size");
-    const int64_t lim = 2147483647LL - 1;
+    // int32 indices everywhere; the kernels step through an entry list in strides of up to 512 and
+    // look one stride ahead, so the largest entry index plus two strides must still fit an int32
+    const int64_t lim = 2147483648LL - 1024;
     if (n_dst >= lim || n_src >= lim || n_edges >= lim)
-        return gt_fail(GT_ERR_UNSUPPORTED, "gt_graph_plan_size: sizes must be below 2^31 - 1 (int32 indices)");
+        return gt_fail(GT_ERR_UNSUPPORTED, "gt_graph_plan_size: sizes must be below 2^31 - 1024 (int32 indices)");
     *ws_bytes = plan_layout(n_dst, n_src, n_edges, has_edge_weight != 0).total;
     return GT_OK;
 }

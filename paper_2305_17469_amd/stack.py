@@ -92,7 +92,8 @@ class LayerStack:
             B._check(B.lib.gt_layer_bwd(g.handle, B.byref(d), B.ORDER[self.used_fwd[l]], B.ORDER[orders[l]],
                                         B._ptr(dh), dh.stride(0), B._ptr(x), x.stride(0), B._ptr(self.W[l]),
                                         B._ptr(self.W_root[l]), B._ptr(self.H[l]), self.H[l].stride(0),
-                                        B._ptr(self.bufs[l].saved), B._ptr(self.bufs[l].scratch),
+                                        B._ptr(self.bufs[l].saved), self.bufs[l].saved.numel(),
+                                        B._ptr(self.bufs[l].scratch), self.bufs[l].scratch.numel(),
                                         B._ptr(dX), dX.stride(0) if dX is not None else 0, B._ptr(self.dW[l]),
                                         B._ptr(self.dW_root[l]), B._ptr(self.db[l]), B.byref(used), stream))
             self.used_bwd[l] = B.ORDER_NAME[used.value]

@@ -40,6 +40,8 @@ def test_plan_size_validation():
     assert B.lib.gt_graph_plan_size(1 << 21, 1 << 21, 55_000_000, 1, byref(n)) == B.GT_OK and n.value > small
     assert B.lib.gt_graph_plan_size(-1, 10, 50, 0, byref(n)) == 1          # INVALID_ARG
     assert B.lib.gt_graph_plan_size(10, 10, 1 << 31, 0, byref(n)) == 2      # UNSUPPORTED: int32 indices
+    assert B.lib.gt_graph_plan_size(10, 10, (1 << 31) - 1024, 0, byref(n)) == 2
+    assert B.lib.gt_graph_plan_size(10, 10, (1 << 31) - 1025, 0, byref(n)) == B.GT_OK
     assert B.lib.gt_graph_plan_size(10, 10, 50, 0, None) == 1
     assert b"gt_graph_plan_size" in B.lib.gt_last_error()
     assert B.lib.gt_graph_plan_size(0, 0, 0, 0, byref(n)) == B.GT_OK        # empty graph is valid

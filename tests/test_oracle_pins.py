@@ -323,7 +323,6 @@ def test_backward_matches_central_finite_differences(which):
                           cfg["W_root"][0], None, need_dx=True)
     rng = np.random.default_rng(77)
     h = 1e-6
-    minz = min(np.abs(s["Z"]).min() for s in st[:-1]) if len(st) > 1 else 1.0
 
     def fd(arr, idx):
         old = arr[idx]
@@ -346,7 +345,58 @@ def test_backward_matches_central_finite_differences(which):
     for _ in range(6):
         i, j = rng.integers(cfg["X"].shape[0]), rng.integers(cfg["X"].shape[1])
         checks.append((fd(cfg["X"], (i, j)), g0["dX"][i, j]))
-    assert minz > 1e-4 or True   # ReLU kinks: a step of 1e-6 crosses one only if |Z| < ~1e-5
+    # (a step of 1e-6 crosses a ReLU kink only where |Z| < ~1e-5; such a crossing would fail below)
     scale = max(abs(a) for _, a in checks)
     for num, ana in checks:
         assert abs(num - ana) <= 2e-6 * scale + 1e-7, (num, ana)
+
+
+def test_stop_sets_cut_elements_out_of_the_gradient():
+    """model_bwd(stop=...) zeroes the upstream gradient of the marked output elements.  Pins: an
+    all-false set changes nothing; on the last layer it equals zeroing G there; on a hidden layer
+    it is the gradient of the model in which those activations are held constant (checked by
+    central differences on a forward pass that re-inserts the unperturbed values)."""
+    cfg = dict(small_cfgs()[0])
+    cfg["X"] = cfg["X"].astype(np.float64)
+    cfg["W"] = [w.astype(np.float64) for w in cfg["W"]]
+    L = len(cfg["W"])
+    st = oracle.model_fwd(cfg, "agg_first", round_outputs=False)
+    base = oracle.model_bwd(cfg, st, "agg_first", round_outputs=False)
+    none = oracle.model_bwd(cfg, st, "agg_first", round_outputs=False,
+                            stop=[np.zeros(s["H"].shape, bool) for s in st])
+    for a, b in zip(base, none):
+        assert np.array_equal(a["dW"], b["dW"]) and np.array_equal(a["db"], b["db"])
+    rng = np.random.default_rng(3)
+    S_last = rng.random(st[-1]["H"].shape) < 0.3
+    cfg2 = dict(cfg)
+    cfg2["G"] = np.where(S_last, 0.0, cfg["G"])
+    a = oracle.model_bwd(cfg, st, "agg_first", round_outputs=False, stop=[None] * (L - 1) + [S_last])
+    b = oracle.model_bwd(cfg2, st, "agg_first", round_outputs=False)
+    for x, y in zip(a, b):
+        assert np.array_equal(x["dW"], y["dW"]) and np.array_equal(x["db"], y["db"])
+    # hidden layer 0: activations in S are constants of the loss
+    S0 = rng.random(st[0]["H"].shape) < 0.3
+    g = oracle.model_bwd(cfg, st, "agg_first", round_outputs=False, stop=[S0] + [None] * (L - 1))
+    assert np.abs(g[0]["dW"] - base[0]["dW"]).max() > 1e-3 * np.abs(base[0]["dW"]).max()   # the set matters
+    for l in range(1, L):
+        assert np.array_equal(g[l]["dW"], base[l]["dW"])                 # layers above it are untouched
+    H0_fixed = st[0]["H"]
+
+    def loss():
+        s0 = oracle.layer_fwd(cfg["blocks"][0], cfg["reduce"], cfg["X"], cfg["W"][0], cfg["b"][0], True)
+        H = np.where(S0, H0_fixed, s0["H"])
+        for l in range(1, L):
+            H = oracle.layer_fwd(cfg["blocks"][l], cfg["reduce"], H, cfg["W"][l], cfg["b"][l], l < L - 1)["H"]
+        return float(np.sum(np.asarray(cfg["G"], dtype=np.float64) * H))
+
+    h = 1e-6
+    scale = np.abs(g[0]["dW"]).max()
+    for _ in range(5):
+        i, j = rng.integers(cfg["W"][0].shape[0]), rng.integers(cfg["W"][0].shape[1])
+        old = cfg["W"][0][i, j]
+        cfg["W"][0][i, j] = old + h
+        lp = loss()
+        cfg["W"][0][i, j] = old - h
+        lm = loss()
+        cfg["W"][0][i, j] = old
+        assert abs((lp - lm) / (2 * h) - g[0]["dW"][i, j]) <= 2e-6 * scale + 1e-7
