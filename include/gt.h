@@ -134,6 +134,21 @@ gt_status gt_aggregate_bwd(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, 
                            const void *dY, int64_t lddy, void *dX, int64_t lddx,
                            void *ws, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): gt_aggregate_fwd with the scratch for the partial
+ * rows of split long rows taken from a fixed array inside the library (32 MiB per GPU, held from
+ * library load until the process ends) instead of a caller workspace.  Same arguments, checks,
+ * kernels and results (bit for bit) as gt_aggregate_fwd.  Calls no hipMalloc / hipFree or other
+ * allocating routine and records no kernel-timing events.  If the graph's partial rows at width
+ * F need more than gt_aggregate_static_capacity() bytes (compare gt_aggregate_ws_size), returns
+ * GT_ERR_WORKSPACE and launches nothing.  The GPU that is current at the call must be the one
+ * that holds the graph and the tensors.  All calls on one GPU share the one array: calls that
+ * may overlap in time on the same GPU (different streams or threads) race on it and must be
+ * serialised by the caller; nothing in it needs to be cleared between calls. */
+gt_status gt_aggregate_static_capacity(size_t *bytes /* host */);
+gt_status gt_aggregate_fwd_static(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, int64_t F,
+                                  const void *X, int64_t ldx, void *Y, int64_t ldy, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Edge weighting: NeighborApply (the edge-weight function g of the source and destination
  * embeddings per edge, i.e. SDDMM) and Pull with per-call edge weights (the function h that

@@ -48,7 +48,8 @@ class GtError(RuntimeError):
 
 
 EXPORTS = ["gt_graph_plan_size", "gt_graph_create", "gt_graph_destroy", "gt_graph_outputs", "gt_graph_info",
-           "gt_graph_validate", "gt_aggregate_ws_size", "gt_aggregate_fwd", "gt_aggregate_bwd", "gt_combine_ws_size",
+           "gt_graph_validate", "gt_aggregate_ws_size", "gt_aggregate_fwd", "gt_aggregate_bwd",
+           "gt_aggregate_static_capacity", "gt_aggregate_fwd_static", "gt_combine_ws_size",
            "gt_combine", "gt_neighbor_apply_fwd", "gt_neighbor_apply_bwd", "gt_pull_fwd", "gt_pull_bwd", "gt_cost_get", "gt_cost_set", "gt_cost_get_dtype", "gt_cost_set_dtype", "gt_cost_benefits", "gt_layer_decide", "gt_layer_ws_size",
            "gt_layer_fwd", "gt_layer_bwd", "gt_calibrate_ws_size", "gt_calibrate", "gt_calibrate_dtype", "gt_trace_enable", "gt_trace_reset",
            "gt_trace_count", "gt_trace_get", "gt_sample_ws_size", "gt_sample_neighbors", "gt_reindex_ws_size",
@@ -71,6 +72,8 @@ lib.gt_aggregate_ws_size.argtypes = [c_void_p, c_int64, POINTER(c_size_t)]
 _AGG = [c_void_p, c_int, c_int, c_int64, c_void_p, c_int64, c_void_p, c_int64, c_void_p, c_size_t, c_void_p]
 lib.gt_aggregate_fwd.argtypes = _AGG
 lib.gt_aggregate_bwd.argtypes = _AGG
+lib.gt_aggregate_static_capacity.argtypes = [POINTER(c_size_t)]
+lib.gt_aggregate_fwd_static.argtypes = _AGG[:8] + [c_void_p]
 lib.gt_combine_ws_size.argtypes = [c_int, c_int, c_int, c_int64, c_int64, c_int64, POINTER(c_size_t)]
 lib.gt_combine.argtypes = [c_int, c_int, c_int, c_int64, c_int64, c_int64, c_void_p, c_int64, c_void_p, c_int64,
                            c_void_p, c_int, c_void_p, c_int64, c_int, c_void_p, c_size_t, c_void_p]
@@ -211,6 +214,14 @@ def gt_aggregate_fwd(g: Graph, reduce, X, out=None, F=None):
     _check(lib.gt_aggregate_fwd(g.handle, REDUCE[reduce], _dtype(X), F, _ptr(X), _rows2d(X), _ptr(Y), _rows2d(Y),
                                 _ptr(ws), ws.numel(), _stream()))
     return Y
+
+
+def gt_aggregate_fwd_static(g: Graph, reduce, X, out):
+    """gt_aggregate_fwd without a workspace argument (the library's built-in scratch); `out` must be
+    preallocated by the caller, this wrapper allocates nothing either."""
+    _check(lib.gt_aggregate_fwd_static(g.handle, REDUCE[reduce], _dtype(X), X.shape[1], _ptr(X), _rows2d(X), _ptr(out),
+                                       _rows2d(out), _stream()))
+    return out
 
 
 def gt_aggregate_bwd(g: Graph, reduce, dY, out=None, F=None):

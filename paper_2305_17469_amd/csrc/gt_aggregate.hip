@@ -16,7 +16,7 @@ size_t gt_aggregate_ws_bytes(const gt_graph *g, int64_t F) {
 
 gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce, gt_dtype in_dtype, gt_dtype out_dtype,
                            int64_t F, const void *X, int64_t ldx, void *Y, int64_t ldy, const float *bias, gt_act act,
-                           void *ws, size_t ws_bytes, hipStream_t st) {
+                           void *ws, size_t ws_bytes, hipStream_t st, bool traced) {
     const char *fn = transposed ? "gt_aggregate_bwd" : "gt_aggregate_fwd";
     if (!g) return gt_fail(GT_ERR_INVALID_ARG, "%s: g is null", fn);
     if (F < 0) return gt_fail(GT_ERR_INVALID_ARG, "%s: F < 0", fn);
@@ -61,7 +61,7 @@ gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce,
     a.partials = static_cast<float *>(ws); a.ldp = (F + 7) / 8 * 8;
     a.splits = sc.splits; a.n_splits = sc.n_splits;
     a.table_bytes = n_in * ldx * (int64_t)es;
-    a.trace_kind = transposed ? GT_TRACE_AGG_BWD : GT_TRACE_AGG_FWD;
+    a.trace_kind = !traced ? -1 : transposed ? GT_TRACE_AGG_BWD : GT_TRACE_AGG_FWD;
     a.n_rows = n_out; a.n_edges = g->n_edges;
 
     const int ve = in_dtype == GT_F32 ? 4 : 8;
@@ -110,4 +110,64 @@ extern "C" gt_status gt_aggregate_bwd(const gt_graph *g, gt_reduce reduce, gt_dt
                                       int64_t lddy, void *dX, int64_t lddx, void *ws, size_t ws_bytes, void *stream) {
     return gt_aggregate_run(g, true, reduce, dtype, dtype, F, dY, lddy, dX, lddx, nullptr, GT_ACT_NONE, ws, ws_bytes,
                             (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------------------------
+// gt_aggregate_fwd for callers that cannot allocate: the fp32 partial rows of the split long rows
+// live in a fixed array inside the library instead of a caller workspace.
+// ---------------------------------------------------------------------------------------------
+#include <mutex>
+
+#define GT_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+// No kernel names the array (they receive its address as an argument); the host-side reference in
+// static_scratch() below is what makes the compiler keep it and export its device symbol.  (Marking
+// it `used` as well leaves the device symbol with local binding, and the runtime's lookup fails.)
+static __device__ __align__(256) unsigned char scratch[GT_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int GT_MAX_DEVICES = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[GT_MAX_DEVICES] = {};   // device address of `scratch` on each device, looked up once
+
+// `scratch` names a host-side stand-in here; its device address is different on every GPU and
+// comes from hipGetSymbolAddress with that GPU current.
+gt_status static_scratch(void **ptr) {
+    int dev = -1;
+    GT_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= GT_MAX_DEVICES) return gt_fail(GT_ERR_UNSUPPORTED, "gt_aggregate_fwd_static: device index %d", dev);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        GT_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p & 255)) return gt_fail(GT_ERR_INTERNAL, "gt_aggregate_fwd_static: bad address of the static scratch");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return GT_OK;
+}
+}  // namespace
+
+extern "C" gt_status gt_aggregate_static_capacity(size_t *bytes) {
+    if (!bytes) return gt_fail(GT_ERR_INVALID_ARG, "gt_aggregate_static_capacity: null");
+    *bytes = GT_STATIC_SCRATCH_BYTES;
+    return GT_OK;
+}
+
+extern "C" gt_status gt_aggregate_fwd_static(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, int64_t F, const void *X,
+                                             int64_t ldx, void *Y, int64_t ldy, void *stream) {
+    if (!g) return gt_fail(GT_ERR_INVALID_ARG, "gt_aggregate_fwd_static: g is null");
+    if (F < 0) return gt_fail(GT_ERR_INVALID_ARG, "gt_aggregate_fwd_static: F < 0");
+    const size_t need = g->fwd.n_partials > 0 ? gt_aggregate_ws_bytes(g, F) : 0;
+    if (need > GT_STATIC_SCRATCH_BYTES)
+        return gt_fail(GT_ERR_WORKSPACE, "gt_aggregate_fwd_static: %zu bytes of partial rows exceed the built-in %zu; "
+                       "use gt_aggregate_fwd with a caller workspace", need, (size_t)GT_STATIC_SCRATCH_BYTES);
+    void *ws = nullptr;
+    if (need > 0) {
+        const gt_status s = static_scratch(&ws);
+        if (s != GT_OK) return s;
+    }
+    // every partial slot is written by its work item before the second kernel reads it: nothing in
+    // the array has to start at zero; kernel timing is off for this call (it would create events)
+    return gt_aggregate_run(g, false, reduce, dtype, dtype, F, X, ldx, Y, ldy, nullptr, GT_ACT_NONE, ws,
+                            GT_STATIC_SCRATCH_BYTES, (hipStream_t)stream, false);
 }

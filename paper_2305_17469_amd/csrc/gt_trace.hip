@@ -25,7 +25,7 @@ hipEvent_t take_event() {
 bool gt_trace_on() { return g_on; }
 
 int gt_trace_open(int kind, int64_t width, int64_t rows, int64_t work, hipStream_t st) {
-    if (!g_on) return -1;
+    if (!g_on || kind < 0) return -1;
     Rec r{take_event(), take_event(), kind, width, rows, work};
     if (!r.a || !r.b) return -1;
     if (hipEventRecord(r.a, st) != hipSuccess) return -1;
