@@ -1,12 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the GNN hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3]
 
 A step is one forward + backward pass of the whole model of the chosen workload through
 gt_layer_fwd / gt_layer_bwd (aggregation, combination, kernel placement and their derivatives),
 with all inputs resident in HBM.  The graph plan (degrees, transposed structure, work lists) is
 built once per graph before the timed region and its time is reported separately (`plan_ms`).
+Default workload: config 3 (R-MAT 2^21 vertices, 52 M edges, bf16 100-256-256-47), the largest
+single-GPU configuration and the one whose gathered tables exceed the last-level cache.
+`value` = edge*features the aggregation launches of one step actually executed / step time (the
+nominal, aggregation-first work of the same step is printed beside it).  K steps are timed with
+the per-kernel event timing off; K more steps follow with it on and give the per-kernel figures.
 Prints ONE JSON line.  Everything runs on one GPU; --gpus above 1 is refused.
 """
 from __future__ import annotations
@@ -44,10 +49,12 @@ def build_workload(name, scale):
     raise SystemExit("unknown --config %s" % name)
 
 
-def agg_algorithmic_bytes(E, n_out, F, s, reduce, transposed, has_ew):
-    """Gather-model bytes of one aggregation launch: every edge gathers one row of F elements,
-    every output row is written once, plus the index / coefficient streams."""
-    b = E * F * s + n_out * F * s + E * 4 + (n_out + 1) * 4
+def agg_algorithmic_bytes(E, n_out, F, s, reduce, transposed, has_ew, n_in=None):
+    """Bytes of one aggregation launch.  Gather model (n_in is None): every edge gathers one row of
+    F elements, every output row is written once, plus the index / coefficient streams: what the
+    kernel asks of the memory system when no source row is reused from a cache.  Compulsory floor
+    (n_in given): every source row read once instead."""
+    b = (E if n_in is None else n_in) * F * s + n_out * F * s + E * 4 + (n_out + 1) * 4
     if has_ew:
         b += E * 4
     if reduce == "symnorm" or (reduce == "mean" and transposed):
@@ -55,22 +62,142 @@ def agg_algorithmic_bytes(E, n_out, F, s, reduce, transposed, has_ew):
     return b
 
 
-def cpu_baseline(cfg, nominal_ef, budget_rows=1 << 18):
+KERNEL_SOURCES = ("gt_aggregate_kernel.h", "gt_aggregate.hip", "gt_plan.hip", "gt_internal.h", "gt_prims.h")
+
+
+def kernel_source_sha16():
+    """Hash of the sources the aggregation kernel and its work lists are built from: a stored
+    counter figure is only quoted for the code it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES:
+        h.update(open(os.path.join(ROOT, "paper_2305_17469_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
+def agg_kernel_name(dt, V, G, NP, U):
+    """The aggregation kernel instance as a profiler lists it."""
+    return "k_aggregate<%s, %d, %d, %d, %d, 0>" % ("unsigned short" if dt == "bf16" else "float", V, G, NP, U)
+
+
+def measure_traffic(args):
+    """HBM-side traffic of the aggregation kernels of one workload, from rocprofv3 counters.
+
+    Runs this script as child processes (this process never touches the GPU):
+      1. rocprofv3 --pmc FETCH_SIZE   -- python3 bench.py --config C --steps 3 --warmup 1 --copy-probe
+      2. rocprofv3 --pmc WRITE_SIZE   -- (same)
+      3. rocprofv3 --kernel-trace --stats -- python3 bench.py --config C            (durations, no counters)
+      4. python3 bench.py --config C                                                (durations from HIP events)
+    Counters are KiB per dispatch; each is scaled by what it reads for the 1 GiB device-to-device copy
+    of the same run (--copy-probe).  Writes gpurun_out/k_aggregate_<C>_traffic.txt (JSON, one entry per
+    kernel instance) and gpurun_out/<C>_kernel_stats.txt; copied to profiles/ they are what the default
+    run quotes as `roofline.traffic`."""
+    import collections
+    import csv
+    import glob
+    import subprocess
+    cfg = args.config
+    tag = cfg + ("" if (args.fwd_order, args.bwd_order) == ("auto", "auto") else "_%s_%s" % (args.fwd_order, args.bwd_order))
+    out_dir = os.path.join(ROOT, "gpurun_out")
+    os.makedirs(out_dir, exist_ok=True)
+    me = os.path.join(ROOT, "bench.py")
+    base = ["python3", me, "--config", cfg, "--no-cpu-baseline", "--fwd-order", args.fwd_order, "--bwd-order", args.bwd_order]
+    env = dict(os.environ, TMPDIR="/tmp")
+    cmds = []
+
+    def run(prefix, extra, log, limit):
+        cmd = ["timeout", "-s", "KILL", str(limit)] + prefix + base + extra
+        cmds.append(" ".join(prefix + ["python3", "bench.py"] + base[2:] + extra).replace(ROOT, "$REPO"))
+        print("[measure-traffic]", cmds[-1], flush=True)
+        with open(os.path.join(out_dir, log), "w") as f:
+            r = subprocess.run(cmd, cwd="/tmp", env=env, stdout=f, stderr=subprocess.STDOUT)
+        if r.returncode != 0:
+            raise SystemExit("measure-traffic: step failed (rc %d), see gpurun_out/%s" % (r.returncode, log))
+
+    def counters(ctr):
+        d = os.path.join(out_dir, "pmc_%s_%s" % (tag, ctr))
+        subprocess.run(["rm", "-rf", d])
+        run(["rocprofv3", "--pmc", ctr, "--output-format", "csv", "-d", d, "-o", "p", "--"],
+            ["--steps", "3", "--warmup", "1", "--copy-probe"], "pmc_%s_%s.log" % (tag, ctr), 400)
+        path = glob.glob(os.path.join(d, "**", "p_counter_collection.csv"), recursive=True)[0]
+        per = collections.defaultdict(list)
+        for r in csv.DictReader(open(path)):
+            if r["Counter_Name"] == ctr:
+                per[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+        return per
+
+    fetch, write = counters("FETCH_SIZE"), counters("WRITE_SIZE")
+    copy_f = max(fetch["__amd_rocclr_copyBuffer"])
+    copy_w = max(write["__amd_rocclr_copyBuffer"])
+    fs, ws = 1048576.0 / copy_f, 1048576.0 / copy_w            # 1 GiB copied = 1,048,576 KiB each way
+    d = os.path.join(out_dir, "prof_%s" % tag)
+    subprocess.run(["rm", "-rf", d])
+    run(["rocprofv3", "--kernel-trace", "--stats", "--output-format", "csv", "-d", d, "-o", "p", "--"],
+        ["--steps", "10", "--warmup", "3"], "prof_%s.log" % tag, 400)
+    stats = list(csv.DictReader(open(glob.glob(os.path.join(d, "**", "p_kernel_stats.csv"), recursive=True)[0])))
+    run([], ["--steps", str(args.steps), "--warmup", str(args.warmup)], "plain_%s.log" % tag, 400)
+    line = [l for l in open(os.path.join(out_dir, "plain_%s.log" % tag)) if l.startswith('{"metric')][-1]
+    plain = json.loads(line)
+    inst = {}
+    for name in fetch:
+        if "k_aggregate<" not in name:
+            continue
+        short = name.replace("(anonymous namespace)::", "").replace("void ", "").split("(")[0]
+        fv, wv = fetch[name], write.get(name, [0.0])
+        st = [r for r in stats if r["Name"] == name]
+        ev = [k for k in plain.get("aggregation_kernels", []) if k["kernel"] == short]
+        inst[short] = dict(dispatches=len(fv), fetch_kib_per_dispatch=sum(fv) / len(fv), write_kib_per_dispatch=sum(wv) / len(wv),
+                           hbm_bytes_per_launch=(sum(fv) / len(fv) * fs + sum(wv) / len(wv) * ws) * 1024.0,
+                           avg_us_rocprof_kernel_trace=float(st[0]["AverageNs"]) / 1e3 if st else None,
+                           avg_ms_hip_events=ev[0]["avg_ms"] if ev else None)
+    res = dict(workload=plain["config"]["workload"], orders_fwd=plain["config"]["orders_fwd"], orders_bwd=plain["config"]["orders_bwd"],
+               source_sha16=kernel_source_sha16(), instances=inst,
+               copy_probe=dict(bytes_each_way=1 << 30, fetch_kib=copy_f, write_kib=copy_w, fetch_scale=fs, write_scale=ws),
+               note="counted at the L2 <-> fabric boundary (TCC_EA read / write requests): bytes served by the 256 MB "
+                    "Infinity Cache are included, so this is an upper bound of the HBM traffic.  Per launch = mean over "
+                    "all dispatches of the kernel instance in the counter runs.",
+               commands=["cd /tmp && TMPDIR=/tmp " + c for c in cmds])
+    tpath = os.path.join(out_dir, "k_aggregate_%s_traffic.txt" % tag)
+    json.dump(res, open(tpath, "w"), indent=1)
+    with open(os.path.join(out_dir, "%s_kernel_stats.txt" % tag), "w") as f:
+        f.write("rocprofv3 kernel-trace summary (made by: python3 bench.py --config %s --measure-traffic%s)\n" % (
+            cfg, "" if tag == cfg else " --fwd-order %s --bwd-order %s" % (args.fwd_order, args.bwd_order)))
+        f.write("command: cd /tmp && TMPDIR=/tmp %s\n" % cmds[2])
+        f.write("bench line of the plain run that followed: ms_per_step %.4f, value %.4e %s, roofline kernel '%s' avg_launch_ms %.4f\n\n" % (
+            plain["ms_per_step"], plain["value"], plain["unit"], plain["roofline"]["kernel"], plain["roofline"]["avg_launch_ms"]))
+        f.write("%-100s %6s %12s %12s %7s\n" % ("kernel", "calls", "avg_us", "total_ms", "pct"))
+        for r in stats[:24]:
+            f.write("%-100s %6s %12.1f %12.3f %7s\n" % (r["Name"].replace("(anonymous namespace)::", "")[:98], r["Calls"],
+                                                         float(r["AverageNs"]) / 1e3, float(r["TotalDurationNs"]) / 1e6, r["Percentage"][:6]))
+    print(json.dumps(res))
+
+
+
+
+def cpu_baseline(cfg, job_ef, mac_budget=1.5e11):
     """The oracle, as it stands, timed on a bounded sample: every kernel of the definitional
     (aggregation-first) fwd+bwd step runs on a strided sample of its rows and its time is scaled
-    by the ratio of full to sampled work."""
+    by the ratio of full to sampled work.  The sample is sized to about `mac_budget`
+    multiply-adds (10-30 s on a 16-thread host); `job_ef` is the numerator of the GPU's `value`,
+    so that the two figures are the same job over two times."""
     import numpy as np
     import oracle
     L = len(cfg["W"])
     est = 0.0
     t_cpu = 0.0
     rng = np.random.default_rng(0)
+    full_macs = 0.0
+    for l in range(L):
+        nd, E = cfg["blocks"][l]["n_dst"], cfg["blocks"][l]["colidx"].size
+        fi, fo = cfg["dims"][l], cfg["dims"][l + 1]
+        full_macs += E * fi * (2 if l > 0 else 1) + nd * fi * fo * (3 if l > 0 else 2)
+    frac = min(1.0, mac_budget / max(full_macs, 1.0))
     for l in range(L):
         blk = cfg["blocks"][l]
         rp, ci, ns, nd = blk["rowptr"], blk["colidx"], blk["n_src"], blk["n_dst"]
         fi, fo = cfg["dims"][l], cfg["dims"][l + 1]
         E = ci.size
-        stride = max(1, nd // budget_rows)
+        stride = max(1, int(round(1.0 / frac)))
         rows = np.arange(0, nd, stride, dtype=np.int64)
         Es = int((rp[rows + 1] - rp[rows]).sum())
         Xl = cfg["X"] if l == 0 else rng.standard_normal((ns, fi)).astype(np.float32)
@@ -104,10 +231,11 @@ def cpu_baseline(cfg, nominal_ef, budget_rows=1 << 18):
             oracle.aggregate_bwd(sub_rp.astype(np.int32), sub_ci, ns, dM, "sum")
             t = time.perf_counter() - t0
             est += t * E / max(Es, 1); t_cpu += t
-    return dict(value=nominal_ef / est, unit="edge*feature/s", cores=oracle.num_threads(), kind="oracle",
-                sample="every kernel of the aggregation-first fwd+bwd step on a strided sample of about %d "
-                       "destination rows per layer (%.1f s of CPU time), scaled to the full row / edge counts; "
-                       "backward scatter on the sampled rows' sub-CSR with sum coefficients" % (budget_rows, t_cpu),
+    return dict(value=job_ef / est, unit="edge*feature/s", cores=oracle.num_threads(), kind="oracle",
+                sample="every kernel of the aggregation-first fwd+bwd step on every %d-th destination row of each "
+                       "layer (%.1f s of CPU time), scaled to the full row / edge counts; backward scatter on the "
+                       "sampled rows' sub-CSR with sum coefficients; value = the GPU step's executed edge*features "
+                       "over the estimated CPU step time" % (max(1, int(round(1.0 / frac))), t_cpu),
                 est_step_seconds=est)
 
 
@@ -318,7 +446,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c2")
+    ap.add_argument("--config", default="c3")
     ap.add_argument("--scale", type=int, default=0, help="override the vertex-count exponent (testing)")
     ap.add_argument("--fwd-order", default="auto")
     ap.add_argument("--bwd-order", default="auto")
@@ -341,10 +469,16 @@ def main():
                     help="aggregation alone on graphs with uniform degrees and uniform sources (no cache reuse)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (reference point for HBM byte counters)")
+    ap.add_argument("--measure-traffic", action="store_true",
+                    help="run this benchmark under rocprofv3 (byte counters, then kernel trace) in child processes "
+                         "and write the per-kernel traffic / duration summaries to gpurun_out/")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
                          "run with --gpus 1")
+
+    if args.measure_traffic:
+        return measure_traffic(args)
 
     import numpy as np
     import torch
@@ -501,18 +635,12 @@ def main():
     for _ in range(args.warmup):
         model.step(X, G, args.fwd_order, args.bwd_order)
     torch.cuda.synchronize()
-    B.gt_trace_reset()
-    B.gt_trace_enable(True)
     graph = None
     if args.graph:
-        # eager traced pass for the per-kernel figures, then capture one step and time replays
-        for _ in range(args.steps):
-            model.step(X, G, args.fwd_order, args.bwd_order)
-        torch.cuda.synchronize()
-        B.gt_trace_enable(False)
         graph = model.capture(X, G, args.fwd_order, args.bwd_order)
         for _ in range(args.warmup):
             graph.replay()
+    # ---- the timed region: exactly K steps, kernel timing off
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -522,18 +650,28 @@ def main():
             model.step(X, G, args.fwd_order, args.bwd_order)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    # ---- K more (eager) steps with every aggregation / combination launch bracketed by HIP events on
+    # its own stream: the per-kernel view of the same step
+    B.gt_trace_reset()
+    B.gt_trace_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        model.step(X, G, args.fwd_order, args.bwd_order)
+    torch.cuda.synchronize()
+    ms_per_step_traced = (time.perf_counter() - t0) * 1e3 / args.steps
     B.gt_trace_enable(False)
     recs = B.gt_trace_records()
+    variants = B.gt_trace_variants()
     B.gt_trace_reset()
-    ms_per_step = elapsed * 1e3 / args.steps
 
     L = len(cfg["W"])
     E_l = [b["colidx"].numel() for b in blocks]
     nominal_ef = sum(E_l[l] * cfg["dims"][l] * (2 if l > 0 else 1) for l in range(L))
     executed_ef = sum(r[3] * r[1] for r in recs if r[0] in (0, 1)) / args.steps
-    value = nominal_ef / (ms_per_step * 1e-3)
+    value = executed_ef / (ms_per_step * 1e-3)
 
-    # per-kernel view of the timed region (HIP events on the launch stream, recorded by the library)
     groups = {}
     for kind, width, rows, work, ms in recs:
         key = (("agg_fwd", "agg_bwd", "combine")[kind], width, rows, work)
@@ -541,45 +679,86 @@ def main():
         g[0] += 1
         g[1] += ms
     kernels = [dict(kernel=k[0], width=k[1], rows=k[2], work=k[3], launches=v[0], avg_ms=v[1] / v[0],
-                    share=v[1] / (ms_per_step * args.steps)) for k, v in sorted(groups.items(), key=lambda kv: -kv[1][1])]
-    # dominant kernel: the aggregation gather kernel instance (same width => same template
-    # instance and kernel name) with the largest total time
-    by_width = {}
-    for kind, width, rows, work, ms in recs:
-        if kind in (0, 1):
-            w = by_width.setdefault(width, dict(n=0, ms=0.0, bytes=0.0))
-            w["n"] += 1
-            w["ms"] += ms
-            w["bytes"] += agg_algorithmic_bytes(work, rows, width, s, cfg["reduce"], kind == 1, False)
+                    share=v[1] / (ms_per_step_traced * args.steps)) for k, v in sorted(groups.items(), key=lambda kv: -kv[1][1])]
+    # aggregation launches by kernel INSTANCE (template arguments = the name a profiler lists), with the
+    # gather-model and compulsory bytes of every launch
+    inst = {}
+    n_in_of = {0: lambda b: b["n_src"], 1: lambda b: b["n_dst"]}
+    blk_by_rows = {}
+    for b in blocks:
+        blk_by_rows[(0, b["n_dst"], b["colidx"].numel())] = b
+        blk_by_rows[(1, b["n_src"], b["colidx"].numel())] = b
+    for (kind, width, rows, work, ms), (V, G_, NP, U) in zip(recs, variants):
+        if kind not in (0, 1):
+            continue
+        name = agg_kernel_name(dt, V, G_, NP, U)
+        blk = blk_by_rows[(kind, rows, work)]
+        w = inst.setdefault(name, dict(n=0, ms=0.0, gather=0.0, floor=0.0, ef=0.0, widths=set(), slice=0.0))
+        w["slice"] = max(w["slice"], n_in_of[kind](blk) * width * s / 1e6)
+        w["n"] += 1
+        w["ms"] += ms
+        w["gather"] += agg_algorithmic_bytes(work, rows, width, s, cfg["reduce"], kind == 1, False)
+        w["floor"] += agg_algorithmic_bytes(work, rows, width, s, cfg["reduce"], kind == 1, False, n_in=n_in_of[kind](blk))
+        w["ef"] += work * width
+        w["widths"].add(width)
+    agg_kernels = [dict(kernel=k, launches=v["n"], avg_ms=v["ms"] / v["n"], widths=sorted(v["widths"]), gathered_slice_mb=v["slice"],
+                        gather_model_bytes_per_launch=v["gather"] / v["n"], compulsory_bytes_per_launch=v["floor"] / v["n"],
+                        gather_model_gbs=v["gather"] / v["ms"] / 1e6, edge_features_per_s=v["ef"] / v["ms"] * 1e3)
+                   for k, v in sorted(inst.items(), key=lambda kv: -kv[1]["ms"])]
     roofline = None
-    if by_width:
-        wdom, d = max(by_width.items(), key=lambda kv: kv[1]["ms"])
-        avg_ms = d["ms"] / d["n"]
-        achieved = d["bytes"] / d["n"] / (avg_ms * 1e-3) / 1e9
-        traffic = None
-        # byte counters cannot be read from inside the run: the figure measured with rocprofv3 --pmc
-        # for this workload and kernel width is kept beside the other profile summaries
-        tpath = os.path.join(ROOT, "profiles", "k_aggregate_%s_traffic.txt" % args.config)
+    if agg_kernels:
+        dom = agg_kernels[0]                      # the aggregation kernel instance with the largest total time
+        avg_ms = dom["avg_ms"]
+        # HBM-side bytes of that instance on this workload, measured with rocprofv3 byte counters by
+        # `bench.py --config C --measure-traffic` and kept under profiles/.  Counters cannot be read
+        # from inside the run, so the stored figure is quoted only if it was taken on the same kernel
+        # sources and the launch duration measured now is within 10 % of the one measured then.
+        tag = args.config + ("" if (args.fwd_order, args.bwd_order) == ("auto", "auto") else "_%s_%s" % (args.fwd_order, args.bwd_order))
+        tpath = os.path.join(ROOT, "profiles", "k_aggregate_%s_traffic.txt" % tag)
+        traffic, why = None, "no counter summary for this workload under profiles/"
         if os.path.exists(tpath):
             tj = json.load(open(tpath))
-            if ("width %d)" % wdom) in tj.get("kernel", ""):
-                traffic = tj.get("hbm_bytes_per_launch")
+            e = tj.get("instances", {}).get(dom["kernel"])
+            if e is None:
+                why = "the counter summary has no entry for this kernel instance"
+            elif tj.get("source_sha16") != kernel_source_sha16():
+                why = "the kernel sources changed since the counters were read"
+            elif not e.get("avg_ms_hip_events") or abs(avg_ms / e["avg_ms_hip_events"] - 1.0) > 0.10:
+                why = "launch duration now %.4f ms, at the counter run %.4f ms: more than 10 %% apart" % (
+                    avg_ms, e.get("avg_ms_hip_events") or 0.0)
+            else:
+                traffic, why = e["hbm_bytes_per_launch"], "profiles/" + os.path.basename(tpath)
+        gather_gbs = dom["gather_model_bytes_per_launch"] / (avg_ms * 1e-3) / 1e9
+        floor_gbs = dom["compulsory_bytes_per_launch"] / (avg_ms * 1e-3) / 1e9
+        table_mb = dom["gathered_slice_mb"]        # what one launch gathers from (a column pass reads a slice of the table)
+        # `achieved`: bytes that crossed the L2 <-> memory-fabric boundary per launch (counters) over the
+        # launch duration (HIP events, this run) when the stored counters apply; else the compulsory bytes
+        # over the duration.  Neither can exceed the HBM peak.  The gather-model rate is printed beside
+        # it: it may exceed the peak where gathered rows are served from L2 / Infinity Cache.
+        basis = "counter bytes (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy)" if traffic else "compulsory bytes"
+        achieved = (traffic / (avg_ms * 1e-3) / 1e9) if traffic else floor_gbs
         roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s", frac=achieved / HBM_PEAK_GBS,
-                        traffic=traffic, kernel="k_aggregate (gather-reduce), width %d" % wdom,
-                        avg_launch_ms=avg_ms, launches=d["n"], algorithmic_bytes_per_launch=d["bytes"] / d["n"])
+                        traffic=traffic, basis=basis, traffic_source=why, kernel=dom["kernel"], widths=dom["widths"],
+                        avg_launch_ms=avg_ms, launches=dom["launches"],
+                        algorithmic_bytes_per_launch=dom["gather_model_bytes_per_launch"],
+                        gather_model_gbs=gather_gbs, gather_model_frac=gather_gbs / HBM_PEAK_GBS,
+                        compulsory_bytes_per_launch=dom["compulsory_bytes_per_launch"], compulsory_frac=floor_gbs / HBM_PEAK_GBS,
+                        regime="gathered table slice %.0f MB vs 256 MB last-level cache: %s" % (
+                            table_mb, "HBM bound (hub rows still hit in L2)" if table_mb > 256 else "cache resident: HBM is not the binding roofline"))
 
     out = dict(metric="GNN layer fwd+bwd edge*features/s", value=value, unit="edge*feature/s", n_gpus=1,
                steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f32" if dt == "f32" else "bf16", data="synthetic",
                config=dict(workload=cfg["name"], n_nodes=[b["n_src"] for b in blocks][0], n_edges=E_l[0],
-                           dims=cfg["dims"], model=None, reduce=cfg["reduce"], layers=L,
+                           dims=cfg["dims"], reduce=cfg["reduce"], layers=L,
+                           storage=dt, accumulate="f32",
                            orders_fwd=model.used_fwd, orders_bwd=model.used_bwd,
-                           nominal_edge_features_per_step=nominal_ef, executed_edge_features_per_step=executed_ef,
+                           executed_edge_features_per_step=executed_ef, nominal_edge_features_per_step=nominal_ef,
+                           nominal_value=nominal_ef / (ms_per_step * 1e-3), ms_per_step_with_kernel_timing=ms_per_step_traced,
                            plan_ms=plan_ms, input_generation_s=gen_s, hip_graph=bool(args.graph)),
-               roofline=roofline, kernels=kernels[:8])
-    del out["config"]["model"]
+               roofline=roofline, aggregation_kernels=agg_kernels, kernels=kernels[:8])
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, nominal_ef)
+        out["cpu_baseline"] = cpu_baseline(cfg, executed_ef)
     print(json.dumps(out))
 
 

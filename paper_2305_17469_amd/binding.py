@@ -52,7 +52,7 @@ EXPORTS = ["gt_graph_plan_size", "gt_graph_create", "gt_graph_destroy", "gt_grap
            "gt_aggregate_static_capacity", "gt_aggregate_fwd_static", "gt_combine_ws_size",
            "gt_combine", "gt_neighbor_apply_fwd", "gt_neighbor_apply_bwd", "gt_pull_fwd", "gt_pull_bwd", "gt_cost_get", "gt_cost_set", "gt_cost_get_dtype", "gt_cost_set_dtype", "gt_cost_benefits", "gt_layer_decide", "gt_layer_ws_size",
            "gt_layer_fwd", "gt_layer_bwd", "gt_calibrate_ws_size", "gt_calibrate", "gt_calibrate_dtype", "gt_trace_enable", "gt_trace_reset",
-           "gt_trace_count", "gt_trace_get", "gt_sample_ws_size", "gt_sample_neighbors", "gt_reindex_ws_size",
+           "gt_trace_count", "gt_trace_get", "gt_trace_get_variant", "gt_sample_ws_size", "gt_sample_neighbors", "gt_reindex_ws_size",
            "gt_reindex", "gt_lookup", "gt_status_string",
            "gt_last_error", "gt_version"]
 
@@ -103,6 +103,7 @@ lib.gt_trace_reset.argtypes = []
 lib.gt_trace_count.argtypes = [POINTER(c_int64)]
 lib.gt_trace_get.argtypes = [c_int64, POINTER(c_int), POINTER(c_int64), POINTER(c_int64), POINTER(c_int64),
                              POINTER(c_double)]
+lib.gt_trace_get_variant.argtypes = [c_int64] + [POINTER(c_int)] * 4
 lib.gt_calibrate_ws_size.argtypes = [POINTER(c_size_t)]
 lib.gt_calibrate.argtypes = [c_void_p, c_size_t, POINTER(gt_cost_coeffs), c_void_p]
 lib.gt_calibrate_dtype.argtypes = [c_int, c_void_p, c_size_t, POINTER(gt_cost_coeffs), c_void_p]
@@ -434,6 +435,18 @@ def gt_trace_records():
         k, w, r, wk, ms = c_int(), c_int64(), c_int64(), c_int64(), c_double()
         _check(lib.gt_trace_get(i, byref(k), byref(w), byref(r), byref(wk), byref(ms)))
         out.append((k.value, w.value, r.value, wk.value, ms.value))
+    return out
+
+
+def gt_trace_variants():
+    """[(V, G, NP, U)] of every record: the aggregation kernel's template arguments (zeros for a combination)."""
+    n = c_int64()
+    _check(lib.gt_trace_count(byref(n)))
+    out = []
+    for i in range(n.value):
+        v = [c_int() for _ in range(4)]
+        _check(lib.gt_trace_get_variant(i, *[byref(x) for x in v]))
+        out.append(tuple(x.value for x in v))
     return out
 
 

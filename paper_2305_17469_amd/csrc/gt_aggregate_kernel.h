@@ -401,6 +401,7 @@ gt_status launch(const AggArgs &a, hipStream_t st) {
         AggArgs b = a;
         b.xcd_run = agg_xcd_run(gx);
         const int tr = gt_trace_open(a.trace_kind, a.F, a.n_rows, a.n_edges, st);
+        gt_trace_variant(tr, V, G, NP, U);
         k_aggregate<T, V, G, NP, U, VWM><<<dim3((unsigned)gx, gy), 256, 0, st>>>(b);
         gt_trace_close(tr, st);
         GT_LAUNCH_CHECK("k_aggregate");

@@ -9,7 +9,7 @@
 #include "gt_trace.h"
 
 namespace {
-struct Rec { hipEvent_t a, b; int kind; int64_t width, rows, work; };
+struct Rec { hipEvent_t a, b; int kind; int64_t width, rows, work; int V = 0, G = 0, NP = 0, U = 0; };
 std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 bool g_on = false;
@@ -26,11 +26,17 @@ bool gt_trace_on() { return g_on; }
 
 int gt_trace_open(int kind, int64_t width, int64_t rows, int64_t work, hipStream_t st) {
     if (!g_on || kind < 0) return -1;
-    Rec r{take_event(), take_event(), kind, width, rows, work};
+    Rec r{};
+    r.a = take_event(); r.b = take_event(); r.kind = kind; r.width = width; r.rows = rows; r.work = work;
     if (!r.a || !r.b) return -1;
     if (hipEventRecord(r.a, st) != hipSuccess) return -1;
     g_recs.push_back(r);
     return (int)g_recs.size() - 1;
+}
+
+void gt_trace_variant(int id, int V, int G, int NP, int U) {
+    if (id < 0 || id >= (int)g_recs.size()) return;
+    g_recs[id].V = V; g_recs[id].G = G; g_recs[id].NP = NP; g_recs[id].U = U;
 }
 
 void gt_trace_close(int id, hipStream_t st) {
@@ -68,5 +74,15 @@ extern "C" gt_status gt_trace_get(int64_t i, int *kind, int64_t *width, int64_t 
         GT_HIP(hipEventElapsedTime(&t, r.a, r.b));
         *ms = (double)t;
     }
+    return GT_OK;
+}
+
+extern "C" gt_status gt_trace_get_variant(int64_t i, int *V, int *G, int *NP, int *U) {
+    if (i < 0 || i >= (int64_t)g_recs.size()) return gt_fail(GT_ERR_INVALID_ARG, "gt_trace_get_variant: index out of range");
+    const Rec &r = g_recs[(size_t)i];
+    if (V) *V = r.V;
+    if (G) *G = r.G;
+    if (NP) *NP = r.NP;
+    if (U) *U = r.U;
     return GT_OK;
 }
