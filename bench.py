@@ -459,6 +459,12 @@ def main():
     ap.add_argument("--edge-bench", type=int, default=0, metavar="F",
                     help="time the edge-weighting primitives (NeighborApply mul/dot, Pull add/scale, fwd+bwd) at "
                          "width F on the workload's first graph instead of the model step")
+    ap.add_argument("--agg-bench", default="", metavar="F[,F...]",
+                    help="time gt_aggregate_fwd / gt_aggregate_bwd alone at the given widths on the workload's first "
+                         "graph, in the workload's data type and reduce mode, instead of the model step")
+    ap.add_argument("--fused-bench", default="", metavar="IN:OUT[,IN:OUT...]",
+                    help="forward-only aggregation-first layer act((A X) W + b) on the workload's first graph: the "
+                         "fused kernel (gt_aggregate_combine_fwd) against gt_aggregate_fwd followed by gt_combine")
     ap.add_argument("--feed-bench", action="store_true",
                     help="time batch preparation on the GPU (sampling, renumbering, lookup, plan) and training of "
                          "300-seed batches, on one stream and with preparation overlapped on a second stream")
@@ -530,6 +536,71 @@ def main():
     torch.cuda.synchronize()
     plan_ms = (time.perf_counter() - t0) * 1e3      # plan build (+ buffer allocation), once per graph
 
+    if args.agg_bench:
+        g = model.graphs[0]
+        tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+        rows = []
+        for spec in args.agg_bench.split(","):      # F or F:ld (row stride in elements)
+            F = int(spec.split(":")[0])
+            v = 8 if dt == "bf16" else 4
+            ld = int(spec.split(":")[1]) if ":" in spec else (F + v - 1) // v * v
+            Xa = torch.randn((g.n_src, ld), device=dev).to(tdt)[:, :F]
+            Ya = torch.empty((g.n_dst, ld), dtype=tdt, device=dev)[:, :F]
+            for name, fn, n_out in (("fwd", B.gt_aggregate_fwd, g.n_dst), ("bwd", B.gt_aggregate_bwd, g.n_src)):
+                if g.n_src != g.n_dst and name == "bwd":
+                    continue
+                for _ in range(max(2, args.warmup)):
+                    fn(g, cfg["reduce"], Xa, out=Ya)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(args.steps):
+                    fn(g, cfg["reduce"], Xa, out=Ya)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / args.steps
+                nb = agg_algorithmic_bytes(g.n_edges, n_out, F, s, cfg["reduce"], name == "bwd", False)
+                rows.append(dict(dir=name, F=F, ld=ld, ms=ms, gather_model_gb=nb / 1e9, gather_model_tbs=nb / ms / 1e9,
+                                 edge_features_per_s=g.n_edges * F / ms * 1e3))
+        print(json.dumps(dict(metric="aggregation alone", workload=cfg["name"], dtype=dt, reduce=cfg["reduce"],
+                              n_edges=g.n_edges, n_rows=g.n_dst, rows=rows)))
+        return
+    if args.fused_bench:
+        g = model.graphs[0]
+        tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+        v = 8 if dt == "bf16" else 4
+        rows = []
+
+        def t_ms(fn):
+            for _ in range(max(2, args.warmup)):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps
+        for spec in args.fused_bench.split(","):
+            fi, fo = [int(x) for x in spec.split(":")]
+            ldi, ldo = (fi + v - 1) // v * v, (fo + v - 1) // v * v
+            Xa = torch.randn((g.n_src, ldi), device=dev).to(tdt)[:, :fi]
+            Wa = (torch.randn((fi, fo), device=dev) * 0.05).to(tdt)
+            ba = torch.randn((fo,), device=dev) * 0.1
+            Ma = torch.empty((g.n_dst, ldi), dtype=tdt, device=dev)[:, :fi]
+            Ya = torch.empty((g.n_dst, ldo), dtype=tdt, device=dev)[:, :fo]
+            Yb = torch.empty((g.n_dst, ldo), dtype=tdt, device=dev)[:, :fo]
+            ok = B.gt_aggregate_combine_supported(dt, fi, fo)
+            ms_agg = t_ms(lambda: B.gt_aggregate_fwd(g, cfg["reduce"], Xa, out=Ma))
+            ms_two = t_ms(lambda: (B.gt_aggregate_fwd(g, cfg["reduce"], Xa, out=Ma), B.gt_combine(Ma, Wa, ba, True, out=Ya)))
+            ms_fused = t_ms(lambda: B.gt_aggregate_combine_fwd(g, cfg["reduce"], Xa, Wa, ba, True, out=Yb)) if ok else None
+            diff = float((Ya.float() - Yb.float()).abs().max() / Ya.float().abs().max()) if ok else None
+            rows.append(dict(in_dim=fi, out_dim=fo, supported=ok, ms_aggregate=ms_agg, ms_two_kernels=ms_two, ms_fused=ms_fused,
+                             max_rel_diff=diff))
+        print(json.dumps(dict(metric="fused aggregation + combination, forward only", workload=cfg["name"], dtype=dt,
+                              reduce=cfg["reduce"], n_edges=g.n_edges, n_dst=g.n_dst, n_src=g.n_src, rows=rows)))
+        return
     if args.edge_bench:
         F = args.edge_bench
         g = model.graphs[0]

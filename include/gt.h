@@ -149,6 +149,21 @@ gt_status gt_aggregate_static_capacity(size_t *bytes /* host */);
 gt_status gt_aggregate_fwd_static(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, int64_t F,
                                   const void *X, int64_t ldx, void *Y, int64_t ldy, void *stream);
 
+/* Fused aggregation-first forward for inference,  Y[n_dst, out_dim] = act( (A X) W + b ):  the
+ * aggregated row of a destination stays on chip (paper: Frontend section, Pull accumulates a
+ * destination's row on chip and writes it once) and is handed straight to the combination's
+ * matrix instructions (Apply); A X is never written to memory, so no backward call can follow.
+ * X[n_src, in_dim] (ldx; rows 16-byte aligned: otherwise GT_ERR_UNSUPPORTED), W[in_dim, out_dim]
+ * dense (row stride out_dim), b[out_dim] fp32 or NULL, all data in `dtype`.  Shapes: in_dim <= 256
+ * (bf16) / 128 (fp32), out_dim <= 256, and weights plus row tiles within the 160 KB of LDS
+ * (gt_aggregate_combine_supported tells; GT_ERR_UNSUPPORTED otherwise).  ws as for gt_aggregate_fwd
+ * at width in_dim (partial rows of split long rows).  Same results as gt_aggregate_fwd followed by
+ * gt_combine up to the summation order inside the matrix instructions. */
+gt_status gt_aggregate_combine_supported(gt_dtype dtype, int64_t in_dim, int64_t out_dim, int *yes /* host */);
+gt_status gt_aggregate_combine_fwd(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, int64_t in_dim,
+                                   int64_t out_dim, const void *X, int64_t ldx, const void *W, const float *b,
+                                   gt_act act, void *Y, int64_t ldy, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------------------------------
  * Edge weighting: NeighborApply (the edge-weight function g of the source and destination
  * embeddings per edge, i.e. SDDMM) and Pull with per-call edge weights (the function h that
@@ -221,6 +236,16 @@ typedef struct {
     int64_t in_dim, out_dim;
     int has_root;
     int need_dx;
+    /* The activation's derivative folded into the kernel that produces the gradient (both 0 = off;
+     * they matter to gt_layer_bwd only).  The input X of a layer is the output of the layer below;
+     * if that output went through a ReLU, dL/d(its pre-activation) = dX (.) [X > 0].
+     *   in_act = GT_ACT_RELU: gt_layer_bwd writes dX already multiplied by [X > 0], as the rows are
+     *            stored (no extra pass over dX).
+     *   dy_is_dz != 0: the dY handed to gt_layer_bwd already carries this layer's own activation
+     *            derivative (the layer above produced it with in_act set), so it is used as dZ as it
+     *            is; Y is not read then and may be NULL. */
+    gt_act in_act;
+    int dy_is_dz;
 } gt_layer_desc;
 
 /* Coefficients of the kernel-time model behind the placement decision (paper: "DKP cost model
@@ -268,8 +293,10 @@ gt_status gt_layer_ws_size(const gt_graph *g, const gt_layer_desc *d,
  * order or GT_AUTO; *used (host, may be NULL) receives the order that ran.
  * saved / scratch: device, 256-byte aligned, at least the sizes gt_layer_ws_size reports
  * (saved_bytes / scratch_bytes are the callers' buffer sizes; GT_ERR_WORKSPACE when too small,
- * before anything is launched).  `saved` is written only by an aggregation-first forward and
- * may be NULL (saved_bytes 0) when GT_COMB_FIRST is forced.  X and Y must not overlap
+ * before anything is launched).  `saved` is written only by an aggregation-first forward.
+ * saved == NULL (saved_bytes 0) makes the call forward-only (inference): no gt_layer_bwd may
+ * follow; A X is then a temporary in `scratch`, or is never written at all where the fused kernel
+ * of gt_aggregate_combine_fwd applies and is the faster path.  X and Y must not overlap
  * (GT_ERR_INVALID_ARG). */
 gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_order req,
                        const void *X, int64_t ldx, const void *W, const void *W_root, const float *b,
@@ -358,7 +385,8 @@ gt_status gt_lookup(gt_dtype dtype, const void *table, int64_t n_rows, int64_t l
  * gives the same quantity from inside a timed region).  While enabled, every aggregation
  * gather kernel and every combination kernel launched by this library is bracketed by two HIP
  * events on its own stream.  Host-side state, not thread-safe; off by default.
- *   kind: 0 aggregation (given CSR), 1 aggregation (transposed), 2 combination
+ *   kind: 0 aggregation (given CSR), 1 aggregation (transposed), 2 combination, 3 fused
+ *   aggregation + combination (width = in_dim)
  *   width: feature width F (aggregation) or N (combination); rows: output rows;
  *   work: edges gathered (aggregation) or M*N*K (combination); ms: kernel duration.
  * gt_trace_get synchronises on the record's end event.

@@ -33,7 +33,7 @@ STATUS_NAME = {0: "GT_OK", 1: "GT_ERR_INVALID_ARG", 2: "GT_ERR_UNSUPPORTED", 3: 
 
 class gt_layer_desc(ctypes.Structure):
     _fields_ = [("reduce", c_int), ("dtype", c_int), ("act", c_int), ("in_dim", c_int64), ("out_dim", c_int64),
-                ("has_root", c_int), ("need_dx", c_int)]
+                ("has_root", c_int), ("need_dx", c_int), ("in_act", c_int), ("dy_is_dz", c_int)]
 
 
 class gt_cost_coeffs(ctypes.Structure):
@@ -49,7 +49,8 @@ class GtError(RuntimeError):
 
 EXPORTS = ["gt_graph_plan_size", "gt_graph_create", "gt_graph_destroy", "gt_graph_outputs", "gt_graph_info",
            "gt_graph_validate", "gt_aggregate_ws_size", "gt_aggregate_fwd", "gt_aggregate_bwd",
-           "gt_aggregate_static_capacity", "gt_aggregate_fwd_static", "gt_combine_ws_size",
+           "gt_aggregate_static_capacity", "gt_aggregate_fwd_static", "gt_aggregate_combine_supported",
+           "gt_aggregate_combine_fwd", "gt_combine_ws_size",
            "gt_combine", "gt_neighbor_apply_fwd", "gt_neighbor_apply_bwd", "gt_pull_fwd", "gt_pull_bwd", "gt_cost_get", "gt_cost_set", "gt_cost_get_dtype", "gt_cost_set_dtype", "gt_cost_benefits", "gt_layer_decide", "gt_layer_ws_size",
            "gt_layer_fwd", "gt_layer_bwd", "gt_calibrate_ws_size", "gt_calibrate", "gt_calibrate_dtype", "gt_trace_enable", "gt_trace_reset",
            "gt_trace_count", "gt_trace_get", "gt_trace_get_variant", "gt_sample_ws_size", "gt_sample_neighbors", "gt_reindex_ws_size",
@@ -74,6 +75,9 @@ lib.gt_aggregate_fwd.argtypes = _AGG
 lib.gt_aggregate_bwd.argtypes = _AGG
 lib.gt_aggregate_static_capacity.argtypes = [POINTER(c_size_t)]
 lib.gt_aggregate_fwd_static.argtypes = _AGG[:8] + [c_void_p]
+lib.gt_aggregate_combine_supported.argtypes = [c_int, c_int64, c_int64, POINTER(c_int)]
+lib.gt_aggregate_combine_fwd.argtypes = [c_void_p, c_int, c_int, c_int64, c_int64, c_void_p, c_int64, c_void_p, c_void_p, c_int,
+                                         c_void_p, c_int64, c_void_p, c_size_t, c_void_p]
 lib.gt_combine_ws_size.argtypes = [c_int, c_int, c_int, c_int64, c_int64, c_int64, POINTER(c_size_t)]
 lib.gt_combine.argtypes = [c_int, c_int, c_int, c_int64, c_int64, c_int64, c_void_p, c_int64, c_void_p, c_int64,
                            c_void_p, c_int, c_void_p, c_int64, c_int, c_void_p, c_size_t, c_void_p]
@@ -225,6 +229,24 @@ def gt_aggregate_fwd_static(g: Graph, reduce, X, out):
     return out
 
 
+def gt_aggregate_combine_supported(dtype, in_dim, out_dim):
+    yes = c_int()
+    _check(lib.gt_aggregate_combine_supported(_dtype_code(dtype), int(in_dim), int(out_dim), byref(yes)))
+    return bool(yes.value)
+
+
+def gt_aggregate_combine_fwd(g: Graph, reduce, X, W, b=None, relu=False, out=None):
+    """Y = act((A X) W + b) in one fused kernel (inference: A X is not kept)."""
+    fi, fo = W.shape
+    Y = torch.empty((g.n_dst, fo), dtype=X.dtype, device=X.device) if out is None else out
+    ws = g.aggregate_ws(fi)
+    assert W.is_contiguous()
+    _check(lib.gt_aggregate_combine_fwd(g.handle, REDUCE[reduce], _dtype(X), fi, fo, _ptr(X), _rows2d(X), _ptr(W), _ptr(b),
+                                        GT_ACT_RELU if relu else GT_ACT_NONE, _ptr(Y), _rows2d(Y), _ptr(ws), ws.numel(),
+                                        _stream()))
+    return Y
+
+
 def gt_aggregate_bwd(g: Graph, reduce, dY, out=None, F=None):
     """dX[n_src, F] = A^T dY."""
     F = dY.shape[1] if F is None else F
@@ -301,7 +323,7 @@ def gt_pull_bwd(g: Graph, reduce, h, dY, Xs, W, out_dXs=None, out_dW=None):
     return dXs, dW
 
 
-def make_desc(reduce, dtype, relu, in_dim, out_dim, has_root=False, need_dx=True):
+def make_desc(reduce, dtype, relu, in_dim, out_dim, has_root=False, need_dx=True, in_relu=False, dy_is_dz=False):
     d = gt_layer_desc()
     d.reduce = REDUCE[reduce]
     if dtype in (torch.bfloat16, "bf16"):
@@ -313,6 +335,7 @@ def make_desc(reduce, dtype, relu, in_dim, out_dim, has_root=False, need_dx=True
     d.act = GT_ACT_RELU if relu else GT_ACT_NONE
     d.in_dim, d.out_dim = int(in_dim), int(out_dim)
     d.has_root, d.need_dx = int(has_root), int(need_dx)
+    d.in_act, d.dy_is_dz = (GT_ACT_RELU if in_relu else GT_ACT_NONE), int(dy_is_dz)
     return d
 
 
@@ -337,12 +360,14 @@ class LayerBuffers:
         self.scratch = _ws(t, g.device)
 
 
-def gt_layer_fwd(g: Graph, desc, X, W, b, bufs: LayerBuffers, order="auto", W_root=None, out=None):
+def gt_layer_fwd(g: Graph, desc, X, W, b, bufs: LayerBuffers, order="auto", W_root=None, out=None, inference=False):
+    """`inference=True` passes no `saved` buffer: forward only, no backward call may follow."""
     tdt = torch.bfloat16 if desc.dtype == GT_BF16 else torch.float32
     Y = torch.empty((g.n_dst, desc.out_dim), dtype=tdt, device=X.device) if out is None else out
     used = c_int()
+    saved = None if inference else bufs.saved
     _check(lib.gt_layer_fwd(g.handle, byref(desc), ORDER[order], _ptr(X), _rows2d(X), _ptr(W), _ptr(W_root), _ptr(b),
-                            _ptr(Y), _rows2d(Y), _ptr(bufs.saved), bufs.saved.numel(), _ptr(bufs.scratch),
+                            _ptr(Y), _rows2d(Y), _ptr(saved), 0 if inference else saved.numel(), _ptr(bufs.scratch),
                             bufs.scratch.numel(), byref(used), _stream()))
     return Y, ORDER_NAME[used.value]
 

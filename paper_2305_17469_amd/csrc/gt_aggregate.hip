@@ -16,7 +16,7 @@ size_t gt_aggregate_ws_bytes(const gt_graph *g, int64_t F) {
 
 gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce, gt_dtype in_dtype, gt_dtype out_dtype,
                            int64_t F, const void *X, int64_t ldx, void *Y, int64_t ldy, const float *bias, gt_act act,
-                           void *ws, size_t ws_bytes, hipStream_t st, bool traced) {
+                           void *ws, size_t ws_bytes, hipStream_t st, bool traced, const void *mask, int64_t ldmask) {
     const char *fn = transposed ? "gt_aggregate_bwd" : "gt_aggregate_fwd";
     if (!g) return gt_fail(GT_ERR_INVALID_ARG, "%s: g is null", fn);
     if (F < 0) return gt_fail(GT_ERR_INVALID_ARG, "%s: F < 0", fn);
@@ -57,6 +57,8 @@ gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce,
         a.coef = sc.coef_sym;               // w_e / sqrt(d(u) d(v)), stored per entry
     }
     a.bias = bias; a.relu = (act == GT_ACT_RELU);
+    a.mask = mask; a.ldmask = ldmask;
+    if (mask && ldmask < F) return gt_fail(GT_ERR_INVALID_ARG, "%s: mask leading dimension smaller than F", fn);
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy; a.F = F;
     a.partials = static_cast<float *>(ws); a.ldp = (F + 7) / 8 * 8;
     a.splits = sc.splits; a.n_splits = sc.n_splits;
@@ -65,7 +67,8 @@ gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce,
     a.n_rows = n_out; a.n_edges = g->n_edges;
 
     const int ve = in_dtype == GT_F32 ? 4 : 8;
-    const bool vec = aligned16(X) && aligned16(Y) && (ldx % ve == 0) && (ldy % ve == 0);
+    const bool vec = aligned16(X) && aligned16(Y) && (ldx % ve == 0) && (ldy % ve == 0) &&
+                     (!mask || (aligned16(mask) && ldmask % ve == 0));
     // A gathered table far larger than the last-level cache, with rows of 512 bytes or more, is
     // aggregated in column passes of 256 bytes, one launch each: every pass gathers from a table
     // slice a fraction of the size, so more of the popular rows stay cached, and the narrow launch
@@ -84,6 +87,7 @@ gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce,
         a.F = fp;
         a.ldp = (fp + 7) / 8 * 8;
         a.bias = bias ? bias + c0 : nullptr;
+        a.mask = mask ? static_cast<const char *>(mask) + c0 * es : nullptr;
         gt_status s;
         if (in_dtype == GT_F32) s = vec ? dispatch<float, 4>(a, st) : dispatch<float, 1>(a, st);
         else s = vec ? dispatch<bf16_t, 8>(a, st) : dispatch<bf16_t, 1>(a, st);

@@ -35,6 +35,8 @@ struct AggArgs {
     int post_mode;           // 0 none, 2 divide by the row's entry count (mean, forward)
     const float *bias;       // per-column bias added after scaling, or null
     int relu;
+    const void *mask;        // [n_rows][ldmask] of type T or null: outputs are zeroed where mask <= 0 (the
+    int64_t ldmask;          // derivative of the ReLU that produced `mask`, applied as the row is written)
     const void *X;
     int64_t ldx;
     void *Y;
@@ -46,6 +48,8 @@ struct AggArgs {
     int64_t n_splits;
     int64_t table_bytes;     // host-side: size of the gathered table (picks the unroll)
     int xcd_run;             // item blocks per XCD run (0 or 1: plain order)
+    int only_split;          // run only the chunk items of split rows (the whole-row items are someone else's)
+    int no_reduce;           // host-side: do not launch the kernel that adds the partial rows
     int trace_kind;          // host-side bookkeeping of the optional kernel timing
     int64_t n_rows, n_edges;
 };
@@ -185,13 +189,27 @@ __device__ inline void finish_row(const AggArgs &a, int row, int gl, int64_t col
         const int64_t col = col0 + (int64_t)(p * G + gl) * V;
         if (col >= a.F) continue;
         const int n = (int)((a.F - col) < V ? (a.F - col) : V);
-        float o[V];
+        float o[V], m[V];
+        if (a.mask) {
+            const T *mp = static_cast<const T *>(a.mask) + (int64_t)row * a.ldmask + col;
+            if (n >= V) {
+                load_vec<T, V>(mp, m);
+            } else {
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    float one[1] = {0.0f};
+                    if (i < n) load_vec<T, 1>(mp + i, one);
+                    m[i] = one[0];
+                }
+            }
+        }
 #pragma unroll
         for (int i = 0; i < V; ++i) {
             float x = acc[p][i];
             if (a.post_mode == 2) x = zero ? 0.0f : x / div;
             if (a.bias && i < n) x += a.bias[col + i];
             if (a.relu) x = x > 0.0f ? x : 0.0f;
+            if (a.mask) x = m[i] > 0.0f ? x : 0.0f;
             o[i] = x;
         }
         store_vec<T, V>(y + col, o, n);
@@ -242,6 +260,7 @@ __global__ void __launch_bounds__(256) k_aggregate(const AggArgs a) {
     if (item_id >= a.n_items) return;   // whole groups leave together; no barriers are used below
     const int4 raw = reinterpret_cast<const int4 *>(a.items)[item_id];
     int row = raw.x, e0 = raw.y, e1 = raw.z, slot = raw.w;
+    if (a.only_split && slot < 0) return;   // uniform within the group
     if constexpr (G == 64) {   // one item per wavefront: keep its bounds in scalar registers
         row = __builtin_amdgcn_readfirstlane(row);
         e0 = __builtin_amdgcn_readfirstlane(e0);
@@ -406,7 +425,7 @@ gt_status launch(const AggArgs &a, hipStream_t st) {
         gt_trace_close(tr, st);
         GT_LAUNCH_CHECK("k_aggregate");
     }
-    if (a.n_splits > 0) {
+    if (a.n_splits > 0 && !a.no_reduce) {
         const int64_t gx = (a.n_splits + 4 * NG - 1) / (4 * NG);
         k_reduce_partials<T, V, G, NP><<<dim3((unsigned)gx, gy), 256, 0, st>>>(a);
         GT_LAUNCH_CHECK("k_reduce_partials");

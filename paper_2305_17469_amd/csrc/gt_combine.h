@@ -8,7 +8,7 @@ size_t gt_gemm_ws_bytes(int transA, int64_t M, int64_t N, int64_t K);
 gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
                       const void *A, int64_t lda, const void *B, int64_t ldb, const float *bias, const float *rowscale,
                       gt_act act, const void *Cin, int64_t ldcin, void *C, int64_t ldc, gt_dtype c_dtype, void *ws,
-                      size_t ws_bytes, hipStream_t st);
+                      size_t ws_bytes, hipStream_t st, const void *mask = nullptr, int64_t ldmask = 0);
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -35,6 +35,7 @@ struct GemmArgs {
     const void *Cin; int64_t ldcin; // optional addend, same type as C
     const float *bias;
     const float *rowscale;         // optional per-row factor applied to the product before addend/bias
+    const void *mask; int64_t ldmask; // optional, type and shape of C: outputs are zeroed where mask <= 0
     int relu;
     int c_bf16;
     int64_t M, N, K;
@@ -127,6 +128,11 @@ __device__ inline void gemm_epilogue(const GemmArgs &g, floatx16 (&acc)[TM][TN],
                                       : static_cast<const float *>(g.Cin)[row * g.ldcin + col + i];
                     x += bia[i];
                     if (g.relu) x = x > 0.0f ? x : 0.0f;
+                    if (g.mask && col + i < g.N) {
+                        const float mk = g.c_bf16 ? gemm_bf16_to_f32(static_cast<const gemm_bf16_t *>(g.mask)[row * g.ldmask + col + i])
+                                                  : static_cast<const float *>(g.mask)[row * g.ldmask + col + i];
+                        x = mk > 0.0f ? x : 0.0f;
+                    }
                     v[i] = x;
                 }
             }

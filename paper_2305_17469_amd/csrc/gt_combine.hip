@@ -370,8 +370,9 @@ size_t gt_gemm_ws_bytes(int transA, int64_t M, int64_t N, int64_t K) {
 gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
                       const void *A, int64_t lda, const void *B, int64_t ldb, const float *bias, const float *rowscale,
                       gt_act act, const void *Cin, int64_t ldcin, void *C, int64_t ldc, gt_dtype c_dtype, void *ws,
-                      size_t ws_bytes, hipStream_t st) {
+                      size_t ws_bytes, hipStream_t st, const void *mask, int64_t ldmask) {
     if (dtype != GT_F32 && dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown dtype", fn);
+    if (mask && ldmask < N) return gt_fail(GT_ERR_INVALID_ARG, "%s: mask leading dimension too small", fn);
     if (c_dtype != GT_F32 && c_dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown c_dtype", fn);
     if (M < 0 || N < 0 || K < 0) return gt_fail(GT_ERR_INVALID_ARG, "%s: negative size", fn);
     if (M == 0 || N == 0) return GT_OK;
@@ -398,6 +399,8 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     g.vecB = (((uintptr_t)B & 15) == 0 && ldb % ve == 0);
     g.bias = bias; g.rowscale = rowscale; g.relu = (act == GT_ACT_RELU); g.c_bf16 = (c_dtype == GT_BF16);
     g.Cin = Cin; g.ldcin = ldcin;
+    g.mask = mask; g.ldmask = ldmask;
+    if (mask && p.splits > 1) return gt_fail(GT_ERR_INTERNAL, "%s: an output mask on a split reduction", fn);
     if (p.splits > 1) { g.C = ws; g.ldc = N; } else { g.C = C; g.ldc = ldc; }
     const int tr = gt_trace_open(GT_TRACE_COMBINE, N, M, M * N * K, st);
     // tall products with a small weight matrix are bound by streaming A and C once: the

@@ -48,6 +48,13 @@ __device__ inline uint4 ws_mask(uint4 v, int nv) {
     return v;
 }
 
+// two bf16 values of v, each kept where the bf16 value at the same place of m is > 0, else zeroed
+__device__ inline uint32_t ws_mask_pair(uint32_t v, uint32_t m) {
+    const uint32_t lo = __uint_as_float(m << 16) > 0.0f ? 0x0000ffffu : 0u;
+    const uint32_t hi = __uint_as_float(m & 0xffff0000u) > 0.0f ? 0xffff0000u : 0u;
+    return v & (lo | hi);
+}
+
 // One slice (32 rows x 128 bytes) of block rb: lane -> row lane/8 + 8 j (j = 0..3), chunk lane%8.
 // Rows past M read the last row (never stored); chunks at or past K read the row's first chunk
 // (always valid) and are zeroed when staged.
@@ -84,6 +91,15 @@ __device__ inline void ws_epilogue(const GemmArgs &g, floatx16 (&acc)[NB], int64
             if (EX) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) v[i] = (g.relu && !(v[i] > 0.0f)) ? 0.0f : v[i];
+                if (g.mask) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        if (!FAST && col + i >= g.N) continue;
+                        const float mk = CB ? gemm_bf16_to_f32(static_cast<const gemm_bf16_t *>(g.mask)[row * g.ldmask + col + i])
+                                            : static_cast<const float *>(g.mask)[row * g.ldmask + col + i];
+                        v[i] = mk > 0.0f ? v[i] : 0.0f;
+                    }
+                }
             }
             if (CB) {
                 gemm_bf16_t *p = static_cast<gemm_bf16_t *>(g.C) + row * g.ldc + col;
@@ -135,9 +151,14 @@ __device__ inline void ws_epilogue_rows_f32(const GemmArgs &g, floatx16 (&acc)[N
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int rr = it * 8 + (lane >> 3), c4 = (lane & 7) * 4;
-            const float4 v = *reinterpret_cast<const float4 *>(stage + rr * SSTR + c4);
+            float4 v = *reinterpret_cast<const float4 *>(stage + rr * SSTR + c4);
             int64_t row = row0 + rr;
             if (row >= g.M) row = g.M - 1;
+            if (EX && g.mask) {   // the host passes a mask here only when its rows allow 16-byte loads
+                const float4 mk = *reinterpret_cast<const float4 *>(static_cast<const float *>(g.mask) + row * g.ldmask + n0 + b * 32 + c4);
+                v.x = mk.x > 0.0f ? v.x : 0.0f; v.y = mk.y > 0.0f ? v.y : 0.0f;
+                v.z = mk.z > 0.0f ? v.z : 0.0f; v.w = mk.w > 0.0f ? v.w : 0.0f;
+            }
             *reinterpret_cast<float4 *>(static_cast<float *>(g.C) + row * g.ldc + n0 + b * 32 + c4) = v;
         }
     }
@@ -175,9 +196,15 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int rr = it * 8 + (lane >> 3);
-            const uint4 v = *reinterpret_cast<const uint4 *>(stage + rr * SSTR + (lane & 7) * 4);
+            uint4 v = *reinterpret_cast<const uint4 *>(stage + rr * SSTR + (lane & 7) * 4);
             int64_t row = row0 + rr;
             if (row >= g.M) row = g.M - 1;
+            if (EX && g.mask) {
+                const uint4 mk = *reinterpret_cast<const uint4 *>(static_cast<const gemm_bf16_t *>(g.mask) + row * g.ldmask + n0 +
+                                                                 bp * 64 + (lane & 7) * 8);
+                v.x = ws_mask_pair(v.x, mk.x); v.y = ws_mask_pair(v.y, mk.y);
+                v.z = ws_mask_pair(v.z, mk.z); v.w = ws_mask_pair(v.w, mk.w);
+            }
             *reinterpret_cast<uint4 *>(static_cast<gemm_bf16_t *>(g.C) + row * g.ldc + n0 + bp * 64 + (lane & 7) * 8) = v;
         }
     }
@@ -578,9 +605,10 @@ gt_status ws_x3_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
 
 template <int NB, int NS>
 gt_status ws_x3_launch(const GemmArgs &g, int transB, hipStream_t st) {
-    const bool extras = g.bias || g.relu;
+    const bool extras = g.bias || g.relu || g.mask;
     if constexpr (NB >= 4) {
-        const bool fast = g.N % (NB * 32) == 0 && g.ldc % 4 == 0 && (((uintptr_t)g.C & 15) == 0);
+        const bool fast = g.N % (NB * 32) == 0 && g.ldc % 4 == 0 && (((uintptr_t)g.C & 15) == 0) &&
+                          (!g.mask || (g.ldmask % 8 == 0 && ((uintptr_t)g.mask & 15) == 0));
         if (fast)
             return extras ? ws_x3_launch_ex<NB, NS, true, true>(g, transB, st)
                           : ws_x3_launch_ex<NB, NS, false, true>(g, transB, st);
@@ -611,9 +639,10 @@ gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
 
 template <typename T, int NB, int NS>
 gt_status ws_launch(const GemmArgs &g, int transB, hipStream_t st) {
-    const bool extras = g.bias || g.relu;
+    const bool extras = g.bias || g.relu || g.mask;
     if constexpr (NB >= 4) {   // the branch-free form exists for the wide slices, where the stores dominate
-        const bool fast = g.N % (NB * 32) == 0 && g.ldc % 4 == 0 && (((uintptr_t)g.C & 15) == 0);
+        const bool fast = g.N % (NB * 32) == 0 && g.ldc % 4 == 0 && (((uintptr_t)g.C & 15) == 0) &&
+                          (!g.mask || (g.ldmask % 8 == 0 && ((uintptr_t)g.mask & 15) == 0));
         if (fast)
             return extras ? ws_launch_ex<T, NB, NS, true, true>(g, transB, st)
                           : ws_launch_ex<T, NB, NS, false, true>(g, transB, st);

@@ -85,6 +85,12 @@ static inline size_t gt_dtype_size(gt_dtype t) { return t == GT_BF16 ? 2 : 4; }
 gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce, gt_dtype in_dtype,
                            gt_dtype out_dtype, int64_t F, const void *X, int64_t ldx, void *Y, int64_t ldy,
                            const float *bias, gt_act act, void *ws, size_t ws_bytes, hipStream_t stream,
-                           bool traced = true);
+                           bool traced = true, const void *mask = nullptr, int64_t ldmask = 0);
 
 size_t gt_aggregate_ws_bytes(const gt_graph *g, int64_t F);
+
+// fused aggregation-first forward (gt_fused.hip): Y = act((A X) W + b) without writing A X
+bool gt_fused_applicable(gt_dtype dtype, int64_t in_dim, int64_t out_dim);
+gt_status gt_fused_run(const gt_graph *g, gt_reduce reduce, gt_dtype dtype, int64_t fi, int64_t fo, const void *X, int64_t ldx,
+                       const void *W, int64_t ldw, const float *bias, gt_act act, void *Y, int64_t ldy, void *ws,
+                       size_t ws_bytes, hipStream_t st);

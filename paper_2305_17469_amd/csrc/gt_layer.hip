@@ -262,6 +262,7 @@ gt_status check_desc(const char *fn, const gt_graph *g, const gt_layer_desc *d) 
     if (d->reduce != GT_SUM && d->reduce != GT_MEAN && d->reduce != GT_SYMNORM)
         return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown reduce", fn);
     if (d->act != GT_ACT_NONE && d->act != GT_ACT_RELU) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown activation", fn);
+    if (d->in_act != GT_ACT_NONE && d->in_act != GT_ACT_RELU) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown in_act", fn);
     if (d->reduce == GT_SYMNORM && g->n_dst != g->n_src)
         return gt_fail(GT_ERR_UNSUPPORTED, "%s: GT_SYMNORM needs a square graph", fn);
     if (d->has_root && g->n_dst > g->n_src)
@@ -274,6 +275,20 @@ void *at(void *base, size_t off) { return static_cast<char *>(base) + off; }
 bool ranges_overlap(const void *a, size_t a_elems, const void *b, size_t b_elems, size_t es) {
     const char *a0 = static_cast<const char *>(a), *b0 = static_cast<const char *>(b);
     return a0 < b0 + b_elems * es && b0 < a0 + a_elems * es;
+}
+
+// Forward-only aggregation-first layers: where the fused aggregation + combination kernel is used
+// instead of the two kernels.  Measured on MI355X (ms, two kernels / fused): input rows of 64 bytes on a
+// 2^20-vertex uniform graph, 16 -> 64 fp32 0.49 / 0.37, 16 -> 256 0.63 / 0.55: the gather of such
+// rows is bound by the number of memory requests, and writing and re-reading A X costs as much as
+// gathering it.  Wider rows lose: one workgroup per CU holds the weights, and eight wavefronts hide
+// less gather latency than the aggregation kernel's two dozen (2^21-vertex power-law graph, bf16
+// 100 -> 256: 1.96 / 2.52; 2^18 vertices, fp32 128 -> 41: 0.52 / 1.10; 41 -> 128: 0.27 / 0.57).
+bool fused_preferred(const gt_graph *g, const gt_layer_desc *d, const void *X, int64_t ldx) {
+    const int ve = d->dtype == GT_BF16 ? 8 : 4;
+    if (!gt_fused_applicable(d->dtype, d->in_dim, d->out_dim) || ((uintptr_t)X & 15) || ldx % ve) return false;
+    (void)g;
+    return d->in_dim * (int64_t)gt_dtype_size(d->dtype) <= 64;
 }
 
 void decide(const gt_graph *g, const gt_layer_desc *d, gt_order *fwd, gt_order *bwd) {
@@ -441,8 +456,8 @@ extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_
         return gt_fail(GT_ERR_INVALID_ARG, "%s: X and Y overlap", fn);
     gt_order order = req;
     if (order == GT_AUTO) { gt_order bw; decide(g, d, &order, &bw); }
-    if (order == GT_AGG_FIRST) {
-        if (!saved || ((uintptr_t)saved & 255)) return gt_fail(GT_ERR_WORKSPACE, "%s: saved null or not 256-byte aligned", fn);
+    if (order == GT_AGG_FIRST && saved) {
+        if ((uintptr_t)saved & 255) return gt_fail(GT_ERR_WORKSPACE, "%s: saved not 256-byte aligned", fn);
         if (saved_bytes < L.saved)
             return gt_fail(GT_ERR_WORKSPACE, "%s: saved_bytes %zu < required %zu", fn, saved_bytes, L.saved);
     }
@@ -452,14 +467,20 @@ extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_
 
     void *gws = at(scratch, L.gemm_ws);
     if (order == GT_AGG_FIRST) {
+        // forward only (no `saved`): A X is a temporary, or is never written at all where the fused
+        // kernel applies and is the faster of the two
+        if (!saved && !d->has_root && fused_preferred(g, d, X, ldx))
+            return gt_fused_run(g, d->reduce, t, fi, fo, X, ldx, W, fo, b, d->act, Y, ldy, at(scratch, L.agg_ws),
+                                L.agg_ws_bytes, st);
+        void *M = saved ? saved : at(scratch, L.dM);
         // M = A X (kept for the weight gradient), then the combination on n_dst rows
-        s = gt_aggregate_run(g, false, d->reduce, t, t, fi, X, ldx, saved, L.ldi, nullptr, GT_ACT_NONE,
+        s = gt_aggregate_run(g, false, d->reduce, t, t, fi, X, ldx, M, L.ldi, nullptr, GT_ACT_NONE,
                              at(scratch, L.agg_ws), L.agg_ws_bytes, st);
         if (s != GT_OK) return s;
         if (!d->has_root)
-            return gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, saved, L.ldi, W, fo, b, nullptr, d->act, nullptr, 0, Y, ldy,
+            return gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, M, L.ldi, W, fo, b, nullptr, d->act, nullptr, 0, Y, ldy,
                                t, gws, L.gemm_ws_bytes, st);
-        s = gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, saved, L.ldi, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, Y,
+        s = gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, M, L.ldi, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, Y,
                         ldy, t, gws, L.gemm_ws_bytes, st);
         if (s != GT_OK) return s;
     } else {
@@ -491,7 +512,8 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
         return gt_fail(GT_ERR_INVALID_ARG, "%s: fwd_used must be the order gt_layer_fwd reported", fn);
     if (req != GT_AUTO && req != GT_AGG_FIRST && req != GT_COMB_FIRST) return gt_fail(GT_ERR_INVALID_ARG, "%s: bad order", fn);
     if (!dY || !X || !W || !dW) return gt_fail(GT_ERR_INVALID_ARG, "%s: dY, X, W or dW is null", fn);
-    if (d->act == GT_ACT_RELU && !Y) return gt_fail(GT_ERR_INVALID_ARG, "%s: Y is needed for the ReLU derivative", fn);
+    if (d->act == GT_ACT_RELU && !d->dy_is_dz && !Y)
+        return gt_fail(GT_ERR_INVALID_ARG, "%s: Y is needed for the ReLU derivative", fn);
     if ((d->has_root != 0) != (W_root != nullptr) || (d->has_root != 0) != (dW_root != nullptr))
         return gt_fail(GT_ERR_INVALID_ARG, "%s: W_root and dW_root must be given iff has_root", fn);
     if ((d->need_dx != 0) != (dX != nullptr)) return gt_fail(GT_ERR_INVALID_ARG, "%s: dX must be given iff need_dx", fn);
@@ -535,7 +557,7 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
     const void *dZ = dY;
     int64_t lddz = lddy;
     float *partial = static_cast<float *>(at(scratch, L.colsum));
-    if (d->act == GT_ACT_RELU) {
+    if (d->act == GT_ACT_RELU && !d->dy_is_dz) {
         void *z = at(scratch, L.dZ);
         s = (t == GT_F32) ? mask_colsum<float>(dY, lddy, Y, ldy, z, L.ldo, g->n_dst, fo, partial, db, st)
                           : mask_colsum<bf16_t>(dY, lddy, Y, ldy, z, L.ldo, g->n_dst, fo, partial, db, st);
@@ -574,23 +596,33 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
         if (s != GT_OK) return s;
     }
     if (!d->need_dx) return GT_OK;
+    // in_act: dX leaves already multiplied by [X > 0] (X is a ReLU output: the derivative of the
+    // layer below's activation).  The kernel that writes dX applies it as it stores the rows; with a
+    // root term, whose product is added to part of dX afterwards, it is a pass of its own at the end.
+    const bool mask_dx = d->in_act == GT_ACT_RELU;
+    const void *mk = (mask_dx && !d->has_root) ? X : nullptr;
     if (order == GT_COMB_FIRST) {
         // dX = (A^T dZ) W^T
         s = gt_gemm_run(fn, t, 0, 1, g->n_src, fi, fo, S, L.ldo, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dX, lddx,
-                        t, gws, L.gemm_ws_bytes, st);
+                        t, gws, L.gemm_ws_bytes, st, mk, ldx);
     } else {
         // dM = dZ W^T (the combination's derivative uses the transposed weight), dX = A^T dM
         void *dM = at(scratch, L.dM);
         s = gt_gemm_run(fn, t, 0, 1, g->n_dst, fi, fo, dZ, lddz, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dM, L.ldi,
                         t, gws, L.gemm_ws_bytes, st);
         if (s != GT_OK) return s;
-        s = gt_aggregate_run(g, true, d->reduce, t, t, fi, dM, L.ldi, dX, lddx, nullptr, GT_ACT_NONE, aws, L.agg_ws_bytes, st);
+        s = gt_aggregate_run(g, true, d->reduce, t, t, fi, dM, L.ldi, dX, lddx, nullptr, GT_ACT_NONE, aws, L.agg_ws_bytes, st,
+                             true, mk, ldx);
     }
     if (s != GT_OK) return s;
     if (d->has_root) {
         // dX[0:n_dst] += dZ W_root^T
         s = gt_gemm_run(fn, t, 0, 1, g->n_dst, fi, fo, dZ, lddz, W_root, fo, nullptr, nullptr, GT_ACT_NONE, dX, lddx, dX,
                         lddx, t, gws, L.gemm_ws_bytes, st);
+        if (s != GT_OK) return s;
+        if (mask_dx)
+            s = (t == GT_F32) ? mask_colsum<float>(dX, lddx, X, ldx, dX, lddx, g->n_src, fi, nullptr, nullptr, st)
+                              : mask_colsum<bf16_t>(dX, lddx, X, ldx, dX, lddx, g->n_src, fi, nullptr, nullptr, st);
     }
     return s;
 }

@@ -3,7 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-enum { GT_TRACE_AGG_FWD = 0, GT_TRACE_AGG_BWD = 1, GT_TRACE_COMBINE = 2 };
+enum { GT_TRACE_AGG_FWD = 0, GT_TRACE_AGG_BWD = 1, GT_TRACE_COMBINE = 2, GT_TRACE_FUSED = 3 };
 
 bool gt_trace_on();
 // returns a record id (or -1 when tracing is off); `work` is edges (aggregation) or M*N*K (combine)

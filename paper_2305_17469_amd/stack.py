@@ -20,7 +20,7 @@ class LayerStack:
     graph repeats the same dict).  Weights are device tensors of the layer dtype, biases fp32.
     Hidden layers use ReLU, the last layer none; the first layer produces no input gradient."""
 
-    def __init__(self, blocks, dims, dtype, reduce, W, b, W_root=None, pad=True):
+    def __init__(self, blocks, dims, dtype, reduce, W, b, W_root=None, pad=True, fold_relu_grad=True):
         self.dtype, self.reduce, self.dims = dtype, reduce, list(dims)
         self.tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
         self.L = len(dims) - 1
@@ -53,8 +53,10 @@ class LayerStack:
         feat_shapes, f32_shapes = [], []
         for l in range(self.L):
             g = self.graphs[l]
+            # hidden layers end in a ReLU: the layer above folds its derivative into the gradient it
+            # hands down (in_relu), and the layer itself then takes that gradient as dZ (dy_is_dz)
             d = B.make_desc(reduce, dtype, l < self.L - 1, dims[l], dims[l + 1], has_root=self.W_root[l] is not None,
-                            need_dx=l > 0)
+                            need_dx=l > 0, in_relu=fold_relu_grad and l > 0, dy_is_dz=fold_relu_grad and l < self.L - 1)
             self.descs.append(d)
             self.bufs.append(B.LayerBuffers(g, d))
             feat_shapes += [(g.n_dst, ld(dims[l + 1])), (g.n_src if l > 0 else 0, ld(dims[l]))]

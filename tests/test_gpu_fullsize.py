@@ -110,10 +110,15 @@ def run_and_check(cfg, n_rand=768, n_top=12, n_cols=6):
         dYl = cfg["G"] if l == L - 1 else _seeded((nd, fo), dt, 901, 60 + l)
         Ym = _seeded((nd, fo), dt, 902, 60 + l) if relu else None
         dYd = G if l == L - 1 else _up(dYl, dt, dev)
+        assert bool(d.dy_is_dz) == relu and bool(d.in_act) == (l > 0)
         Ymd = _up(Ym, dt, dev) if relu else Yd
         r = B.gt_layer_bwd(g, d, used_f, dYd, Xd, W[l], Ymd, bufs, "auto", Wr[l], out_dX=model.dH[l])
         torch.cuda.synchronize()
-        dZ = (dYl * (Ym > 0) if relu else dYl).astype(np.float64)
+        # descriptors of the benchmark configuration fold the ReLU derivative into the producer of the
+        # gradient: a hidden layer takes its dY as dZ (dy_is_dz), a layer above a ReLU returns
+        # dX (.) [X > 0] (in_act)
+        own_mask = relu and not d.dy_is_dz
+        dZ = (dYl * (Ym > 0) if own_mask else dYl).astype(np.float64)
         errs["db%d" % l] = max_rel_err(down(r["db"]), dZ.sum(axis=0))
         ks = np.sort(rng.choice(fi, size=min(n_cols, fi), replace=False))
         Mk = oracle.aggregate_fwd(rp, ci, ns, np.ascontiguousarray(Xl[:, ks]), cfg["reduce"])
@@ -129,6 +134,8 @@ def run_and_check(cfg, n_rand=768, n_top=12, n_cols=6):
             if sage:
                 inb = Rs < nd
                 dX[inb] += oracle.combine(dZ[Rs[inb]], Wrl, transB=True)
+            if d.in_act:
+                dX = dX * (Xl[Rs] > 0)
             if dt == "bf16":
                 dX = oracle.round_bf16(dX)
             errs["dX%d" % l] = max_rel_err(_f32(r["dX"])[Rs].astype(np.float64), dX)

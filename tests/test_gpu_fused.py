@@ -1,0 +1,127 @@
+"""gt_aggregate_combine_fwd (the fused aggregation-first forward: aggregated rows go from
+registers through LDS into the matrix instructions, A X is never written) against the oracle's
+layer_fwd, element by element; and gt_layer_fwd without a `saved` buffer (forward only)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gt_inputs import graphs, tensors
+from gpu_util import announce, down, empty_feat, max_rel_err, pad_to, tol_for, up_feat, up_i32
+
+pytestmark = pytest.mark.gpu
+
+
+def _hub_graph():
+    """4,096-vertex R-MAT plus planted hub rows (split into chunk items), empty rows included."""
+    rp, ci = graphs.rmat_csr(12, 8, seed=51, self_loops=False)
+    n = rp.size - 1
+    dst = np.repeat(np.arange(n), np.diff(rp))
+    rng = np.random.default_rng(9)
+    es = np.concatenate([rng.choice(n, 2500, replace=False), rng.choice(n, 600, replace=False)])
+    ed = np.concatenate([np.full(2500, 21), np.full(600, 1300)])
+    rp, ci = graphs.csr_from_pairs(np.concatenate([ci, es]), np.concatenate([dst, ed]), n, n)
+    return rp, ci, n
+
+
+SHAPES = [("bf16", 100, 256), ("bf16", 100, 47), ("bf16", 256, 64), ("bf16", 64, 128), ("bf16", 8, 256),
+          ("f32", 64, 16), ("f32", 128, 64), ("f32", 16, 256), ("f32", 41, 128), ("f32", 100, 100)]
+
+
+@pytest.mark.parametrize("dtype,fi,fo", SHAPES)
+def test_fused_forward_matches_oracle(dtype, fi, fo):
+    from paper_2305_17469_amd import binding as B
+    assert B.gt_aggregate_combine_supported(dtype, fi, fo)
+    rp, ci, n = _hub_graph()
+    g = B.Graph(up_i32(rp), up_i32(ci), n)
+    assert g.info()["fwd_split_rows"] >= 2
+    blk = dict(rowptr=rp, colidx=ci, n_src=n, n_dst=n)
+    X = tensors.normal((n, fi), seed=400 + fi)
+    W = tensors.glorot(fi, fo, seed=401 + fo)
+    b = (0.1 * tensors.normal((fo,), seed=402)).astype(np.float32)
+    if dtype == "bf16":
+        X, W = tensors.bf16_values(X), tensors.bf16_values(W)
+    Xd, Wd, bd = up_feat(X, dtype, pad_to(fi, dtype)), up_feat(W, dtype), torch.from_numpy(b).cuda()
+    tol = tol_for(dtype)
+    for reduce in ("sum", "mean", "symnorm"):
+        for relu, bias in ((True, True), (False, False)):
+            announce("fused agg+combine", dtype, fi, fo, reduce, "relu" if relu else "linear")
+            out = empty_feat(n, fo, dtype, pad_to(fo, dtype))
+            B.gt_aggregate_combine_fwd(g, reduce, Xd, Wd, bd if bias else None, relu, out=out)
+            ref = oracle.layer_fwd(blk, reduce, X, W, b if bias else np.zeros(fo), relu)["H"]
+            if dtype == "bf16":
+                ref = oracle.round_bf16(ref)
+            got = down(out)
+            assert not np.isnan(got).any(), "a row was not written"
+            assert max_rel_err(got, ref) <= tol, (dtype, fi, fo, reduce, relu, max_rel_err(got, ref))
+            if out.stride(0) > fo:   # padding columns of the output are never written
+                pad = out.as_strided((n, out.stride(0) - fo), (out.stride(0), 1), out.storage_offset() + fo)
+                assert torch.isnan(pad).all()
+            # the two-kernel path of the library gives the same result up to the matrix instructions' summation order
+            two = B.gt_combine(B.gt_aggregate_fwd(g, reduce, Xd), Wd, bd if bias else None, relu)
+            assert max_rel_err(got, down(two)) <= (2.0 ** -7 if dtype == "bf16" else 2e-6)
+
+
+def test_fused_bipartite_block_and_argument_errors():
+    from paper_2305_17469_amd import binding as B
+    from gt_inputs import configs
+    announce("fused agg+combine: bipartite block, errors")
+    blk = configs.sage_minibatch(12, 64)["blocks"][0]
+    rp, ci, ns, nd = blk["rowptr"], blk["colidx"], blk["n_src"], blk["n_dst"]
+    g = B.Graph(up_i32(rp), up_i32(ci), ns)
+    X = tensors.normal((ns, 48), seed=7)
+    W = tensors.glorot(48, 40, seed=8)
+    out = B.gt_aggregate_combine_fwd(g, "mean", up_feat(X, "f32"), up_feat(W, "f32"))
+    ref = oracle.layer_fwd(blk, "mean", X, W, np.zeros(40), False)["H"]
+    assert max_rel_err(down(out), ref) <= 1e-5
+    with pytest.raises(B.GtError) as e:
+        B.gt_aggregate_combine_fwd(g, "symnorm", up_feat(X, "f32"), up_feat(W, "f32"))
+    assert e.value.status == 2                                    # not a square graph
+    assert not B.gt_aggregate_combine_supported("bf16", 256, 256)  # weights + tiles exceed the LDS
+    assert not B.gt_aggregate_combine_supported("f32", 129, 16)
+    assert not B.gt_aggregate_combine_supported("f32", 16, 257)
+    Xw = up_feat(tensors.normal((ns, 129), seed=1), "f32", 132)
+    Ww = up_feat(tensors.glorot(129, 16, seed=2), "f32")
+    with pytest.raises(B.GtError) as e:
+        B.gt_aggregate_combine_fwd(g, "sum", Xw, Ww)
+    assert e.value.status == 2
+    Xu = up_feat(tensors.normal((ns, 41), seed=1), "f32", 41)      # rows not 16-byte aligned
+    with pytest.raises(B.GtError) as e:
+        B.gt_aggregate_combine_fwd(g, "sum", Xu, up_feat(tensors.glorot(41, 16, seed=2), "f32"))
+    assert e.value.status == 2
+    g0 = B.Graph(up_i32(np.zeros(1, np.int32)), up_i32(np.zeros(0, np.int32)), 0)
+    assert B.lib.gt_aggregate_combine_fwd(g0.handle, 0, 0, 16, 16, None, 16, None, None, 0, None, 16, None, 0, None) == 0
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layer_forward_only_without_saved_buffer(dtype):
+    """gt_layer_fwd with saved == NULL (inference) gives the same outputs as the training call, in
+    both forced orders and AUTO, with and without the root term."""
+    _forward_only(dtype, 100, 64)
+    _forward_only(dtype, 16, 64)      # 64-byte (fp32) / 32-byte (bf16) rows: AUTO / agg_first take the fused kernel
+
+
+def _forward_only(dtype, fi, fo):
+    from paper_2305_17469_amd import binding as B
+    rp, ci, n = _hub_graph()
+    g = B.Graph(up_i32(rp), up_i32(ci), n)
+    X = tensors.normal((n, fi), seed=21)
+    W = tensors.glorot(fi, fo, seed=22)
+    Wr = tensors.glorot(fi, fo, seed=23)
+    b = (0.1 * tensors.normal((fo,), seed=24)).astype(np.float32)
+    if dtype == "bf16":
+        X, W, Wr = tensors.bf16_values(X), tensors.bf16_values(W), tensors.bf16_values(Wr)
+    Xd, Wd, Wrd, bd = up_feat(X, dtype, pad_to(fi, dtype)), up_feat(W, dtype), up_feat(Wr, dtype), torch.from_numpy(b).cuda()
+    blk = dict(rowptr=rp, colidx=ci, n_src=n, n_dst=n)
+    for root in (False, True):
+        d = B.make_desc("mean", dtype, True, fi, fo, has_root=root)
+        bufs = B.LayerBuffers(g, d)
+        ref = oracle.layer_fwd(blk, "mean", X, W, b, True, W_root=Wr if root else None)["H"]
+        if dtype == "bf16":
+            ref = oracle.round_bf16(ref)
+        for order in ("agg_first", "comb_first", "auto"):
+            announce("layer forward only", dtype, fi, fo, "root" if root else "plain", order)
+            Y, used = B.gt_layer_fwd(g, d, Xd, Wd, bd, bufs, order, Wrd if root else None, inference=True)
+            assert max_rel_err(down(Y), ref) <= tol_for(dtype), (dtype, root, order)

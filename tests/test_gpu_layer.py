@@ -18,7 +18,7 @@ def small_workloads():
             configs.reorder_stress(11, True, "mean", 100, 47)]
 
 
-def run_model(cfg, fwd_order, bwd_order, pad=True, ref=None):
+def run_model(cfg, fwd_order, bwd_order, pad=True, ref=None, fold=False):
     """The whole model through gt_layer_fwd / gt_layer_bwd, twice over:
       chained      forward with every layer reading the library's own previous output (what a user
                    runs); only its outputs are compared;
@@ -26,8 +26,9 @@ def run_model(cfg, fwd_order, bwd_order, pad=True, ref=None):
                    type), then the backward chain through those layers: X, Y and `saved` of a layer
                    come from its layer-wise forward, the upstream gradient from the layer above,
                    zeroed on the oracle-made set of ReLU decisions that rounding may flip.
-    `ref` = oracle_reference(cfg).  Returns (chained outputs, layer-wise outputs, gradients,
-    forward orders, backward orders)."""
+    `ref` = oracle_reference(cfg).  `fold`: the descriptors ask for the ReLU derivative to be
+    folded into the kernel that produces the gradient (in_act / dy_is_dz).  Returns (chained
+    outputs, layer-wise outputs, gradients, forward orders, backward orders)."""
     from paper_2305_17469_amd import binding as B
     st, stop = (ref or oracle_reference(cfg))[:2]
     dt = cfg["dtype"]
@@ -43,8 +44,8 @@ def run_model(cfg, fwd_order, bwd_order, pad=True, ref=None):
     Ws = [up_feat(w, dt) for w in cfg["W"]]
     Wr = [up_feat(w, dt) if sage else None for w in cfg["W_root"]]
     bs = [torch.from_numpy(b).cuda() for b in cfg["b"]]
-    descs = [B.make_desc(cfg["reduce"], dt, l < L - 1, cfg["dims"][l], cfg["dims"][l + 1], has_root=sage, need_dx=l > 0)
-             for l in range(L)]
+    descs = [B.make_desc(cfg["reduce"], dt, l < L - 1, cfg["dims"][l], cfg["dims"][l + 1], has_root=sage, need_dx=l > 0,
+                         in_relu=fold and l > 0, dy_is_dz=fold and l < L - 1) for l in range(L)]
     bufs = [B.LayerBuffers(graphs[l], descs[l]) for l in range(L)]
 
     def fwd(l, Xin):
@@ -71,8 +72,8 @@ def run_model(cfg, fwd_order, bwd_order, pad=True, ref=None):
             dH = torch.zeros((dH.shape[0], dH.stride(0)), dtype=dH.dtype, device=dH.device)[:, :dH.shape[1]]
             dH.copy_(keep)
             dH.masked_fill_(torch.from_numpy(stop[l]).cuda(), 0.0)
-        r = B.gt_layer_bwd(graphs[l], descs[l], used_f[l], dH, Xin[l], Ws[l], Hl[l], bufs[l], bwd_order, Wr[l],
-                           out_dX=out_dX)
+        r = B.gt_layer_bwd(graphs[l], descs[l], used_f[l], dH, Xin[l], Ws[l], None if descs[l].dy_is_dz else Hl[l],
+                           bufs[l], bwd_order, Wr[l], out_dX=out_dX)
         grads[l] = r
         used_b[l] = r["used"]
         dH = r["dX"]
@@ -96,7 +97,7 @@ def oracle_reference(cfg):
     return _ORACLE_CACHE[key]
 
 
-def compare(cfg, Hc, Hl, grads, what):
+def compare(cfg, Hc, Hl, grads, what, fold=False):
     """Outputs against the oracle's forward, gradients against the oracle's backward.  The ReLU
     derivative is a yes/no decision taken from a floating-point value (paper: "Training for GNNs",
     the activation's derivative): the library's decision [Y > 0] must equal the oracle's [Z > 0]
@@ -120,7 +121,9 @@ def compare(cfg, Hc, Hl, grads, what):
         if og[l]["dW_root"] is not None:
             errs["dWr%d" % l] = max_rel_err(down(grads[l]["dW_root"]), og[l]["dW_root"])
         if l > 0:
-            errs["dX%d" % l] = max_rel_err(down(grads[l]["dX"]), og[l]["dX"])
+            # folded: dX comes back multiplied by [X > 0], X being the oracle's activation given to the layer
+            want = og[l]["dX"] * (st[l - 1]["H"] > 0.0) if fold else og[l]["dX"]
+            errs["dX%d" % l] = max_rel_err(down(grads[l]["dX"]), want)
     assert max(errs.values()) <= tol, (what, errs)
     # the rounding sets must stay a small part of the outputs, or the gradient check would be hollow
     assert all(v <= (0.05 if cfg["dtype"] == "bf16" else 1e-3) for v in frac.values()), frac
@@ -130,14 +133,17 @@ def compare(cfg, Hc, Hl, grads, what):
 @pytest.mark.parametrize("cfg", small_workloads(), ids=lambda c: c["name"])
 @pytest.mark.parametrize("orders", [("agg_first", "agg_first"), ("comb_first", "comb_first"),
                                     ("agg_first", "comb_first"), ("comb_first", "agg_first"), ("auto", "auto")])
-def test_model_fwd_bwd_parity(cfg, orders):
-    announce("layer parity", cfg["name"], orders)
-    Hc, Hl, grads, uf, ub = run_model(cfg, *orders)
+@pytest.mark.parametrize("fold", [False, True], ids=["mask_pass", "mask_folded"])
+def test_model_fwd_bwd_parity(cfg, orders, fold):
+    if fold and len(cfg["W"]) == 1:
+        pytest.skip("a single layer has no ReLU between layers")
+    announce("layer parity", cfg["name"], orders, "folded" if fold else "")
+    Hc, Hl, grads, uf, ub = run_model(cfg, *orders, fold=fold)
     if orders[0] != "auto":
         assert all(u == orders[0] for u in uf)
         # the first layer has no dX: its backward order is reported as the forward's
         assert all(u == orders[1] for u in ub[1:])
-    compare(cfg, Hc, Hl, grads, (cfg["name"], orders))
+    compare(cfg, Hc, Hl, grads, (cfg["name"], orders, fold), fold=fold)
 
 
 def test_unpadded_strides_take_the_elementwise_path():
@@ -147,8 +153,9 @@ def test_unpadded_strides_take_the_elementwise_path():
     announce("layer parity unpadded ld", cfg["name"])
     cfg2 = dict(configs.reddit_like(11))       # 602 -> 128 -> 41, ld = 602 and 41: not multiples of 4
     for c in (cfg, cfg2):
-        Hc, Hl, grads, _, _ = run_model(c, "auto", "auto", pad=False)
-        compare(c, Hc, Hl, grads, (c["name"], "unpadded"))
+        for fold in (False, True):
+            Hc, Hl, grads, _, _ = run_model(c, "auto", "auto", pad=False, fold=fold)
+            compare(c, Hc, Hl, grads, (c["name"], "unpadded", fold), fold=fold)
 
 
 def test_auto_matches_decide_and_expected_orders():
