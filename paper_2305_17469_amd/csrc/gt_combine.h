@@ -8,7 +8,10 @@ size_t gt_gemm_ws_bytes(int transA, int64_t M, int64_t N, int64_t K);
 gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
                       const void *A, int64_t lda, const void *B, int64_t ldb, const float *bias, const float *rowscale,
                       gt_act act, const void *Cin, int64_t ldcin, void *C, int64_t ldc, gt_dtype c_dtype, void *ws,
-                      size_t ws_bytes, hipStream_t st, const void *mask = nullptr, int64_t ldmask = 0);
+                      size_t ws_bytes, hipStream_t st, const void *mask = nullptr, int64_t ldmask = 0,
+                      float *colsum_b = nullptr);
+// colsum_b (transA products with !transB only): also writes the N column sums of op(B) there, a
+// by-product of streaming B (the bias gradient when B is dZ); sums have a fixed order.
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -36,6 +39,8 @@ struct GemmArgs {
     const float *bias;
     const float *rowscale;         // optional per-row factor applied to the product before addend/bias
     const void *mask; int64_t ldmask; // optional, type and shape of C: outputs are zeroed where mask <= 0
+    float *colsum;                 // optional [splits][N]: column sums of op(B) over each split's k-range (!transB),
+                                   // written by the workgroups of row tile 0
     int relu;
     int c_bf16;
     int64_t M, N, K;

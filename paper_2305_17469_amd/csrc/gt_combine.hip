@@ -65,6 +65,22 @@ struct TileLoader {
             }
         }
     }
+    // adds this thread's (masked) elements to cs: the VE columns a thread loads are the same for all of
+    // its vectors when 256 is a multiple of VPR
+    __device__ inline void add_to(float (&cs)[VE]) const {
+#pragma unroll
+        for (int it = 0; it < NV; ++it) {
+            const int nv = nvalid[it];
+            const uint32_t w[4] = {reg[it].x, reg[it].y, reg[it].z, reg[it].w};
+#pragma unroll
+            for (int e = 0; e < VE; ++e) {
+                float x;
+                if constexpr (sizeof(T) == 4) x = __uint_as_float(w[e]);
+                else x = __uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
+                cs[e] += e < nv ? x : 0.0f;
+            }
+        }
+    }
     template <int STR>
     __device__ inline void store(T *lds) const {
 #pragma unroll
@@ -127,6 +143,12 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
         for (int b = 0; b < TN; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+    // column sums of op(B) over this workgroup's k-range, a by-product of loading B (row tile 0 only)
+    constexpr int VEB = Elem<T>::VE;
+    const bool do_cs = !TB && g.colsum && tile_m == 0;
+    float cs[VEB];
+#pragma unroll
+    for (int e = 0; e < VEB; ++e) cs[e] = 0.0f;
 
     typedef TileLoader<T, TA ? KT : BM, TA ? BM : KT> LoadA;
     typedef TileLoader<T, TB ? BN : KT, TB ? KT : BN> LoadB;
@@ -150,6 +172,9 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
         __syncthreads();                      // previous tile fully consumed
         la[st].template store<ASTR>(As);
         lb[st].template store<BSTR>(Bs);
+        if constexpr (!TB) {
+            if (do_cs) lb[st].add_to(cs);
+        }
         __syncthreads();
         if (k0 + STAGES * KT < kend) fetch(la[st], lb[st], k0 + STAGES * KT);
 
@@ -235,6 +260,25 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
     }
 
     __syncthreads();   // every wavefront is done reading the operand tiles
+    if constexpr (!TB) {
+        if (do_cs) {   // uniform over the workgroup
+            // thread t holds columns (t % VPR) * VE ..; the 256 / VPR threads that share them are added in
+            // thread order
+            constexpr int VPR = BN / VEB;
+            static_assert(256 % VPR == 0 && 256 * VEB * 4 <= SMEM_BYTES, "column-sum staging");
+            float *red = reinterpret_cast<float *>(smem);
+#pragma unroll
+            for (int e = 0; e < VEB; ++e) red[threadIdx.x * VEB + e] = cs[e];
+            __syncthreads();
+            if (threadIdx.x < BN) {
+                const int cv = threadIdx.x / VEB, e = threadIdx.x % VEB;
+                float t = 0.0f;
+                for (int o = 0; o < 256 / VPR; ++o) t += red[(cv + VPR * o) * VEB + e];
+                if (n0 + threadIdx.x < g.N) g.colsum[(int64_t)blockIdx.z * g.N + n0 + threadIdx.x] = t;
+            }
+            __syncthreads();
+        }
+    }
     gemm_epilogue<TM, TN>(g, acc, m0 + wm * TM * 32, n0 + wn * TN * 32, l32, h,
                           reinterpret_cast<float *>(smem) + wave * GEMM_STAGE_FLOATS(TN));
 }
@@ -364,13 +408,24 @@ size_t gt_gemm_ws_bytes(int transA, int64_t M, int64_t N, int64_t K) {
     const SplitPlan p = plan_split(transA, M, N, K, false);
     const SplitPlan q = plan_split(transA, M, N, K, use_x3(GT_F32, transA, M, N, K));
     const int splits = p.splits > q.splits ? p.splits : q.splits;
-    return splits > 1 ? gt_align_up((size_t)splits * (size_t)M * (size_t)N * 4) : 0;
+    // partial tiles of a split reduction, plus (weight-gradient shape) room for the column sums of B per split
+    return (splits > 1 ? gt_align_up((size_t)splits * (size_t)M * (size_t)N * 4) : 0) +
+           (transA ? gt_align_up((size_t)splits * (size_t)N * 4) : 0);
+}
+
+// out[c] = sum over the splits' column sums, in split order
+__global__ void __launch_bounds__(256) k_colsum_splits(const float *partial, int splits, int64_t cols, float *out) {
+    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= cols) return;
+    float t = 0.0f;
+    for (int z = 0; z < splits; ++z) t += partial[(int64_t)z * cols + c];
+    out[c] = t;
 }
 
 gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
                       const void *A, int64_t lda, const void *B, int64_t ldb, const float *bias, const float *rowscale,
                       gt_act act, const void *Cin, int64_t ldcin, void *C, int64_t ldc, gt_dtype c_dtype, void *ws,
-                      size_t ws_bytes, hipStream_t st, const void *mask, int64_t ldmask) {
+                      size_t ws_bytes, hipStream_t st, const void *mask, int64_t ldmask, float *colsum_b) {
     if (dtype != GT_F32 && dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown dtype", fn);
     if (mask && ldmask < N) return gt_fail(GT_ERR_INVALID_ARG, "%s: mask leading dimension too small", fn);
     if (c_dtype != GT_F32 && c_dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown c_dtype", fn);
@@ -385,7 +440,9 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
         return gt_fail(GT_ERR_INVALID_ARG, "%s: pointer misaligned for dtype", fn);
     const bool x3 = use_x3(dtype, transA, M, N, K);
     const SplitPlan p = plan_split(transA, M, N, K, x3);
-    const size_t need = p.splits > 1 ? gt_align_up((size_t)p.splits * (size_t)M * (size_t)N * 4) : 0;
+    if (colsum_b && (!transA || transB)) return gt_fail(GT_ERR_INTERNAL, "%s: column sums of B need the A^T B shape", fn);
+    const size_t need_part = p.splits > 1 ? gt_align_up((size_t)p.splits * (size_t)M * (size_t)N * 4) : 0;
+    const size_t need = need_part + (colsum_b ? gt_align_up((size_t)p.splits * (size_t)N * 4) : 0);
     if (need) {
         if (!ws || ((uintptr_t)ws & 255)) return gt_fail(GT_ERR_WORKSPACE, "%s: ws null or not 256-byte aligned", fn);
         if (ws_bytes < need) return gt_fail(GT_ERR_WORKSPACE, "%s: ws_bytes %zu < required %zu", fn, ws_bytes, need);
@@ -400,6 +457,7 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     g.bias = bias; g.rowscale = rowscale; g.relu = (act == GT_ACT_RELU); g.c_bf16 = (c_dtype == GT_BF16);
     g.Cin = Cin; g.ldcin = ldcin;
     g.mask = mask; g.ldmask = ldmask;
+    g.colsum = colsum_b ? reinterpret_cast<float *>(static_cast<char *>(ws) + need_part) : nullptr;
     if (mask && p.splits > 1) return gt_fail(GT_ERR_INTERNAL, "%s: an output mask on a split reduction", fn);
     if (p.splits > 1) { g.C = ws; g.ldc = N; } else { g.C = C; g.ldc = ldc; }
     const int tr = gt_trace_open(GT_TRACE_COMBINE, N, M, M * N * K, st);
@@ -418,6 +476,10 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
         k_splitk_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(static_cast<const float *>(ws), p.splits, M, N, C,
                                                                      ldc, Cin, ldcin, bias, rowscale, g.relu, g.c_bf16);
         GT_LAUNCH_CHECK("k_splitk_reduce");
+    }
+    if (colsum_b) {
+        k_colsum_splits<<<(unsigned)((N + 255) / 256), 256, 0, st>>>(g.colsum, p.splits, N, colsum_b);
+        GT_LAUNCH_CHECK("k_colsum_splits");
     }
     return GT_OK;
 }

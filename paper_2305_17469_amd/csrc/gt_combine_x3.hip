@@ -130,6 +130,16 @@ struct LoadKM {
             }
         }
     }
+    // adds this thread's (masked) elements to cs[q][0..3]: rows 4 iq .. + 3 of patch q, summed over its four k
+    __device__ inline void add_to(float (&cs)[NPATCH][4]) const {
+#pragma unroll
+        for (int q = 0; q < NPATCH; ++q)
+#pragma unroll
+            for (int dk = 0; dk < 4; ++dk) {
+                const float4 v = mask4(r[q][dk], nv[q][dk]);
+                cs[q][0] += v.x; cs[q][1] += v.y; cs[q][2] += v.z; cs[q][3] += v.w;
+            }
+    }
     __device__ inline void store(gemm_bf16_t *lds) const {
         const int kq = threadIdx.x & 7;
 #pragma unroll
@@ -183,6 +193,14 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
     // op(A)(i,k) = TA ? A[k*lda + i] : A[i*lda + k];  op(B)(k,j) = TB ? B[j*ldb + k] : B[k*ldb + j]
     typename std::conditional<TA, LoadKM<BM>, LoadKC<BM>>::type la;
     typename std::conditional<TB, LoadKC<BN>, LoadKM<BN>>::type lb;
+    // column sums of op(B) over this workgroup's k-range, a by-product of loading B (row tile 0 only)
+    constexpr int NPB = BN > 128 ? BN / 128 : 1;
+    const bool do_cs = !TB && g.colsum && tile_m == 0;
+    float cs[NPB][4];
+#pragma unroll
+    for (int q = 0; q < NPB; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cs[q][e] = 0.0f;
     if (kbeg < kend) {
         la.load(A, g.lda, m0, kbeg, g.M, kend, VA);
         lb.load(B, g.ldb, n0, kbeg, g.N, kend, VB);
@@ -193,6 +211,9 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
         __syncthreads();
         la.store(As);
         lb.store(Bs);
+        if constexpr (!TB) {
+            if (do_cs) lb.add_to(cs);
+        }
         __syncthreads();
         if (k0 + KT < kend) {
             la.load(A, g.lda, m0, k0 + KT, g.M, kend, VA);
@@ -233,6 +254,26 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
         }
     }
     __syncthreads();   // every wavefront is done reading the operand planes
+    if constexpr (!TB) {
+        if (do_cs) {   // uniform over the workgroup
+            // thread t holds, per patch q, columns 4 ((t >> 3) + 32 q) ..; the eight threads t & 7 that share
+            // them (they loaded different k) are added in thread order
+            static_assert((size_t)256 * NPB * 4 * 4 <= x3_lds_bytes<WGM, WGN>(), "column-sum staging");
+            float *red = reinterpret_cast<float *>(smem_raw);
+#pragma unroll
+            for (int q = 0; q < NPB; ++q)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) red[(threadIdx.x * NPB + q) * 4 + e] = cs[q][e];
+            __syncthreads();
+            for (int j = threadIdx.x; j < BN; j += 256) {
+                const int iq = j >> 2, e = j & 3, q = iq >> 5, base = (iq & 31) * 8;
+                float t = 0.0f;
+                for (int kq = 0; kq < 8; ++kq) t += red[((base + kq) * NPB + q) * 4 + e];
+                if (n0 + j < g.N) g.colsum[(int64_t)blockIdx.z * g.N + n0 + j] = t;
+            }
+            __syncthreads();
+        }
+    }
     gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h,
                         reinterpret_cast<float *>(smem_raw) + wave * GEMM_STAGE_FLOATS(2));
 }

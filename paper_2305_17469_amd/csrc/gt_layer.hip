@@ -554,6 +554,7 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
     if (used) *used = order;
 
     // dZ = dY * [Y > 0], db = column sums of dZ
+    float *db_from_gemm = nullptr;
     const void *dZ = dY;
     int64_t lddz = lddy;
     float *partial = static_cast<float *>(at(scratch, L.colsum));
@@ -563,8 +564,13 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
                           : mask_colsum<bf16_t>(dY, lddy, Y, ldy, z, L.ldo, g->n_dst, fo, partial, db, st);
         dZ = z; lddz = L.ldo;
     } else if (db) {
-        s = (t == GT_F32) ? mask_colsum<float>(dY, lddy, nullptr, 0, nullptr, 0, g->n_dst, fo, partial, db, st)
-                          : mask_colsum<bf16_t>(dY, lddy, nullptr, 0, nullptr, 0, g->n_dst, fo, partial, db, st);
+        // dZ is dY as it is.  Its column sums come for free from a weight-gradient product that streams
+        // dZ as its second operand (the root term's, or (A X)^T dZ); only a combination-first forward
+        // without a root term has none, and sums dZ in a pass of its own.
+        if (d->has_root || fwd_used == GT_AGG_FIRST) db_from_gemm = db;
+        else
+            s = (t == GT_F32) ? mask_colsum<float>(dY, lddy, nullptr, 0, nullptr, 0, g->n_dst, fo, partial, db, st)
+                              : mask_colsum<bf16_t>(dY, lddy, nullptr, 0, nullptr, 0, g->n_dst, fo, partial, db, st);
     }
     if (s != GT_OK) return s;
 
@@ -573,13 +579,14 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
     if (d->has_root) {
         // dW_root = X[0:n_dst]^T dZ
         s = gt_gemm_run(fn, t, 1, 0, fi, fo, g->n_dst, X, ldx, dZ, lddz, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dW_root,
-                        fo, GT_F32, gws, L.gemm_ws_bytes, st);
+                        fo, GT_F32, gws, L.gemm_ws_bytes, st, nullptr, 0, db_from_gemm);
         if (s != GT_OK) return s;
+        db_from_gemm = nullptr;
     }
     if (fwd_used == GT_AGG_FIRST) {
         // dW = (A X)^T dZ with the saved A X
         s = gt_gemm_run(fn, t, 1, 0, fi, fo, g->n_dst, saved, L.ldi, dZ, lddz, nullptr, nullptr, GT_ACT_NONE, nullptr, 0,
-                        dW, fo, GT_F32, gws, L.gemm_ws_bytes, st);
+                        dW, fo, GT_F32, gws, L.gemm_ws_bytes, st, nullptr, 0, db_from_gemm);
         if (s != GT_OK) return s;
     }
     const bool need_S = (fwd_used == GT_COMB_FIRST) || (d->need_dx && order == GT_COMB_FIRST);
