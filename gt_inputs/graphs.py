@@ -75,9 +75,9 @@ def rmat_csr(scale: int, avg_draws: int, seed: int, self_loops: bool = True):
     return csr_from_pairs(s, d, n, n, self_loops=self_loops)
 
 
-def er_csr(scale: int, avg_draws: int, seed: int):
+def er_csr(scale: int, avg_draws: float, seed: int):
     n = 1 << scale
-    s, d = uniform_edges(n, avg_draws * n, seed)
+    s, d = uniform_edges(n, int(avg_draws * n), seed)
     return csr_from_pairs(s, d, n, n, self_loops=False)
 
 

@@ -257,6 +257,11 @@ typedef struct {
 typedef struct {
     double alpha_fwd, beta_fwd, gamma_fwd, delta_fwd;
     double alpha_bwd, beta_bwd, gamma_bwd, delta_bwd;
+    /* One addition to the paper's model: no aggregation launch is modelled faster than this many
+     * seconds (launch plus the chain of dependent loads of one work item), so that on a graph of a
+     * few thousand vertices a narrower aggregation does not count as a faster one.  Fitted by
+     * gt_calibrate like the other coefficients (the time of an aggregation on a tiny graph); 0 = none. */
+    double aggr_floor;
 } gt_cost_coeffs;
 
 gt_status gt_cost_get(gt_cost_coeffs *c /* host */);          /* the fp32 set */

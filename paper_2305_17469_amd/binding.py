@@ -38,7 +38,7 @@ class gt_layer_desc(ctypes.Structure):
 
 class gt_cost_coeffs(ctypes.Structure):
     _fields_ = [(n, c_double) for n in ("alpha_fwd", "beta_fwd", "gamma_fwd", "delta_fwd",
-                                        "alpha_bwd", "beta_bwd", "gamma_bwd", "delta_bwd")]
+                                        "alpha_bwd", "beta_bwd", "gamma_bwd", "delta_bwd", "aggr_floor")]
 
 
 class GtError(RuntimeError):

@@ -174,8 +174,34 @@ __device__ inline void store_vec<bf16_t, 1>(bf16_t *p, const float (&v)[1], int 
 }
 
 // scale, bias, activation and store of one finished output row segment
+// the mask values of this lane's segments of output row `row` (16-byte loads where the segment is whole);
+// issued early by the callers so that the load is not a dependent round trip at the end of the item
 template <typename T, int V, int G, int NP>
-__device__ inline void finish_row(const AggArgs &a, int row, int gl, int64_t col0, float (&acc)[NP][V]) {
+__device__ inline void load_mask_row(const AggArgs &a, int row, int gl, int64_t col0, float (&m)[NP][V]) {
+#pragma unroll
+    for (int p = 0; p < NP; ++p) {
+        const int64_t col = col0 + (int64_t)(p * G + gl) * V;
+#pragma unroll
+        for (int i = 0; i < V; ++i) m[p][i] = 1.0f;
+        if (col >= a.F) continue;
+        const int n = (int)((a.F - col) < V ? (a.F - col) : V);
+        const T *mp = static_cast<const T *>(a.mask) + (int64_t)row * a.ldmask + col;
+        if (n >= V) {
+            load_vec<T, V>(mp, m[p]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                float one[1] = {1.0f};
+                if (i < n) load_vec<T, 1>(mp + i, one);
+                m[p][i] = one[0];
+            }
+        }
+    }
+}
+
+template <typename T, int V, int G, int NP>
+__device__ inline void finish_row(const AggArgs &a, int row, int gl, int64_t col0, float (&acc)[NP][V],
+                                  const float (&msk)[NP][V]) {
     bool zero = false;
     float div = 1.0f;
     if (a.post_mode == 2) {
@@ -189,27 +215,14 @@ __device__ inline void finish_row(const AggArgs &a, int row, int gl, int64_t col
         const int64_t col = col0 + (int64_t)(p * G + gl) * V;
         if (col >= a.F) continue;
         const int n = (int)((a.F - col) < V ? (a.F - col) : V);
-        float o[V], m[V];
-        if (a.mask) {
-            const T *mp = static_cast<const T *>(a.mask) + (int64_t)row * a.ldmask + col;
-            if (n >= V) {
-                load_vec<T, V>(mp, m);
-            } else {
-#pragma unroll
-                for (int i = 0; i < V; ++i) {
-                    float one[1] = {0.0f};
-                    if (i < n) load_vec<T, 1>(mp + i, one);
-                    m[i] = one[0];
-                }
-            }
-        }
+        float o[V];
 #pragma unroll
         for (int i = 0; i < V; ++i) {
             float x = acc[p][i];
             if (a.post_mode == 2) x = zero ? 0.0f : x / div;
             if (a.bias && i < n) x += a.bias[col + i];
             if (a.relu) x = x > 0.0f ? x : 0.0f;
-            if (a.mask) x = m[i] > 0.0f ? x : 0.0f;
+            if (a.mask) x = msk[p][i] > 0.0f ? x : 0.0f;
             o[i] = x;
         }
         store_vec<T, V>(y + col, o, n);
@@ -244,7 +257,9 @@ static inline int agg_xcd_run(int64_t gx) {
 
 // One group of G lanes per work item; 64/G items per wavefront; 4 wavefronts per workgroup.
 // blockIdx.y selects a column tile of G*V*NP columns.
-template <typename T, int V, int G, int NP, int U, int VWM = VWM_NONE>
+// MK: an output mask is present (its values are fetched when the item starts; a separate instance so
+// that the registers they occupy during the gather cost the unmasked kernel nothing)
+template <typename T, int V, int G, int NP, int U, int VWM = VWM_NONE, bool MK = false>
 __global__ void __launch_bounds__(256) k_aggregate(const AggArgs a) {
     constexpr int NG = 64 / G;
     const int lane = threadIdx.x & 63;
@@ -275,6 +290,14 @@ __global__ void __launch_bounds__(256) k_aggregate(const AggArgs a) {
     for (int p = 0; p < NP; ++p)
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[p][i] = 0.0f;
+    float msk[NP][V];
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+        for (int i = 0; i < V; ++i) msk[p][i] = 1.0f;
+    if constexpr (MK) {
+        if (slot < 0) load_mask_row<T, V, G, NP>(a, row, gl, col0, msk);   // needed only when the row is finished here
+    }
 
     typedef typename Raw<T, V>::type raw_t;
     // The group fetches G neighbour ids and coefficients with one coalesced load and walks them;
@@ -352,7 +375,7 @@ __global__ void __launch_bounds__(256) k_aggregate(const AggArgs a) {
                 if (col + i < a.F) P[col + i] = acc[p][i];
         }
     } else {
-        finish_row<T, V, G, NP>(a, row, gl, col0, acc);
+        finish_row<T, V, G, NP>(a, row, gl, col0, acc, msk);
     }
 }
 
@@ -373,6 +396,12 @@ __global__ void __launch_bounds__(256) k_reduce_partials(const AggArgs a) {
     for (int p = 0; p < NP; ++p)
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[p][i] = 0.0f;
+    float msk[NP][V];
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+        for (int i = 0; i < V; ++i) msk[p][i] = 1.0f;
+    if (a.mask) load_mask_row<T, V, G, NP>(a, s.row, gl, col0, msk);
     // Four partial rows are requested at a time (branch free: a request past the end re-reads the
     // last row and is discarded) and added in chunk order.  Partial rows are padded to a multiple
     // of 8 floats, so whole vectors can be read; padding lanes are never stored.
@@ -407,7 +436,7 @@ __global__ void __launch_bounds__(256) k_reduce_partials(const AggArgs a) {
                 for (int i = 0; i < V; ++i) acc[p][i] += live ? t[u][p][i] : 0.0f;
         }
     }
-    finish_row<T, V, G, NP>(a, s.row, gl, col0, acc);
+    finish_row<T, V, G, NP>(a, s.row, gl, col0, acc, msk);
 }
 
 template <typename T, int V, int G, int NP, int U, int VWM = VWM_NONE>
@@ -421,7 +450,12 @@ gt_status launch(const AggArgs &a, hipStream_t st) {
         b.xcd_run = agg_xcd_run(gx);
         const int tr = gt_trace_open(a.trace_kind, a.F, a.n_rows, a.n_edges, st);
         gt_trace_variant(tr, V, G, NP, U);
-        k_aggregate<T, V, G, NP, U, VWM><<<dim3((unsigned)gx, gy), 256, 0, st>>>(b);
+        if constexpr (VWM == VWM_NONE) {
+            if (b.mask) k_aggregate<T, V, G, NP, U, VWM, true><<<dim3((unsigned)gx, gy), 256, 0, st>>>(b);
+            else k_aggregate<T, V, G, NP, U, VWM, false><<<dim3((unsigned)gx, gy), 256, 0, st>>>(b);
+        } else {
+            k_aggregate<T, V, G, NP, U, VWM, false><<<dim3((unsigned)gx, gy), 256, 0, st>>>(b);
+        }
         gt_trace_close(tr, st);
         GT_LAUNCH_CHECK("k_aggregate");
     }

@@ -5,7 +5,10 @@
 // The measurements are synthetic: a regular random graph and dense matrices built inside the
 // caller's workspace.  Each kernel-time model has two unknowns,
 //     t_aggr = gamma * (F * E) + delta * (F * n_out),    t_comb = alpha * (rows*in*out) + beta * (rows*width),
-// and is fitted through the 2x2 normal equations of its samples.
+// and is fitted through the 2x2 normal equations of its samples.  The backward combination
+// samples are the two products a backward pass runs: dZ W^T and the weight gradient X^T dZ
+// (reduction over the rows).  The floor of an aggregation's time is measured directly: the time
+// per launch of a narrow aggregation on a graph of 1,024 vertices, back to back on the stream.
 #include <math.h>
 
 #include "gt_internal.h"
@@ -123,7 +126,8 @@ extern "C" gt_status gt_calibrate_dtype(gt_dtype dtype, void *ws, size_t ws_byte
     GT_LAUNCH_CHECK("k_cal_fill");
 
     Fit2 agg_f, agg_b, gemm_f, gemm_b;
-    const int64_t degs[2] = {8, CAL_DMAX};
+    // rows of 2, 8 and 32 entries: the per-row term (delta) is what a graph of very short rows is bound by
+    const int64_t degs[3] = {2, 8, CAL_DMAX};
     const int64_t widths[3] = {32, 128, 256};
     for (int64_t d : degs) {
         const int64_t E = CAL_N * d;
@@ -157,8 +161,35 @@ extern "C" gt_status gt_calibrate_dtype(gt_dtype dtype, void *ws, size_t ws_byte
                                              GT_ACT_NONE, nullptr, 0, X, CAL_FMAX, dtype, nullptr, 0, st); }, st, &t);
         if (s != GT_OK) return s;
         gemm_b.add((double)CAL_N * in * out, (double)CAL_N * in, t);
+        // the weight gradient X^T dZ: [in, out] fp32 over CAL_N rows, split over workgroups (partials in agg_ws)
+        s = time_it([&] { return gt_gemm_run("gt_calibrate", dtype, 1, 0, in, out, CAL_N, X, CAL_FMAX, Y, CAL_FMAX, nullptr,
+                                             nullptr, GT_ACT_NONE, nullptr, 0, Wf, out, GT_F32, base + L.agg_ws,
+                                             (size_t)64 << 20, st); }, st, &t);
+        if (s != GT_OK) return s;
+        gemm_b.add((double)CAL_N * in * out, (double)CAL_N * in, t);
+    }
+    // floor of an aggregation launch: 1,024 vertices, 8 neighbours each, 16 columns
+    double floor_s = 0.0;
+    {
+        const int64_t n = 1024, d = 8, E = n * d;
+        k_cal_graph<<<(unsigned)((E + 256) / 256), 256, 0, st>>>(rowptr, colidx, n, d);
+        GT_LAUNCH_CHECK("k_cal_graph");
+        gt_graph *g = nullptr;
+        s = gt_graph_create(&g, n, n, E, rowptr, colidx, nullptr, base + L.plan, L.plan_bytes, st);
+        if (s != GT_OK) return s;
+        double best = 1e30;
+        for (int rep = 0; rep < 3 && s == GT_OK; ++rep) {   // the smallest of three: launch jitter only adds
+            double t = 0;
+            s = time_it([&] { return gt_aggregate_run(g, false, GT_SUM, dtype, dtype, 16, X, CAL_FMAX, Y, CAL_FMAX, nullptr,
+                                                      GT_ACT_NONE, base + L.agg_ws, (size_t)64 << 20, st); }, st, &t);
+            if (t < best) best = t;
+        }
+        gt_graph_destroy(g);
+        if (s != GT_OK) return s;
+        floor_s = best < 1e-6 ? 1e-6 : (best > 2e-5 ? 2e-5 : best);
     }
     gt_cost_coeffs c;
+    c.aggr_floor = floor_s;
     gemm_f.solve(&c.alpha_fwd, &c.beta_fwd);
     gemm_b.solve(&c.alpha_bwd, &c.beta_bwd);
     agg_f.solve(&c.gamma_fwd, &c.delta_fwd);

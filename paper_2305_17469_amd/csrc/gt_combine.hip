@@ -310,6 +310,44 @@ __global__ void __launch_bounds__(256) k_splitk_reduce(const float *P, int split
     else static_cast<float *>(C)[row * ldc + col] = v;
 }
 
+// The same for many splits: eight lanes per output element, lane l adds the partials l, l + 8, ... (four
+// loads in flight), the eight sums are then added in lane order.  A fixed order again, and the chain of
+// dependent additions is an eighth as long (256 splits of a 64 x 64 output: one thread per element
+// walked 32 rounds of loads one after the other).
+__global__ void __launch_bounds__(256) k_splitk_reduce8(const float *P, int splits, int64_t M, int64_t N, void *C,
+                                                        int64_t ldc, const void *Cin, int64_t ldcin, const float *bias,
+                                                        const float *rowscale, int relu, int c_bf16) {
+    const int l = threadIdx.x & 7;
+    const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 3;
+    const bool live = idx < M * N;
+    const int64_t stride = M * N;
+    float v = 0.0f;
+    if (live) {
+        int z = l;
+        for (; z + 24 < splits; z += 32) {
+            float t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t[u] = P[(int64_t)(z + 8 * u) * stride + idx];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v += t[u];
+        }
+        for (; z < splits; z += 8) v += P[(int64_t)z * stride + idx];
+    }
+    float tot = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) tot += __shfl(v, k, 8);
+    if (!live || l != 0) return;
+    const int64_t row = idx / N, col = idx % N;
+    v = tot;
+    if (rowscale) v *= rowscale[row];
+    if (Cin) v += c_bf16 ? bf16_to_f32(static_cast<const bf16_t *>(Cin)[row * ldcin + col])
+                         : static_cast<const float *>(Cin)[row * ldcin + col];
+    if (bias) v += bias[col];
+    if (relu) v = v > 0.0f ? v : 0.0f;
+    if (c_bf16) static_cast<bf16_t *>(C)[row * ldc + col] = (bf16_t)f32_to_bf16(v);
+    else static_cast<float *>(C)[row * ldc + col] = v;
+}
+
 // Workgroup tile.  Products with little work and so few 256- or 128-row tiles that most compute
 // units would idle (the layers of a sampled batch: a thousand rows, a 256 x 47 weight gradient) use
 // 64 x 64 tiles, one MFMA block per wavefront, and cut the reduction finer; they are bound by the
@@ -413,13 +451,23 @@ size_t gt_gemm_ws_bytes(int transA, int64_t M, int64_t N, int64_t K) {
            (transA ? gt_align_up((size_t)splits * (size_t)N * 4) : 0);
 }
 
-// out[c] = sum over the splits' column sums, in split order
+// out[c] = sum over the splits' column sums: 4 columns per workgroup, 64 lanes per column stride over
+// the splits, the lanes' sums are added in lane order (fixed order; a single thread per column walking
+// a few hundred splits one after the other took 0.1 ms)
 __global__ void __launch_bounds__(256) k_colsum_splits(const float *partial, int splits, int64_t cols, float *out) {
-    const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (c >= cols) return;
-    float t = 0.0f;
-    for (int z = 0; z < splits; ++z) t += partial[(int64_t)z * cols + c];
-    out[c] = t;
+    __shared__ float red[256];
+    const int cl = threadIdx.x & 3, rl = threadIdx.x >> 2;
+    const int64_t c = (int64_t)blockIdx.x * 4 + cl;
+    float s = 0.0f;
+    if (c < cols)
+        for (int z = rl; z < splits; z += 64) s += partial[(int64_t)z * cols + c];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (rl == 0 && c < cols) {
+        float t = 0.0f;
+        for (int k = 0; k < 64; ++k) t += red[k * 4 + cl];
+        out[c] = t;
+    }
 }
 
 gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
@@ -473,12 +521,17 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     if (s != GT_OK) return s;
     if (p.splits > 1) {
         const int64_t n = M * N;
-        k_splitk_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(static_cast<const float *>(ws), p.splits, M, N, C,
-                                                                     ldc, Cin, ldcin, bias, rowscale, g.relu, g.c_bf16);
+        if (p.splits >= 64)
+            k_splitk_reduce8<<<(unsigned)((n * 8 + 255) / 256), 256, 0, st>>>(static_cast<const float *>(ws), p.splits, M, N,
+                                                                            C, ldc, Cin, ldcin, bias, rowscale, g.relu,
+                                                                            g.c_bf16);
+        else
+            k_splitk_reduce<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(static_cast<const float *>(ws), p.splits, M, N, C,
+                                                                         ldc, Cin, ldcin, bias, rowscale, g.relu, g.c_bf16);
         GT_LAUNCH_CHECK("k_splitk_reduce");
     }
     if (colsum_b) {
-        k_colsum_splits<<<(unsigned)((N + 255) / 256), 256, 0, st>>>(g.colsum, p.splits, N, colsum_b);
+        k_colsum_splits<<<(unsigned)((N + 3) / 4), 256, 0, st>>>(g.colsum, p.splits, N, colsum_b);
         GT_LAUNCH_CHECK("k_colsum_splits");
     }
     return GT_OK;

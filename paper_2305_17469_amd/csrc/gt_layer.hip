@@ -26,23 +26,23 @@ typedef uint16_t bf16_t;
 // Coefficients in seconds, one set per data type (index: gt_dtype).  Defaults are the values
 // gt_calibrate fitted on an MI355X; gt_calibrate replaces them with values fitted on the device
 // at hand.
-gt_cost_coeffs g_cost[2] = {{1.1e-14, 1.3e-12, 4.9e-13, 9.2e-13, 1.07e-14, 1.25e-12, 4.5e-13, 1.3e-12},
-                            {7.4e-15, 1.28e-12, 2.3e-13, 7.2e-13, 3.6e-15, 9.2e-13, 1.9e-13, 1.14e-12}};
+gt_cost_coeffs g_cost[2] = {{1.12e-14, 1.25e-12, 4.89e-13, 1.04e-12, 9.1e-15, 1.58e-12, 4.49e-13, 1.26e-12, 4.2e-6},
+                            {7.85e-15, 9.95e-13, 2.33e-13, 7.3e-13, 4.05e-15, 1.0e-12, 1.94e-13, 1.03e-12, 4.6e-6}};
 const gt_cost_coeffs &cost_of(gt_dtype t) { return g_cost[t == GT_BF16 ? 1 : 0]; }
 
 // An aggregation launch cannot finish faster than the chain of dependent loads of one work item
 // (descriptor, neighbour ids, rows, a chunk of them for a hub row) however narrow the rows are:
-// below this floor a narrower aggregation is not a faster one, so the model must not prefer it.
-// (4,096-vertex graph, 64 -> 16: both orders measure the same within launch jitter; without the
-// floor the model picked the order that measured 9 % slower.)
-constexpr double GT_AGGR_FLOOR_S = 4e-6;
+// below the floor `aggr_floor` a narrower aggregation is not a faster one, so the model must not
+// prefer it.  (4,096-vertex graph, 64 -> 16: both orders measure the same within launch jitter;
+// without the floor the model picked the order that measured 9 % slower.)  The floor is fitted
+// with the other coefficients (gt_calibrate times an aggregation on a tiny graph).
 
 double t_comb(const gt_cost_coeffs &c, bool bwd, double rows, double in, double out) {
     return bwd ? rows * (c.alpha_bwd * in * out + c.beta_bwd * in) : rows * (c.alpha_fwd * in * out + c.beta_fwd * out);
 }
 double t_aggr(const gt_cost_coeffs &c, bool bwd, double E, double n_out, double F) {
     const double t = bwd ? F * (c.gamma_bwd * E + c.delta_bwd * n_out) : F * (c.gamma_fwd * E + c.delta_fwd * n_out);
-    return t > GT_AGGR_FLOOR_S ? t : GT_AGGR_FLOOR_S;
+    return t > c.aggr_floor ? t : c.aggr_floor;
 }
 
 __device__ inline float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
@@ -367,8 +367,8 @@ gt_status mask_colsum(const void *dY, int64_t lddy, const void *Y, int64_t ldy, 
 
 static gt_status check_coeffs(const char *fn, const gt_cost_coeffs *c) {
     if (!c) return gt_fail(GT_ERR_INVALID_ARG, "%s: null", fn);
-    const double v[8] = {c->alpha_fwd, c->beta_fwd, c->gamma_fwd, c->delta_fwd,
-                         c->alpha_bwd, c->beta_bwd, c->gamma_bwd, c->delta_bwd};
+    const double v[9] = {c->alpha_fwd, c->beta_fwd, c->gamma_fwd, c->delta_fwd,
+                         c->alpha_bwd, c->beta_bwd, c->gamma_bwd, c->delta_bwd, c->aggr_floor};
     for (double x : v)
         if (!(x >= 0.0) || !isfinite(x)) return gt_fail(GT_ERR_INVALID_ARG, "%s: coefficients must be finite and >= 0", fn);
     return GT_OK;

@@ -91,12 +91,13 @@ def test_cost_set_get_roundtrip_and_validation():
         c = B.gt_cost_coeffs(1, 2, 3, 4, 5, 6, 7, 8)
         B.gt_cost_set(c)                                   # installs the set for every data type
         for g in (B.gt_cost_get(), B.gt_cost_get_dtype("f32"), B.gt_cost_get_dtype("bf16")):
-            assert [getattr(g, f[0]) for f in g._fields_] == [1, 2, 3, 4, 5, 6, 7, 8]
-        B.gt_cost_set_dtype("bf16", B.gt_cost_coeffs(8, 7, 6, 5, 4, 3, 2, 1))   # one data type only
+            assert [getattr(g, f[0]) for f in g._fields_] == [1, 2, 3, 4, 5, 6, 7, 8, 0]
+        B.gt_cost_set_dtype("bf16", B.gt_cost_coeffs(8, 7, 6, 5, 4, 3, 2, 1, 3e-6))   # one data type only
         g = B.gt_cost_get_dtype("bf16")
-        assert [getattr(g, f[0]) for f in g._fields_] == [8, 7, 6, 5, 4, 3, 2, 1]
+        assert [getattr(g, f[0]) for f in g._fields_] == [8, 7, 6, 5, 4, 3, 2, 1, 3e-6]
         g = B.gt_cost_get()
-        assert [getattr(g, f[0]) for f in g._fields_] == [1, 2, 3, 4, 5, 6, 7, 8]
+        assert [getattr(g, f[0]) for f in g._fields_] == [1, 2, 3, 4, 5, 6, 7, 8, 0]
+        assert B.lib.gt_cost_set(byref(B.gt_cost_coeffs(1, 2, 3, 4, 5, 6, 7, 8, -1e-6))) == 1   # negative floor
         bad = B.gt_cost_coeffs(-1, 2, 3, 4, 5, 6, 7, 8)
         assert B.lib.gt_cost_set(byref(bad)) == 1
         assert B.lib.gt_cost_set_dtype(1, byref(bad)) == 1

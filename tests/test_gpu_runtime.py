@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from gt_inputs import configs
-from gpu_util import announce, up_feat, up_i32
+from gpu_util import announce, pad_to, up_feat, up_i32
 
 pytestmark = pytest.mark.gpu
 
@@ -42,6 +42,8 @@ def test_calibrate_fits_positive_coefficients_and_keeps_decisions():
             assert vals["gamma_fwd"] > 0 and vals["gamma_bwd"] > 0 and vals["alpha_fwd"] > 0 and vals["alpha_bwd"] > 0
             # a gather of one feature takes between 0.05 and 50 ps on this class of device
             assert 5e-14 < vals["gamma_fwd"] < 5e-11 and 5e-14 < vals["gamma_bwd"] < 5e-11
+            # the floor of an aggregation launch: a few microseconds
+            assert 1e-6 <= vals["aggr_floor"] <= 2e-5
         # bf16 rows are half as long: gathering one feature must not cost more than in fp32
         assert fitted["bf16"].gamma_fwd <= 1.1 * fitted["f32"].gamma_fwd
         one = B.gt_calibrate_dtype("bf16")         # one data type alone leaves the other set untouched
@@ -138,3 +140,53 @@ def test_weight_stationary_combination_replays_from_a_captured_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out, ref), rep
+
+
+def _time_step(m, X, G, fo, bo, reps=6):
+    for _ in range(2):
+        m.step(X, G, fo, bo)
+    torch.cuda.synchronize()
+    best = float("inf")
+    for _ in range(3):                            # best of three timed groups: box noise only adds
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            m.step(X, G, fo, bo)
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1) / reps)
+    return best
+
+
+@pytest.mark.parametrize("which", ["c2_scale16", "c5a_scale18", "c5b_scale18", "c6a"])
+def test_auto_placement_is_the_measured_faster_order(which):
+    """Dynamic kernel placement under test: for every layer, both placements (aggregation-first and
+    combination-first, forward and backward alike) are forced and timed; where they differ by more
+    than 20 % AUTO must have picked the faster one (paper: the placement is chosen from the cost
+    model so that the cheaper order runs)."""
+    from paper_2305_17469_amd import binding as B
+    cfg = {"c2_scale16": lambda: configs.reddit_like(16), "c5a_scale18": lambda: configs.reorder_stress(18, True, "sum"),
+           "c5b_scale18": lambda: configs.reorder_stress(18, False, "sum"), "c6a": lambda: configs.paper_batch("light")}[which]()
+    dev = torch.device("cuda:0")
+    announce("placement under test:", cfg["name"])
+    m = _stack(cfg, dev)
+    dt = cfg["dtype"]
+    X, G = up_feat(cfg["X"], dt, pad_to(cfg["dims"][0], dt)), up_feat(cfg["G"], dt, pad_to(cfg["dims"][-1], dt))
+    m.step(X, G)
+    auto_f, auto_b = list(m.used_fwd), list(m.used_bwd)
+    decided = 0
+    for l in range(m.L):
+        t = {}
+        for o in ("agg_first", "comb_first"):
+            fo, bo = list(auto_f), list(auto_b)
+            fo[l], bo[l] = o, o
+            t[o] = _time_step(m, X, G, fo, bo)
+        fast = min(t, key=t.get)
+        slow = max(t, key=t.get)
+        print(cfg["name"], "layer", l, cfg["dims"][l], "->", cfg["dims"][l + 1], t, "auto", auto_f[l], auto_b[l])
+        if t[slow] > 1.2 * t[fast]:
+            decided += 1
+            assert auto_f[l] == fast, (cfg["name"], l, t, auto_f[l])
+            if l > 0:
+                assert auto_b[l] == fast, (cfg["name"], l, t, auto_b[l])
+    assert decided >= 1, "no layer of this workload separates the two orders by 20 %"
