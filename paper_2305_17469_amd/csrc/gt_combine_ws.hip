@@ -176,6 +176,16 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
     const int l32 = lane & 31, h = lane >> 5;
 #pragma unroll
     for (int bp = 0; bp < NB / 2; ++bp) {
+        uint4 mkv[4];
+        if (EX && g.mask) {   // requested before the staging below, so that the round trip overlaps it
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                int64_t row = row0 + it * 8 + (lane >> 3);
+                if (row >= g.M) row = g.M - 1;
+                mkv[it] = *reinterpret_cast<const uint4 *>(static_cast<const gemm_bf16_t *>(g.mask) + row * g.ldmask + n0 +
+                                                          bp * 64 + (lane & 7) * 8);
+            }
+        }
         __asm__ volatile("" ::: "memory");
 #pragma unroll
         for (int bb = 0; bb < 2; ++bb) {
@@ -200,8 +210,7 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
             int64_t row = row0 + rr;
             if (row >= g.M) row = g.M - 1;
             if (EX && g.mask) {
-                const uint4 mk = *reinterpret_cast<const uint4 *>(static_cast<const gemm_bf16_t *>(g.mask) + row * g.ldmask + n0 +
-                                                                 bp * 64 + (lane & 7) * 8);
+                const uint4 mk = mkv[it];
                 v.x = ws_mask_pair(v.x, mk.x); v.y = ws_mask_pair(v.y, mk.y);
                 v.z = ws_mask_pair(v.z, mk.z); v.w = ws_mask_pair(v.w, mk.w);
             }
