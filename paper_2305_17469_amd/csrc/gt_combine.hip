@@ -283,6 +283,163 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
                           reinterpret_cast<float *>(smem) + wave * GEMM_STAGE_FLOATS(TN));
 }
 
+// bf16 weight gradient  C[M, N] (+)= A^T B  with A stored [K][lda] (m contiguous) and B stored [K][ldb]
+// (n contiguous): both operands are k-major in memory, while an MFMA fragment wants eight consecutive
+// k of one row.  The general kernel above leaves the tiles k-major in LDS and builds every fragment
+// from eight 2-byte LDS reads; here a thread loads a 4 (k) x 8 (row) patch (four 16-byte loads),
+// transposes it in registers and writes eight 8-byte k-runs, so the tiles sit in LDS as [row][k] and a
+// fragment is one 16-byte read (a quarter of the LDS instructions; measured on MI355X, 256 x 256 over
+// 2^21 rows: see the design notes).  128 x 128 workgroup tile, 4 wavefronts of 64 x 64, k-tile 32:
+// threads 0..127 load the A tile, 128..255 the B tile.  Split over k like k_gemm (partials in g.C when
+// gridDim.z > 1), same epilogue, same column-sum by-product.
+__device__ inline uint32_t tn_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }   // lo16(a) | lo16(b) << 16
+__device__ inline uint32_t tn_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }   // hi16(a) | hi16(b) << 16
+
+// BIG = false: 128 x 128 tile, 4 wavefronts of 64 x 64.  BIG = true: ONE 256 x 256 tile per workgroup, i.e.
+// the whole output of a layer of up to 256 x 256 weights, 8 wavefronts of 64 x 128, one workgroup per
+// k-range: every element of A and B is then read from memory exactly once (with 128 x 128 tiles each
+// is read by two workgroups, on different XCDs, and the product is bound by those reads).
+template <bool BIG>
+__global__ void __launch_bounds__(BIG ? 512 : 256) k_gemm_tn_bf16(const GemmArgs g) {
+    constexpr int KT = 32, STR = KT + 8, BM = BIG ? 256 : 128, BN = BM, NT = BIG ? 512 : 256, HALF = NT / 2;
+    constexpr int WN = BIG ? 4 : 2;                                  // 32-column MFMA blocks per wavefront
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // max(tiles, output stages): see tn_lds_bytes
+    bf16_t *As = reinterpret_cast<bf16_t *>(smem);
+    bf16_t *Bs = As + BM * STR;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+    int tile_m, tile_n;
+    if (!gemm_tile_of_block(g, tile_m, tile_n)) return;
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+    const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
+    const int64_t kend = (kbeg + g.k_per_split < g.K) ? kbeg + g.k_per_split : g.K;
+
+    // this thread's patch: operand (first half of the threads: A, second half: B), k-group (4 k), row
+    // group (8 rows of the tile)
+    const bool isB = threadIdx.x >= HALF;
+    const int t = threadIdx.x & (HALF - 1), kq = t & 7, rq = t >> 3;
+    const bf16_t *P = static_cast<const bf16_t *>(isB ? g.B : g.A);
+    const int64_t ld = isB ? g.ldb : g.lda;
+    const int64_t c0 = (isB ? n0 : m0) + rq * 8;              // first row (column of the stored matrix) of the patch
+    const int64_t clim = isB ? g.N : g.M;
+    const int nv = c0 >= clim ? 0 : (int)((clim - c0) < 8 ? (clim - c0) : 8);
+    bf16_t *dst = (isB ? Bs : As) + rq * 8 * STR + kq * 4;
+
+    floatx16 acc[2][WN];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < WN; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
+    const bool do_cs = g.colsum && tile_m == 0 && isB;
+    float cs[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cs[e] = 0.0f;
+
+    // One register stage: the loads of the next k-tile are in flight while a tile is multiplied.  (A second
+    // stage pushed the 256 x 256 form, whose accumulators alone take 128 registers, into scratch memory:
+    // 0.52 -> 5.3 ms.)
+    uint4 r[1][4];
+    bool rok[1][4];
+    auto fetch = [&](uint4 (&rr)[4], bool (&ok)[4], int64_t k0) {
+#pragma unroll
+        for (int dk = 0; dk < 4; ++dk) {
+            const int64_t k = k0 + kq * 4 + dk;
+            ok[dk] = k < kend && nv > 0;
+            rr[dk] = *reinterpret_cast<const uint4 *>(P + (ok[dk] ? k * ld + c0 : 0));   // branch free: masked at the store
+        }
+    };
+    auto consume = [&](const uint4 (&rr)[4], const bool (&ok)[4]) {   // registers -> LDS, transposed
+        uint32_t w[4][4];
+#pragma unroll
+        for (int dk = 0; dk < 4; ++dk) {
+            uint4 v = rr[dk];
+            const int n = ok[dk] ? nv : 0;
+            v.x &= n >= 2 ? 0xffffffffu : (n == 1 ? 0x0000ffffu : 0u);
+            v.y &= n >= 4 ? 0xffffffffu : (n == 3 ? 0x0000ffffu : 0u);
+            v.z &= n >= 6 ? 0xffffffffu : (n == 5 ? 0x0000ffffu : 0u);
+            v.w &= n >= 8 ? 0xffffffffu : (n == 7 ? 0x0000ffffu : 0u);
+            w[dk][0] = v.x; w[dk][1] = v.y; w[dk][2] = v.z; w[dk][3] = v.w;
+        }
+        if (do_cs) {
+#pragma unroll
+            for (int dk = 0; dk < 4; ++dk)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    cs[2 * c] += __uint_as_float(w[dk][c] << 16);
+                    cs[2 * c + 1] += __uint_as_float(w[dk][c] & 0xffff0000u);
+                }
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {   // rows 2c and 2c + 1 of the patch: their four k as one 8-byte run each
+            *reinterpret_cast<uint2 *>(dst + (2 * c) * STR) = make_uint2(tn_lo(w[0][c], w[1][c]), tn_lo(w[2][c], w[3][c]));
+            *reinterpret_cast<uint2 *>(dst + (2 * c + 1) * STR) = make_uint2(tn_hi(w[0][c], w[1][c]), tn_hi(w[2][c], w[3][c]));
+        }
+    };
+    auto multiply = [&]() {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            const int kk = s * 16 + h * 8;   // lane half h supplies k = kk .. kk + 7 of this step
+            bf16x8 af[2], bfr[WN];
+#pragma unroll
+            for (int a = 0; a < 2; ++a) af[a] = *reinterpret_cast<const bf16x8 *>(&As[((wm * 2 + a) * 32 + l32) * STR + kk]);
+#pragma unroll
+            for (int b = 0; b < WN; ++b) bfr[b] = *reinterpret_cast<const bf16x8 *>(&Bs[((wn * WN + b) * 32 + l32) * STR + kk]);
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < WN; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+        }
+    };
+    if (kbeg < kend) fetch(r[0], rok[0], kbeg);
+    for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
+        __syncthreads();   // previous tile fully consumed
+        consume(r[0], rok[0]);
+        __syncthreads();
+        if (k0 + KT < kend) fetch(r[0], rok[0], k0 + KT);
+        multiply();
+    }
+    __syncthreads();   // every wavefront is done reading the operand tiles
+    if (g.colsum && tile_m == 0) {   // uniform over the workgroup
+        // B thread (rq, kq) holds columns 8 rq .. + 7; the eight k-groups that share them are added in order
+        float *red = reinterpret_cast<float *>(smem);
+        if (isB) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) red[t * 8 + e] = cs[e];
+        }
+        __syncthreads();
+        if (threadIdx.x < BN) {
+            const int q = threadIdx.x >> 3, e = threadIdx.x & 7;
+            float sum = 0.0f;
+            for (int k = 0; k < 8; ++k) sum += red[((q << 3) + k) * 8 + e];
+            if (n0 + threadIdx.x < g.N) g.colsum[(int64_t)blockIdx.z * g.N + n0 + threadIdx.x] = sum;
+        }
+        __syncthreads();
+    }
+    float *stage = reinterpret_cast<float *>(smem) + wave * GEMM_STAGE_FLOATS(2);
+    if constexpr (!BIG) {
+        gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h, stage);
+    } else {   // 64 x 128 per wavefront, written as two 64 x 64 halves through the same stage
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            floatx16 part[2][2];
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b) part[a][b] = acc[a][half * 2 + b];
+            gemm_epilogue<2, 2>(g, part, m0 + wm * 64, n0 + wn * 128 + half * 64, l32, h, stage);
+        }
+    }
+}
+template <bool BIG>
+constexpr size_t tn_lds_bytes() {
+    constexpr size_t tiles = (size_t)(BIG ? 512 : 256) * 40 * 2, stages = (size_t)(BIG ? 8 : 4) * GEMM_STAGE_FLOATS(2) * 4;
+    return tiles > stages ? tiles : stages;
+}
+
 // C = act(sum_z P[z] + C_in + bias), partials added in z order
 __global__ void __launch_bounds__(256) k_splitk_reduce(const float *P, int splits, int64_t M, int64_t N, void *C,
                                                        int64_t ldc, const void *Cin, int64_t ldcin, const float *bias,
@@ -378,9 +535,26 @@ bool use_x3(gt_dtype dtype, int transA, int64_t M, int64_t N, int64_t K) {
 
 struct SplitPlan { int splits; int64_t k_per_split; };
 
-SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K, bool x3) {
+// bf16 weight gradients of up to 256 x 256 outputs over a long reduction: one 256 x 256 tile per workgroup
+// (k_gemm_tn_bf16<true>), one workgroup per CU
+bool tn256_shape(int transA, int transB, int64_t M, int64_t N, int64_t K) {
+    return transA && !transB && M > 64 && M <= 256 && N > 64 && N <= 256 && K >= 8192 &&
+           (double)M * (double)N * (double)K >= 268435456.0;
+}
+
+SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K, bool x3, bool tn256 = false) {
     TileShape t = pick_tile(M, N, K);
     if (x3) { gt_gemm_x3_tile(M, N, &t.bm, &t.bn); t.small = false; }
+    if (tn256) {
+        SplitPlan p{1, (K + KT - 1) / KT * KT};
+        int64_t want = 256, max_by_len = K / (4 * KT);
+        if (want > max_by_len) want = max_by_len;
+        if (want < 1) want = 1;
+        const int64_t kps = ((K + want - 1) / want + KT - 1) / KT * KT;
+        p.splits = (int)((K + kps - 1) / kps);
+        p.k_per_split = kps;
+        return p;
+    }
     const int64_t tiles = ((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
     SplitPlan p{1, (K + KT - 1) / KT * KT};
     if (K <= 0) { p.k_per_split = KT; return p; }
@@ -415,6 +589,14 @@ gt_status launch_gemm(GemmArgs g, int splits, hipStream_t st) {
     g.ntn = (int)((g.N + bn - 1) / bn);
     g.ntm = (int)((g.M + bm - 1) / bm);
     dim3 grid(gemm_grid_x(g.ntm, g.ntn), 1, (unsigned)splits);
+    if constexpr (sizeof(T) == 2 && TA && !TB) {
+        // the weight-gradient shape in bf16 with 128 x 128 tiles: transposing loads (see k_gemm_tn_bf16)
+        if (!t.small && bn == 128 && g.vecA && g.vecB) {
+            k_gemm_tn_bf16<false><<<grid, 256, tn_lds_bytes<false>(), st>>>(g);
+            GT_LAUNCH_CHECK("k_gemm_tn_bf16");
+            return GT_OK;
+        }
+    }
 #define GT_GEMM_CFG(VA_, VB_)                                                                         \
     do {                                                                                             \
         if (t.small) k_gemm<T, TA, TB, 2, 2, 1, 1, VA_, VB_><<<grid, 256, 0, st>>>(g);               \
@@ -428,6 +610,16 @@ gt_status launch_gemm(GemmArgs g, int splits, hipStream_t st) {
     else GT_GEMM_CFG(false, false);
 #undef GT_GEMM_CFG
     GT_LAUNCH_CHECK("k_gemm");
+    return GT_OK;
+}
+
+gt_status launch_tn256(GemmArgs g, int splits, hipStream_t st) {
+    g.ntm = 1; g.ntn = 1;
+    constexpr size_t lds = tn_lds_bytes<true>();
+    GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_tn_bf16<true>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    k_gemm_tn_bf16<true><<<dim3(1, 1, (unsigned)splits), 512, lds, st>>>(g);
+    GT_LAUNCH_CHECK("k_gemm_tn_bf16");
     return GT_OK;
 }
 
@@ -445,7 +637,11 @@ gt_status launch_gemm_t(const GemmArgs &g, int transA, int transB, int splits, h
 size_t gt_gemm_ws_bytes(int transA, int64_t M, int64_t N, int64_t K) {
     const SplitPlan p = plan_split(transA, M, N, K, false);
     const SplitPlan q = plan_split(transA, M, N, K, use_x3(GT_F32, transA, M, N, K));
-    const int splits = p.splits > q.splits ? p.splits : q.splits;
+    int splits = p.splits > q.splits ? p.splits : q.splits;
+    if (tn256_shape(transA, 0, M, N, K)) {
+        const SplitPlan r = plan_split(transA, M, N, K, false, true);
+        if (r.splits > splits) splits = r.splits;
+    }
     // partial tiles of a split reduction, plus (weight-gradient shape) room for the column sums of B per split
     return (splits > 1 ? gt_align_up((size_t)splits * (size_t)M * (size_t)N * 4) : 0) +
            (transA ? gt_align_up((size_t)splits * (size_t)N * 4) : 0);
@@ -487,7 +683,10 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     if (((uintptr_t)A % es) || ((uintptr_t)B % es) || ((uintptr_t)C % cs) || ((uintptr_t)Cin % cs))
         return gt_fail(GT_ERR_INVALID_ARG, "%s: pointer misaligned for dtype", fn);
     const bool x3 = use_x3(dtype, transA, M, N, K);
-    const SplitPlan p = plan_split(transA, M, N, K, x3);
+    const int ve0 = dtype == GT_BF16 ? 8 : 4;
+    const bool tn256 = dtype == GT_BF16 && tn256_shape(transA, transB, M, N, K) && ((uintptr_t)A & 15) == 0 &&
+                       ((uintptr_t)B & 15) == 0 && lda % ve0 == 0 && ldb % ve0 == 0;
+    const SplitPlan p = plan_split(transA, M, N, K, x3, tn256);
     if (colsum_b && (!transA || transB)) return gt_fail(GT_ERR_INTERNAL, "%s: column sums of B need the A^T B shape", fn);
     const size_t need_part = p.splits > 1 ? gt_align_up((size_t)p.splits * (size_t)M * (size_t)N * 4) : 0;
     const size_t need = need_part + (colsum_b ? gt_align_up((size_t)p.splits * (size_t)N * 4) : 0);
@@ -514,6 +713,7 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     const bool ws_path = p.splits == 1 && c_dtype == dtype && !Cin && !rowscale &&
                          gt_gemm_ws_applicable(dtype, transA, M, N, K, g.vecA);
     gt_status s = ws_path ? gt_gemm_ws_launch(g, dtype, transB, st)
+                  : tn256 ? launch_tn256(g, p.splits, st)
                   : x3 ? gt_gemm_x3_launch(g, transA, transB, p.splits, st)
                        : (dtype == GT_F32) ? launch_gemm_t<float>(g, transA, transB, p.splits, st)
                                            : launch_gemm_t<bf16_t>(g, transA, transB, p.splits, st);

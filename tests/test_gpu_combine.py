@@ -31,7 +31,9 @@ SHAPES = [(1, 1, 1), (300, 64, 64), (257, 16, 100), (515, 41, 128), (130, 47, 25
           # large enough to keep the big tiles
           (1024, 47, 256), (1100, 256, 47), (3000, 200, 300),
           # at most 64 output rows over a long reduction: 64 x 256 tiles of the split-bf16 kernel
-          (48, 300, 20000)]
+          (48, 300, 20000),
+          # weight-gradient shapes over a long reduction, split over workgroups (bf16: the transposing-load kernel)
+          (256, 256, 20000), (100, 250, 12000), (200, 130, 11000)]
 
 
 def _check(got, ref, absr, dtype, c_bf16, what):
