@@ -75,9 +75,10 @@ def kernel_source_sha16():
     return h.hexdigest()[:16]
 
 
-def agg_kernel_name(dt, V, G, NP, U):
+def agg_kernel_name(dt, V, G, NP, U, masked):
     """The aggregation kernel instance as a profiler lists it."""
-    return "k_aggregate<%s, %d, %d, %d, %d, 0>" % ("unsigned short" if dt == "bf16" else "float", V, G, NP, U)
+    return "k_aggregate<%s, %d, %d, %d, %d, 0, %s>" % ("unsigned short" if dt == "bf16" else "float", V, G, NP, U,
+                                                      "true" if masked else "false")
 
 
 def measure_traffic(args):
@@ -121,14 +122,18 @@ def measure_traffic(args):
             ["--steps", "3", "--warmup", "1", "--copy-probe"], "pmc_%s_%s.log" % (tag, ctr), 400)
         path = glob.glob(os.path.join(d, "**", "p_counter_collection.csv"), recursive=True)[0]
         per = collections.defaultdict(list)
-        for r in csv.DictReader(open(path)):
-            if r["Counter_Name"] == ctr:
-                per[r["Kernel_Name"]].append(float(r["Counter_Value"]))
+        rows = sorted((r for r in csv.DictReader(open(path)) if r["Counter_Name"] == ctr), key=lambda r: int(r["Dispatch_Id"]))
+        for r in rows:
+            per[r["Kernel_Name"]].append(float(r["Counter_Value"]))
         return per
 
     fetch, write = counters("FETCH_SIZE"), counters("WRITE_SIZE")
-    copy_f = max(fetch["__amd_rocclr_copyBuffer"])
-    copy_w = max(write["__amd_rocclr_copyBuffer"])
+    # the probe among the runtime's copy kernels (uploads of the inputs use the same kernel): the one that
+    # wrote closest to 1 GiB; the two runs dispatch the same kernels in the same order
+    cw, cf = write["__amd_rocclr_copyBuffer"], fetch["__amd_rocclr_copyBuffer"]
+    assert len(cw) == len(cf), "the two counter runs dispatched different copy kernels"
+    probe = min(range(len(cw)), key=lambda i: abs(cw[i] - 1048576.0))
+    copy_f, copy_w = cf[probe], cw[probe]
     fs, ws = 1048576.0 / copy_f, 1048576.0 / copy_w            # 1 GiB copied = 1,048,576 KiB each way
     d = os.path.join(out_dir, "prof_%s" % tag)
     subprocess.run(["rm", "-rf", d])
@@ -755,7 +760,7 @@ def main():
 
     groups = {}
     for kind, width, rows, work, ms in recs:
-        key = (("agg_fwd", "agg_bwd", "combine")[kind], width, rows, work)
+        key = (("agg_fwd", "agg_bwd", "combine", "fused")[kind], width, rows, work)
         g = groups.setdefault(key, [0, 0.0])
         g[0] += 1
         g[1] += ms
@@ -769,10 +774,10 @@ def main():
     for b in blocks:
         blk_by_rows[(0, b["n_dst"], b["colidx"].numel())] = b
         blk_by_rows[(1, b["n_src"], b["colidx"].numel())] = b
-    for (kind, width, rows, work, ms), (V, G_, NP, U) in zip(recs, variants):
+    for (kind, width, rows, work, ms), (V, G_, NP, U, MK) in zip(recs, variants):
         if kind not in (0, 1):
             continue
-        name = agg_kernel_name(dt, V, G_, NP, U)
+        name = agg_kernel_name(dt, V, G_, NP, U, MK)
         blk = blk_by_rows[(kind, rows, work)]
         w = inst.setdefault(name, dict(n=0, ms=0.0, gather=0.0, floor=0.0, ef=0.0, widths=set(), slice=0.0))
         w["slice"] = max(w["slice"], n_in_of[kind](blk) * width * s / 1e6)

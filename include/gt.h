@@ -401,10 +401,10 @@ gt_status gt_trace_reset(void);
 gt_status gt_trace_count(int64_t *n /* host */);
 gt_status gt_trace_get(int64_t i, int *kind, int64_t *width, int64_t *rows, int64_t *work, double *ms);
 /* Which instance of the aggregation kernel record i timed: V elements per lane and load, G lanes
- * per work item, NP column tiles per lane, U row loads in flight (all 0 for a combination record).
- * Together with the data type these are the kernel's template arguments, i.e. its name in a
- * profiler's kernel list. */
-gt_status gt_trace_get_variant(int64_t i, int *V, int *G, int *NP, int *U);
+ * per work item, NP column tiles per lane, U row loads in flight, and whether it applies an output
+ * mask (all 0 for a combination record).  Together with the data type these are the kernel's
+ * template arguments, i.e. its name in a profiler's kernel list. */
+gt_status gt_trace_get_variant(int64_t i, int *V, int *G, int *NP, int *U, int *masked);
 
 const char *gt_status_string(gt_status s);
 const char *gt_last_error(void);

@@ -107,7 +107,7 @@ lib.gt_trace_reset.argtypes = []
 lib.gt_trace_count.argtypes = [POINTER(c_int64)]
 lib.gt_trace_get.argtypes = [c_int64, POINTER(c_int), POINTER(c_int64), POINTER(c_int64), POINTER(c_int64),
                              POINTER(c_double)]
-lib.gt_trace_get_variant.argtypes = [c_int64] + [POINTER(c_int)] * 4
+lib.gt_trace_get_variant.argtypes = [c_int64] + [POINTER(c_int)] * 5
 lib.gt_calibrate_ws_size.argtypes = [POINTER(c_size_t)]
 lib.gt_calibrate.argtypes = [c_void_p, c_size_t, POINTER(gt_cost_coeffs), c_void_p]
 lib.gt_calibrate_dtype.argtypes = [c_int, c_void_p, c_size_t, POINTER(gt_cost_coeffs), c_void_p]
@@ -464,12 +464,12 @@ def gt_trace_records():
 
 
 def gt_trace_variants():
-    """[(V, G, NP, U)] of every record: the aggregation kernel's template arguments (zeros for a combination)."""
+    """[(V, G, NP, U, masked)] of every record: the aggregation kernel's template arguments (zeros for a combination)."""
     n = c_int64()
     _check(lib.gt_trace_count(byref(n)))
     out = []
     for i in range(n.value):
-        v = [c_int() for _ in range(4)]
+        v = [c_int() for _ in range(5)]
         _check(lib.gt_trace_get_variant(i, *[byref(x) for x in v]))
         out.append(tuple(x.value for x in v))
     return out

@@ -449,7 +449,7 @@ gt_status launch(const AggArgs &a, hipStream_t st) {
         AggArgs b = a;
         b.xcd_run = agg_xcd_run(gx);
         const int tr = gt_trace_open(a.trace_kind, a.F, a.n_rows, a.n_edges, st);
-        gt_trace_variant(tr, V, G, NP, U);
+        gt_trace_variant(tr, V, G, NP, U, VWM == VWM_NONE && a.mask != nullptr);
         if constexpr (VWM == VWM_NONE) {
             if (b.mask) k_aggregate<T, V, G, NP, U, VWM, true><<<dim3((unsigned)gx, gy), 256, 0, st>>>(b);
             else k_aggregate<T, V, G, NP, U, VWM, false><<<dim3((unsigned)gx, gy), 256, 0, st>>>(b);

@@ -10,5 +10,5 @@ bool gt_trace_on();
 int gt_trace_open(int kind, int64_t width, int64_t rows, int64_t work, hipStream_t st);
 void gt_trace_close(int id, hipStream_t st);
 // template parameters of the aggregation kernel instance a record belongs to (V elements per lane,
-// G lanes per item, NP column passes per lane, U row loads in flight)
-void gt_trace_variant(int id, int V, int G, int NP, int U);
+// G lanes per item, NP column passes per lane, U row loads in flight, output mask present)
+void gt_trace_variant(int id, int V, int G, int NP, int U, int masked);

@@ -9,7 +9,7 @@
 #include "gt_trace.h"
 
 namespace {
-struct Rec { hipEvent_t a, b; int kind; int64_t width, rows, work; int V = 0, G = 0, NP = 0, U = 0; };
+struct Rec { hipEvent_t a, b; int kind; int64_t width, rows, work; int V = 0, G = 0, NP = 0, U = 0, MK = 0; };
 std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 bool g_on = false;
@@ -34,9 +34,9 @@ int gt_trace_open(int kind, int64_t width, int64_t rows, int64_t work, hipStream
     return (int)g_recs.size() - 1;
 }
 
-void gt_trace_variant(int id, int V, int G, int NP, int U) {
+void gt_trace_variant(int id, int V, int G, int NP, int U, int masked) {
     if (id < 0 || id >= (int)g_recs.size()) return;
-    g_recs[id].V = V; g_recs[id].G = G; g_recs[id].NP = NP; g_recs[id].U = U;
+    g_recs[id].V = V; g_recs[id].G = G; g_recs[id].NP = NP; g_recs[id].U = U; g_recs[id].MK = masked;
 }
 
 void gt_trace_close(int id, hipStream_t st) {
@@ -77,12 +77,13 @@ extern "C" gt_status gt_trace_get(int64_t i, int *kind, int64_t *width, int64_t 
     return GT_OK;
 }
 
-extern "C" gt_status gt_trace_get_variant(int64_t i, int *V, int *G, int *NP, int *U) {
+extern "C" gt_status gt_trace_get_variant(int64_t i, int *V, int *G, int *NP, int *U, int *masked) {
     if (i < 0 || i >= (int64_t)g_recs.size()) return gt_fail(GT_ERR_INVALID_ARG, "gt_trace_get_variant: index out of range");
     const Rec &r = g_recs[(size_t)i];
     if (V) *V = r.V;
     if (G) *G = r.G;
     if (NP) *NP = r.NP;
     if (U) *U = r.U;
+    if (masked) *masked = r.MK;
     return GT_OK;
 }
