@@ -115,10 +115,10 @@ def measure_traffic(args):
         if r.returncode != 0:
             raise SystemExit("measure-traffic: step failed (rc %d), see gpurun_out/%s" % (r.returncode, log))
 
-    def counters(ctr):
+    def counters(ctr, extra_ctrs=()):
         d = os.path.join(out_dir, "pmc_%s_%s" % (tag, ctr))
         subprocess.run(["rm", "-rf", d])
-        run(["rocprofv3", "--pmc", ctr, "--output-format", "csv", "-d", d, "-o", "p", "--"],
+        run(["rocprofv3", "--pmc", ctr, *extra_ctrs, "--output-format", "csv", "-d", d, "-o", "p", "--"],
             ["--steps", "3", "--warmup", "1", "--copy-probe"], "pmc_%s_%s.log" % (tag, ctr), 400)
         path = glob.glob(os.path.join(d, "**", "p_counter_collection.csv"), recursive=True)[0]
         per = collections.defaultdict(list)
@@ -128,6 +128,7 @@ def measure_traffic(args):
         return per
 
     fetch, write = counters("FETCH_SIZE"), counters("WRITE_SIZE")
+    mfma = counters("MfmaUtil")     # matrix-pipe busy share per dispatch (a run of its own)
     # the probe among the runtime's copy kernels (uploads of the inputs use the same kernel): the one that
     # wrote closest to 1 GiB; the two runs dispatch the same kernels in the same order
     cw, cf = write["__amd_rocclr_copyBuffer"], fetch["__amd_rocclr_copyBuffer"]
@@ -155,8 +156,19 @@ def measure_traffic(args):
                            hbm_bytes_per_launch=(sum(fv) / len(fv) * fs + sum(wv) / len(wv) * ws) * 1024.0,
                            avg_us_rocprof_kernel_trace=float(st[0]["AverageNs"]) / 1e3 if st else None,
                            avg_ms_hip_events=ev[0]["avg_ms"] if ev else None)
+    # the matrix kernels of the same runs: bytes past L2 per launch, duration, matrix-pipe utilisation
+    mm = {}
+    for name in fetch:
+        if "k_gemm" not in name and "k_fused" not in name:
+            continue
+        short = name.replace("(anonymous namespace)::", "").replace("void ", "").split("(")[0]
+        fv, wv, uv = fetch[name], write.get(name, [0.0]), mfma.get(name, [])
+        st = [r for r in stats if r["Name"] == name]
+        mm[short] = dict(dispatches=len(fv), hbm_bytes_per_launch=(sum(fv) / len(fv) * fs + sum(wv) / len(wv) * ws) * 1024.0,
+                         avg_us_rocprof_kernel_trace=float(st[0]["AverageNs"]) / 1e3 if st else None,
+                         mfma_util_percent=sum(uv) / len(uv) if uv else None)
     res = dict(workload=plain["config"]["workload"], orders_fwd=plain["config"]["orders_fwd"], orders_bwd=plain["config"]["orders_bwd"],
-               source_sha16=kernel_source_sha16(), instances=inst,
+               source_sha16=kernel_source_sha16(), instances=inst, matrix_kernels=mm,
                copy_probe=dict(bytes_each_way=1 << 30, fetch_kib=copy_f, write_kib=copy_w, fetch_scale=fs, write_scale=ws),
                note="counted at the L2 <-> fabric boundary (TCC_EA read / write requests): bytes served by the 256 MB "
                     "Infinity Cache are included, so this is an upper bound of the HBM traffic.  Per launch = mean over "
