@@ -283,12 +283,15 @@ bool ranges_overlap(const void *a, size_t a_elems, const void *b, size_t b_elems
 // rows is bound by the number of memory requests, and writing and re-reading A X costs as much as
 // gathering it.  Wider rows lose: one workgroup per CU holds the weights, and eight wavefronts hide
 // less gather latency than the aggregation kernel's two dozen (2^21-vertex power-law graph, bf16
-// 100 -> 256: 1.96 / 2.52; 2^18 vertices, fp32 128 -> 41: 0.52 / 1.10; 41 -> 128: 0.27 / 0.57).
+// 100 -> 256: 1.96 / 2.52; 2^18 vertices, fp32 128 -> 41: 0.52 / 1.10; 41 -> 128: 0.27 / 0.57).  So do
+// narrow rows of a table small enough to sit in the L2s, where the aggregation kernel is not request
+// bound (2^18 vertices, 16 -> 64 fp32, a 16 MB table: 0.24 / 0.36; 2^21 vertices, 16 -> 64 bf16, 64 MB:
+// 1.09 / 1.03).  Hence: rows of at most 64 bytes AND a gathered table of at least 32 MiB.
 bool fused_preferred(const gt_graph *g, const gt_layer_desc *d, const void *X, int64_t ldx) {
     const int ve = d->dtype == GT_BF16 ? 8 : 4;
     if (!gt_fused_applicable(d->dtype, d->in_dim, d->out_dim) || ((uintptr_t)X & 15) || ldx % ve) return false;
-    (void)g;
-    return d->in_dim * (int64_t)gt_dtype_size(d->dtype) <= 64;
+    const int64_t row_bytes = d->in_dim * (int64_t)gt_dtype_size(d->dtype);
+    return row_bytes <= 64 && g->n_src * row_bytes >= ((int64_t)32 << 20);
 }
 
 void decide(const gt_graph *g, const gt_layer_desc *d, gt_order *fwd, gt_order *bwd) {

@@ -100,7 +100,36 @@ def test_layer_forward_only_without_saved_buffer(dtype):
     """gt_layer_fwd with saved == NULL (inference) gives the same outputs as the training call, in
     both forced orders and AUTO, with and without the root term."""
     _forward_only(dtype, 100, 64)
-    _forward_only(dtype, 16, 64)      # 64-byte (fp32) / 32-byte (bf16) rows: AUTO / agg_first take the fused kernel
+    _forward_only(dtype, 16, 64)
+
+
+def test_forward_only_layer_takes_the_fused_kernel_for_narrow_rows_of_a_large_table():
+    """Rows of 64 bytes from a 32 MiB table (2^19 vertices x 16 fp32 columns): a forward-only
+    aggregation-first layer call runs the fused kernel (seen in the kernel trace as kind 3) and matches
+    the oracle on every element; the training call (with `saved`) runs the two kernels."""
+    from paper_2305_17469_amd import binding as B
+    announce("layer forward only: fused kernel route")
+    rp, ci = graphs.er_csr(19, 4, seed=61)
+    n = rp.size - 1
+    g = B.Graph(up_i32(rp), up_i32(ci), n)
+    fi, fo = 16, 32
+    X = tensors.normal((n, fi), seed=62)
+    W = tensors.glorot(fi, fo, seed=63)
+    b = (0.1 * tensors.normal((fo,), seed=64)).astype(np.float32)
+    Xd, Wd, bd = up_feat(X, "f32"), up_feat(W, "f32"), torch.from_numpy(b).cuda()
+    d = B.make_desc("mean", "f32", True, fi, fo)
+    bufs = B.LayerBuffers(g, d)
+    ref = oracle.layer_fwd(dict(rowptr=rp, colidx=ci, n_src=n, n_dst=n), "mean", X, W, b, True)["H"]
+    for inference, want_fused in ((True, True), (False, False)):
+        B.gt_trace_reset()
+        B.gt_trace_enable(True)
+        Y, used = B.gt_layer_fwd(g, d, Xd, Wd, bd, bufs, "agg_first", inference=inference)
+        torch.cuda.synchronize()
+        B.gt_trace_enable(False)
+        kinds = [r[0] for r in B.gt_trace_records()]
+        B.gt_trace_reset()
+        assert (3 in kinds) == want_fused, (inference, kinds)
+        assert max_rel_err(down(Y), ref) <= 1e-5, inference
 
 
 def _forward_only(dtype, fi, fo):
