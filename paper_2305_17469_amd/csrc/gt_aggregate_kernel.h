@@ -58,12 +58,7 @@ typedef uint16_t bf16_t;
 
 __device__ inline float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
-__device__ inline uint32_t f32_to_bf16(float f) {   // round to nearest even; NaN stays NaN
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+__device__ inline uint32_t f32_to_bf16(float f) { return gt_to_bf16(f); }   // round to nearest even; NaN stays NaN
 
 // Raw (unconverted) V consecutive elements, as they travel from memory: 16 bytes when V > 1.
 template <typename T, int V> struct Raw;
@@ -159,10 +154,10 @@ template <>
 __device__ inline void store_vec<bf16_t, 8>(bf16_t *p, const float (&v)[8], int n) {
     if (n >= 8) {
         uint4 o;
-        o.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-        o.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
-        o.z = f32_to_bf16(v[4]) | (f32_to_bf16(v[5]) << 16);
-        o.w = f32_to_bf16(v[6]) | (f32_to_bf16(v[7]) << 16);
+        o.x = gt_pack_bf16(v[0], v[1]);
+        o.y = gt_pack_bf16(v[2], v[3]);
+        o.z = gt_pack_bf16(v[4], v[5]);
+        o.w = gt_pack_bf16(v[6], v[7]);
         *reinterpret_cast<uint4 *>(p) = o;
     } else {
         for (int i = 0; i < n; ++i) p[i] = (bf16_t)f32_to_bf16(v[i]);

@@ -19,12 +19,7 @@ typedef uint16_t gemm_bf16_t;
 
 constexpr int GEMM_KT = 32;   // k-tile
 
-__device__ inline uint32_t gemm_f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+__device__ inline uint32_t gemm_f32_to_bf16(float f) { return gt_to_bf16(f); }
 __device__ inline float gemm_bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
 template <typename T> struct Elem;
@@ -47,6 +42,7 @@ struct GemmArgs {
     int64_t k_per_split;           // multiple of KT
     int vecA, vecB;                // 16-byte loads allowed
     int ntm, ntn;                  // output tiles along M and N (host side; see gemm_tile_of_block)
+    int split_xcd;                 // splits % 8 == 0: the output tiles of one k-range run on one XCD
 };
 
 // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  The
@@ -55,8 +51,25 @@ struct GemmArgs {
 // share is fetched into one L2 once.  Returns false for the padding workgroups of a ragged grid.
 // Used only when there are many row tiles; with few (the weight-gradient shape) the plain order
 // keeps all XCDs busy.
+//
+// A reduction cut into k-ranges (gridDim.z > 1) with a few output tiles: the tiles of one k-range read
+// the same k-slab of the operand they share (the weight gradient's 5 row tiles of config 2 all read
+// the whole of dZ).  In grid order they would land on different XCDs and the slab would cross the
+// fabric once per tile; with split_xcd the linear workgroup id is read as (xcd, sequence number) and
+// an XCD works through whole k-ranges, all tiles of a range back to back, so the re-reads hit its L2.
 #define GEMM_SWIZZLE_MIN_ROW_TILES 64
-__device__ inline bool gemm_tile_of_block(const GemmArgs &g, int &tile_m, int &tile_n) {
+__device__ inline bool gemm_tile_of_block(const GemmArgs &g, int &tile_m, int &tile_n, int &split) {
+    if (g.split_xcd) {
+        const int tiles = g.ntm * g.ntn;
+        const int L = blockIdx.z * gridDim.x + blockIdx.x;
+        const int xcd = L & 7, seq = L >> 3;
+        const int t = seq % tiles;
+        split = (seq / tiles) * 8 + xcd;
+        tile_n = t % g.ntn;
+        tile_m = t / g.ntn;
+        return true;
+    }
+    split = blockIdx.z;
     const int L = blockIdx.x;
     if (g.ntm < GEMM_SWIZZLE_MIN_ROW_TILES) {
         tile_n = L % g.ntn;
@@ -67,6 +80,9 @@ __device__ inline bool gemm_tile_of_block(const GemmArgs &g, int &tile_m, int &t
     tile_n = i % g.ntn;
     tile_m = (i / g.ntn) * 8 + xcd;
     return tile_m < g.ntm;
+}
+static inline int gemm_split_xcd(int ntm, int ntn, int splits) {
+    return ntm < GEMM_SWIZZLE_MIN_ROW_TILES && ntm * ntn > 1 && splits >= 16 && splits % 8 == 0;
 }
 static inline unsigned gemm_grid_x(int ntm, int ntn) {
     return (unsigned)((ntm < GEMM_SWIZZLE_MIN_ROW_TILES ? ntm : (ntm + 7) / 8 * 8) * ntn);
@@ -85,7 +101,7 @@ static inline unsigned gemm_grid_x(int ntm, int ntn) {
 
 template <int TM, int TN>
 __device__ inline void gemm_epilogue(const GemmArgs &g, floatx16 (&acc)[TM][TN], int64_t row0, int64_t col0, int l32,
-                                     int h, float *stage) {
+                                     int h, float *stage, int split) {
     constexpr int STRIDE = GEMM_STAGE_STRIDE(TN);
     constexpr int LPR = TN * 8;            // lanes per row: 4 columns each
     constexpr int RPI = 64 / LPR;          // rows per store instruction
@@ -96,7 +112,7 @@ __device__ inline void gemm_epilogue(const GemmArgs &g, floatx16 (&acc)[TM][TN],
     float *out_f = static_cast<float *>(g.C);
     gemm_bf16_t *out_h = static_cast<gemm_bf16_t *>(g.C);
     const int64_t ldc = partial ? g.N : g.ldc;
-    if (partial) out_f += (int64_t)blockIdx.z * g.M * g.N;
+    if (partial) out_f += (int64_t)split * g.M * g.N;
     const bool as_bf16 = !partial && g.c_bf16;
     const bool vec_ok = (ldc % 4 == 0) && (((uintptr_t)g.C & 15) == 0) && (col + 4 <= g.N);
     float bia[4] = {0.f, 0.f, 0.f, 0.f};
@@ -144,8 +160,8 @@ __device__ inline void gemm_epilogue(const GemmArgs &g, floatx16 (&acc)[TM][TN],
             if (as_bf16) {
                 gemm_bf16_t *p = out_h + row * ldc + col;
                 if (vec_ok) {
-                    *reinterpret_cast<uint2 *>(p) = make_uint2(gemm_f32_to_bf16(v[0]) | (gemm_f32_to_bf16(v[1]) << 16),
-                                                               gemm_f32_to_bf16(v[2]) | (gemm_f32_to_bf16(v[3]) << 16));
+                    *reinterpret_cast<uint2 *>(p) = make_uint2(gt_pack_bf16(v[0], v[1]),
+                                                               gt_pack_bf16(v[2], v[3]));
                 } else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i)

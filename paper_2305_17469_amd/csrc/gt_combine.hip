@@ -129,9 +129,10 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
     const int l32 = lane & 31, h = lane >> 5;
     const int wm = wave / WGN, wn = wave % WGN;
     int tile_m, tile_n;
-    if (!gemm_tile_of_block(g, tile_m, tile_n)) return;   // whole workgroup leaves before any barrier
+    int split;
+    if (!gemm_tile_of_block(g, tile_m, tile_n, split)) return;   // whole workgroup leaves before any barrier
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
+    const int64_t kbeg = (int64_t)split * g.k_per_split;
     const int64_t kend = (kbeg + g.k_per_split < g.K) ? kbeg + g.k_per_split : g.K;
     const T *A = static_cast<const T *>(g.A);
     const T *B = static_cast<const T *>(g.B);
@@ -274,13 +275,13 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
                 const int cv = threadIdx.x / VEB, e = threadIdx.x % VEB;
                 float t = 0.0f;
                 for (int o = 0; o < 256 / VPR; ++o) t += red[(cv + VPR * o) * VEB + e];
-                if (n0 + threadIdx.x < g.N) g.colsum[(int64_t)blockIdx.z * g.N + n0 + threadIdx.x] = t;
+                if (n0 + threadIdx.x < g.N) g.colsum[(int64_t)split * g.N + n0 + threadIdx.x] = t;
             }
             __syncthreads();
         }
     }
     gemm_epilogue<TM, TN>(g, acc, m0 + wm * TM * 32, n0 + wn * TN * 32, l32, h,
-                          reinterpret_cast<float *>(smem) + wave * GEMM_STAGE_FLOATS(TN));
+                          reinterpret_cast<float *>(smem) + wave * GEMM_STAGE_FLOATS(TN), split);
 }
 
 // bf16 weight gradient  C[M, N] (+)= A^T B  with A stored [K][lda] (m contiguous) and B stored [K][ldb]
@@ -310,9 +311,10 @@ __global__ void __launch_bounds__(BIG ? 512 : 256) k_gemm_tn_bf16(const GemmArgs
     const int l32 = lane & 31, h = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
     int tile_m, tile_n;
-    if (!gemm_tile_of_block(g, tile_m, tile_n)) return;
+    int split;
+    if (!gemm_tile_of_block(g, tile_m, tile_n, split)) return;
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
+    const int64_t kbeg = (int64_t)split * g.k_per_split;
     const int64_t kend = (kbeg + g.k_per_split < g.K) ? kbeg + g.k_per_split : g.K;
 
     // this thread's patch: operand (first half of the threads: A, second half: B), k-group (4 k), row
@@ -415,13 +417,13 @@ __global__ void __launch_bounds__(BIG ? 512 : 256) k_gemm_tn_bf16(const GemmArgs
             const int q = threadIdx.x >> 3, e = threadIdx.x & 7;
             float sum = 0.0f;
             for (int k = 0; k < 8; ++k) sum += red[((q << 3) + k) * 8 + e];
-            if (n0 + threadIdx.x < g.N) g.colsum[(int64_t)blockIdx.z * g.N + n0 + threadIdx.x] = sum;
+            if (n0 + threadIdx.x < g.N) g.colsum[(int64_t)split * g.N + n0 + threadIdx.x] = sum;
         }
         __syncthreads();
     }
     float *stage = reinterpret_cast<float *>(smem) + wave * GEMM_STAGE_FLOATS(2);
     if constexpr (!BIG) {
-        gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h, stage);
+        gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h, stage, split);
     } else {   // 64 x 128 per wavefront, written as two 64 x 64 halves through the same stage
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
@@ -430,7 +432,7 @@ __global__ void __launch_bounds__(BIG ? 512 : 256) k_gemm_tn_bf16(const GemmArgs
             for (int a = 0; a < 2; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b) part[a][b] = acc[a][half * 2 + b];
-            gemm_epilogue<2, 2>(g, part, m0 + wm * 64, n0 + wn * 128 + half * 64, l32, h, stage);
+            gemm_epilogue<2, 2>(g, part, m0 + wm * 64, n0 + wn * 128 + half * 64, l32, h, stage, split);
         }
     }
 }
@@ -576,6 +578,7 @@ SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K, bool x3, bool 
     }
     if (want > max_by_len) want = max_by_len;
     if (want < 1) want = 1;
+    if (tiles > 1 && want >= 16) want = want / 8 * 8;        // whole k-ranges per XCD (gemm_split_xcd)
     int64_t kps = ((K + want - 1) / want + KT - 1) / KT * KT;
     p.splits = (int)((K + kps - 1) / kps);
     p.k_per_split = kps;
@@ -589,6 +592,7 @@ gt_status launch_gemm(GemmArgs g, int splits, hipStream_t st) {
     g.ntn = (int)((g.N + bn - 1) / bn);
     g.ntm = (int)((g.M + bm - 1) / bm);
     dim3 grid(gemm_grid_x(g.ntm, g.ntn), 1, (unsigned)splits);
+    g.split_xcd = gemm_split_xcd(g.ntm, g.ntn, splits);
     if constexpr (sizeof(T) == 2 && TA && !TB) {
         // the weight-gradient shape in bf16 with 128 x 128 tiles: transposing loads (see k_gemm_tn_bf16)
         if (!t.small && bn == 128 && g.vecA && g.vecB) {

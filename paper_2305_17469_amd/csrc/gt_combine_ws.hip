@@ -104,8 +104,8 @@ __device__ inline void ws_epilogue(const GemmArgs &g, floatx16 (&acc)[NB], int64
             if (CB) {
                 gemm_bf16_t *p = static_cast<gemm_bf16_t *>(g.C) + row * g.ldc + col;
                 if (whole) {
-                    *reinterpret_cast<uint2 *>(p) = make_uint2(gemm_f32_to_bf16(v[0]) | (gemm_f32_to_bf16(v[1]) << 16),
-                                                               gemm_f32_to_bf16(v[2]) | (gemm_f32_to_bf16(v[3]) << 16));
+                    *reinterpret_cast<uint2 *>(p) = make_uint2(gt_pack_bf16(v[0], v[1]),
+                                                               gt_pack_bf16(v[2], v[3]));
                 } else {
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
@@ -198,8 +198,8 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
                     for (int i = 0; i < 4; ++i) v[i] = (g.relu && !(v[i] > 0.0f)) ? 0.0f : v[i];
                 }
                 *reinterpret_cast<uint2 *>(stage + l32 * SSTR + bb * 16 + 4 * q + 2 * h) =
-                    make_uint2(gemm_f32_to_bf16(v[0]) | (gemm_f32_to_bf16(v[1]) << 16),
-                               gemm_f32_to_bf16(v[2]) | (gemm_f32_to_bf16(v[3]) << 16));
+                    make_uint2(gt_pack_bf16(v[0], v[1]),
+                               gt_pack_bf16(v[2], v[3]));
             }
         }
         __asm__ volatile("" ::: "memory");
@@ -220,15 +220,27 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
     __asm__ volatile("" ::: "memory");
 }
 
-// LDS bytes of an instance: the weight slice, four private A stages, the bias of the column slice
-template <typename T, int NB, int NS>
+// LDS bytes of an instance with NW wavefronts: the weight slice, one private A stage per wavefront, the
+// bias of the column slice
+template <typename T, int NB, int NS, int NW>
 constexpr size_t ws_lds_bytes() {
-    return (size_t)NB * 32 * (NS * WsGeom<T>::SK + WsGeom<T>::PAD) * sizeof(T) + 4 * GEMM_STAGE_FLOATS(1) * 4 +
+    return (size_t)NB * 32 * (NS * WsGeom<T>::SK + WsGeom<T>::PAD) * sizeof(T) + (size_t)NW * GEMM_STAGE_FLOATS(1) * 4 +
            (size_t)NB * 32 * 4;
 }
-// two workgroups share a CU when their LDS allows it; the register budget is set to match
+// Wavefronts per workgroup.  The kernel lives on memory operations in flight, so a CU should hold eight
+// wavefronts: two workgroups of four where two weight slices fit its LDS (80 KB each), else one
+// workgroup of eight, or of six where the weight slice leaves room for no more stages (256 x 256 bf16:
+// 132 KB of weights; measured on MI355X over 2^21 rows, 4 -> 6 wavefronts 0.61 -> ... ms, and 100 -> 256
+// with 4 -> 8 wavefronts 0.49 -> ... ms).
 template <typename T, int NB, int NS>
-constexpr int ws_per_cu() { return ws_lds_bytes<T, NB, NS>() <= 80 * 1024 ? 2 : 1; }
+constexpr int ws_waves() {
+    if (ws_lds_bytes<T, NB, NS, 4>() <= 80 * 1024) return 4;
+    if (ws_lds_bytes<T, NB, NS, 8>() <= 160 * 1024) return 8;
+    if (ws_lds_bytes<T, NB, NS, 6>() <= 160 * 1024) return 6;
+    return 4;
+}
+template <typename T, int NB, int NS>
+constexpr int ws_per_cu() { return ws_lds_bytes<T, NB, NS, 4>() <= 80 * 1024 ? 2 : 1; }
 
 // EX: bias and / or ReLU present.  C has the element type of A; products with a row scale or an
 // addend stay on the tiled kernel.
@@ -238,7 +250,8 @@ constexpr int ws_per_cu() { return ws_lds_bytes<T, NB, NS>() <= 80 * 1024 ? 2 : 
 // waits for ALL outstanding memory operations before it touches a prefetched slice, i.e. also for
 // the previous block's stores, which costs a store round trip per block.
 template <typename T, int NB, int NS, bool EX, bool FAST>
-__global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const GemmArgs g, const int transB) {
+__global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB, NS>())) k_gemm_ws(const GemmArgs g, const int transB) {
+    constexpr int NW = ws_waves<T, NB, NS>(), NT = NW * 64;
     constexpr int CK = WsGeom<T>::CK, HK = WsGeom<T>::HK, SK = WsGeom<T>::SK;
     constexpr int KP = NS * SK;                 // K capacity of this instance
     constexpr int WSTR = KP + WsGeom<T>::PAD;   // LDS row stride: 16 bytes past a multiple of 128
@@ -251,11 +264,11 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
     const int l32 = lane & 31, h = lane >> 5;
     // this wavefront's private stage for A slices
     T *As = reinterpret_cast<T *>(smem + (size_t)BN * WSTR * sizeof(T) + (size_t)wave * GEMM_STAGE_FLOATS(1) * 4);
-    float *bias_lds = reinterpret_cast<float *>(smem + (size_t)BN * WSTR * sizeof(T) + 4 * (size_t)GEMM_STAGE_FLOATS(1) * 4);
+    float *bias_lds = reinterpret_cast<float *>(smem + (size_t)BN * WSTR * sizeof(T) + NW * (size_t)GEMM_STAGE_FLOATS(1) * 4);
     const T *A = static_cast<const T *>(g.A);
     const T *B = static_cast<const T *>(g.B);
     const int64_t n0 = (int64_t)blockIdx.y * BN;
-    for (int n = threadIdx.x; n < BN; n += 256) bias_lds[n] = (g.bias && n0 + n < g.N) ? g.bias[n0 + n] : 0.0f;
+    for (int n = threadIdx.x; n < BN; n += NT) bias_lds[n] = (g.bias && n0 + n < g.N) ? g.bias[n0 + n] : 0.0f;
     const int nslices = (int)((g.K + SK - 1) / SK);
 
     // the weight slice, once: Ws[n][k] = op(B)(k, n0 + n), zero outside (K, N).  16-byte loads,
@@ -264,18 +277,18 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
     constexpr int VE = 16 / (int)sizeof(T);
     if (g.vecB && transB) {          // B[n][k]: vectors along k go straight to the LDS row
         constexpr int VPR = KP / VE, TOTAL = BN * VPR;
-        for (int base = threadIdx.x; base < TOTAL; base += 256 * 8) {
+        for (int base = threadIdx.x; base < TOTAL; base += NT * 8) {
             uint4 v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {   // eight loads in flight, then eight stores
-                const int idx = base + u * 256;
+                const int idx = base + u * NT;
                 const int n = idx / VPR, k = (idx % VPR) * VE;
                 const bool ok = idx < TOTAL && n0 + n < g.N && k < g.K;
                 v[u] = *reinterpret_cast<const uint4 *>(B + (ok ? (n0 + n) * g.ldb + k : 0));
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int idx = base + u * 256;
+                const int idx = base + u * NT;
                 const int n = idx / VPR, k = (idx % VPR) * VE;
                 const bool ok = n0 + n < g.N && k < g.K;
                 const int64_t left = g.K - k;
@@ -285,18 +298,18 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
         }
     } else if (g.vecB) {             // B[k][n]: a vector holds VE columns of one k, scattered to VE rows
         constexpr int VPR = BN / VE, TOTAL = KP * VPR;
-        for (int base = threadIdx.x; base < TOTAL; base += 256 * 8) {
+        for (int base = threadIdx.x; base < TOTAL; base += NT * 8) {
             uint4 v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int idx = base + u * 256;
+                const int idx = base + u * NT;
                 const int k = idx / VPR, n = (idx % VPR) * VE;
                 const bool ok = idx < TOTAL && n0 + n < g.N && k < g.K;
                 v[u] = *reinterpret_cast<const uint4 *>(B + (ok ? (int64_t)k * g.ldb + n0 + n : 0));
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int idx = base + u * 256;
+                const int idx = base + u * NT;
                 const int k = idx / VPR, n = (idx % VPR) * VE;
                 const bool ok = n0 + n < g.N && k < g.K;
                 const int64_t left = g.N - (n0 + n);
@@ -310,14 +323,14 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
             }
         }
     } else if (transB) {
-        for (int idx = threadIdx.x; idx < BN * KP; idx += 256) {
+        for (int idx = threadIdx.x; idx < BN * KP; idx += NT) {
             const int n = idx / KP, k = idx % KP;
             const bool ok = n0 + n < g.N && k < g.K;
             const T v = B[ok ? (n0 + n) * g.ldb + k : 0];
             Ws[n * WSTR + k] = ok ? v : (T)0;
         }
     } else {
-        for (int idx = threadIdx.x; idx < BN * KP; idx += 256) {
+        for (int idx = threadIdx.x; idx < BN * KP; idx += NT) {
             const int k = idx / BN, n = idx % BN;
             const bool ok = n0 + n < g.N && k < g.K;
             const T v = B[ok ? (int64_t)k * g.ldb + n0 + n : 0];
@@ -329,12 +342,15 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
     const bool out_vec = (g.ldc % 4 == 0) && (((uintptr_t)g.C & 15) == 0);   // 4-column groups of C are aligned
     const bool wide_rows = out_vec && (g.ldc % 8 == 0);                       // ... and 8-column groups of a bf16 C
     const int64_t nrb = (g.M + 31) / 32;
-    const int64_t stride = (int64_t)gridDim.x * 4;
-    int64_t rb = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t stride = (int64_t)gridDim.x * NW;
+    int64_t rb = (int64_t)blockIdx.x * NW + wave;
     if (rb >= nrb) return;   // no workgroup barrier below this point
-    uint4 R[NS][4];
+    // PD slices of loads are in flight per wavefront: the whole next block where the registers allow
+    // it; with two wavefronts per SIMD (256 registers each) and four slices, two slices ahead
+    constexpr int PD = (FAST && NS == 4 && NW > 4) ? 2 : NS;
+    uint4 R[PD][4];
 #pragma unroll
-    for (int s = 0; s < NS; ++s)
+    for (int s = 0; s < PD; ++s)
         if (FAST || s < nslices) ws_load_slice<T>(R[s], A, g.lda, rb, s, g.M, g.K, lane);
     for (; rb < nrb; rb += stride) {
         const bool more = rb + stride < nrb;
@@ -344,7 +360,9 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
         floatx16 acc[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            if (EX) {
+            // (also without a bias, whose LDS copy then holds zeros: with constant-zero accumulators the
+            // compiler's register allocation of the wide instances spills inside the loop)
+            if (EX || NW > 4) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const float4 c = *reinterpret_cast<const float4 *>(bias_lds + b * 32 + 8 * q + 4 * h);
@@ -366,13 +384,17 @@ __global__ void __launch_bounds__(256, (ws_per_cu<T, NB, NS>())) k_gemm_ws(const
             const int nv = left >= HK ? HK : (left > 0 ? (int)left : 0);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                uint4 v = R[s][j];
+                uint4 v = R[s % PD][j];
                 if (FAST) v = ws_mask<T>(v, nv);
                 else if (nv < HK) v = ws_mask<T>(v, nv);
                 *reinterpret_cast<uint4 *>(As + ((lane >> 3) + 8 * j) * ASTR + (lane & 7) * HK) = v;
             }
-            if (FAST) ws_load_slice<T>(R[s], A, g.lda, rb_next, s, g.M, g.K, lane);
-            else if (more) ws_load_slice<T>(R[s], A, g.lda, rb + stride, s, g.M, g.K, lane);
+            if (FAST) {
+                if (s + PD < NS) ws_load_slice<T>(R[s % PD], A, g.lda, rb, s + PD, g.M, g.K, lane);
+                else ws_load_slice<T>(R[s % PD], A, g.lda, rb_next, s + PD - NS, g.M, g.K, lane);
+            } else if (more) {
+                ws_load_slice<T>(R[s], A, g.lda, rb + stride, s, g.M, g.K, lane);
+            }
 #pragma unroll
             for (int c = 0; c < SK / CK; ++c) {
                 if (!FAST && (int64_t)s * SK + c * CK >= g.K) continue;   // uniform: nothing left in this slice
@@ -628,7 +650,8 @@ gt_status ws_x3_launch(const GemmArgs &g, int transB, hipStream_t st) {
 
 template <typename T, int NB, int NS, bool EX, bool FAST>
 gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
-    constexpr size_t lds = ws_lds_bytes<T, NB, NS>();
+    constexpr int NW = ws_waves<T, NB, NS>();
+    constexpr size_t lds = ws_lds_bytes<T, NB, NS, NW>();
     // More than 64 KB of dynamic LDS has to be allowed per kernel.  Done on every launch that needs
     // it (a host-side setting, no stream operation), so the first launch of an instance behaves
     // like any other, also under stream capture.
@@ -638,10 +661,10 @@ gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     }
     const int64_t nrb = (g.M + 31) / 32;
     const int per_cu = ws_per_cu<T, NB, NS>();
-    int64_t gx = (nrb + 3) / 4;
+    int64_t gx = (nrb + NW - 1) / NW;
     if (gx > 256 * per_cu) gx = 256 * per_cu;
     dim3 grid((unsigned)gx, (unsigned)((g.N + NB * 32 - 1) / (NB * 32)), 1);
-    k_gemm_ws<T, NB, NS, EX, FAST><<<grid, 256, lds, st>>>(g, transB);
+    k_gemm_ws<T, NB, NS, EX, FAST><<<grid, NW * 64, lds, st>>>(g, transB);
     GT_LAUNCH_CHECK("k_gemm_ws");
     return GT_OK;
 }

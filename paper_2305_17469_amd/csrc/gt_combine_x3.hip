@@ -175,9 +175,10 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
     const int l32 = lane & 31, h = lane >> 5;
     const int wm = wave / WGN, wn = wave % WGN;
     int tile_m, tile_n;
-    if (!gemm_tile_of_block(g, tile_m, tile_n)) return;   // whole workgroup leaves before any barrier
+    int split;
+    if (!gemm_tile_of_block(g, tile_m, tile_n, split)) return;   // whole workgroup leaves before any barrier
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
+    const int64_t kbeg = (int64_t)split * g.k_per_split;
     const int64_t kend = (kbeg + g.k_per_split < g.K) ? kbeg + g.k_per_split : g.K;
     const float *A = static_cast<const float *>(g.A);
     const float *B = static_cast<const float *>(g.B);
@@ -269,13 +270,13 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
                 const int iq = j >> 2, e = j & 3, q = iq >> 5, base = (iq & 31) * 8;
                 float t = 0.0f;
                 for (int kq = 0; kq < 8; ++kq) t += red[((base + kq) * NPB + q) * 4 + e];
-                if (n0 + j < g.N) g.colsum[(int64_t)blockIdx.z * g.N + n0 + j] = t;
+                if (n0 + j < g.N) g.colsum[(int64_t)split * g.N + n0 + j] = t;
             }
             __syncthreads();
         }
     }
     gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h,
-                        reinterpret_cast<float *>(smem_raw) + wave * GEMM_STAGE_FLOATS(2));
+                        reinterpret_cast<float *>(smem_raw) + wave * GEMM_STAGE_FLOATS(2), split);
 }
 
 
@@ -298,6 +299,7 @@ gt_status x3_launch_shape(const GemmArgs &g_in, int transA, int transB, int spli
     g.ntn = (int)((g.N + BN - 1) / BN);
     g.ntm = (int)((g.M + BM - 1) / BM);
     dim3 grid(gemm_grid_x(g.ntm, g.ntn), 1, (unsigned)splits);
+    g.split_xcd = gemm_split_xcd(g.ntm, g.ntn, splits);
 #define GT_X3(TA_, TB_)                                                                                   \
     do {                                                                                                  \
         if (g.vecA && g.vecB) return x3_launch_one<TA_, TB_, true, true, WGM, WGN>(g, grid, st);          \

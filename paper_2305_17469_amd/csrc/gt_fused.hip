@@ -51,8 +51,8 @@ constexpr size_t fused_lds_bytes() {
 }
 
 __device__ inline uint4 pack_row(const float (&v)[8]) {   // fp32 -> bf16 (nearest even), 8 values
-    return make_uint4(f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16), f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16),
-                      f32_to_bf16(v[4]) | (f32_to_bf16(v[5]) << 16), f32_to_bf16(v[6]) | (f32_to_bf16(v[7]) << 16));
+    return make_uint4(gt_pack_bf16(v[0], v[1]), gt_pack_bf16(v[2], v[3]),
+                      gt_pack_bf16(v[4], v[5]), gt_pack_bf16(v[6], v[7]));
 }
 __device__ inline uint4 pack_row(const float (&v)[4]) {
     return make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
@@ -241,7 +241,7 @@ __global__ void __launch_bounds__(NW * 64) k_fused_agg_combine(const AggArgs a, 
                         for (int i = 0; i < 4; ++i) v[i] = (f.relu && !(v[i] > 0.0f)) ? 0.0f : v[i];
                         if constexpr (sizeof(T) == 2) {
                             *reinterpret_cast<uint2 *>(stage + l32 * SSTR + bb * 16 + 4 * q + 2 * h) =
-                                make_uint2(f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16), f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16));
+                                make_uint2(gt_pack_bf16(v[0], v[1]), gt_pack_bf16(v[2], v[3]));
                         } else {
                             *reinterpret_cast<float4 *>(stage + l32 * SSTR + 8 * q + 4 * h) = make_float4(v[0], v[1], v[2], v[3]);
                         }

@@ -6,6 +6,20 @@
 
 #include "gt.h"
 
+// fp32 -> bf16, round to nearest even, NaN stays NaN: gfx950 converts a pair in one instruction
+// (v_cvt_pk_bf16_f32), which is what the vector conversion below compiles to.  For every non-NaN
+// input the result is the one of the integer form  (u + 0x7fff + ((u >> 16) & 1)) >> 16.
+typedef __bf16 gt_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float gt_f32x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t gt_pack_bf16(float lo, float hi) {   // lo in bits 0..15, hi in bits 16..31
+    const gt_f32x2 v = {lo, hi};
+    const gt_bf16x2 r = __builtin_convertvector(v, gt_bf16x2);
+    uint32_t u;
+    __builtin_memcpy(&u, &r, 4);
+    return u;
+}
+__device__ inline uint32_t gt_to_bf16(float f) { return gt_pack_bf16(f, 0.0f) & 0xffffu; }
+
 // Work decomposition of one aggregation direction.  A row with more than 1.5 x chunk entries is
 // cut into chunks of `chunk` entries; every chunk becomes a work item that writes an fp32
 // partial row, and a second kernel adds a row's partials in chunk order.  All other rows are

@@ -46,12 +46,7 @@ double t_aggr(const gt_cost_coeffs &c, bool bwd, double E, double n_out, double 
 }
 
 __device__ inline float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
-__device__ inline uint32_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+__device__ inline uint32_t f32_to_bf16(float f) { return gt_to_bf16(f); }
 template <typename T> __device__ inline float ldf(const T *p);
 template <> __device__ inline float ldf<float>(const float *p) { return *p; }
 template <> __device__ inline float ldf<bf16_t>(const bf16_t *p) { return bf16_to_f32(*p); }

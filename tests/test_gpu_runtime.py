@@ -49,7 +49,9 @@ def test_calibrate_fits_positive_coefficients_and_keeps_decisions():
         one = B.gt_calibrate_dtype("bf16")         # one data type alone leaves the other set untouched
         assert B.gt_cost_get_dtype("bf16").gamma_fwd == one.gamma_fwd
         assert B.gt_cost_get_dtype("f32").gamma_fwd == c.gamma_fwd
-        cfg = configs.reddit_like(11)
+        # (2^14 vertices: on a few thousand vertices every kernel sits at its launch floor and the two
+        # orders tie within the noise of a fit)
+        cfg = configs.reddit_like(14)
         blk = cfg["blocks"][0]
         g = B.Graph(up_i32(blk["rowptr"]), up_i32(blk["colidx"]), blk["n_src"])
         for dt in ("f32", "bf16"):
