@@ -296,20 +296,23 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
 __device__ inline uint32_t tn_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }   // lo16(a) | lo16(b) << 16
 __device__ inline uint32_t tn_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }   // hi16(a) | hi16(b) << 16
 
-// BIG = false: 128 x 128 tile, 4 wavefronts of 64 x 64.  BIG = true: ONE 256 x 256 tile per workgroup, i.e.
-// the whole output of a layer of up to 256 x 256 weights, 8 wavefronts of 64 x 128, one workgroup per
-// k-range: every element of A and B is then read from memory exactly once (with 128 x 128 tiles each
-// is read by two workgroups, on different XCDs, and the product is bound by those reads).
+// BIG = false: 128 x 128 tile, 4 wavefronts of 64 x 64, k-tile 32.  BIG = true: ONE 256 x 256 tile per
+// workgroup, i.e. the whole output of a layer of up to 256 x 256 weights, one workgroup per k-range: every
+// element of A and B is then read from memory exactly once (with 128 x 128 tiles each is read by two
+// workgroups, on different XCDs, and the product is bound by those reads).  That form runs 16 wavefronts
+// of 64 x 64 with a k-tile of 64: the bytes a CU has in flight are the loads its threads hold in
+// registers, and 1,024 threads x 64 bytes are what it takes to cover the memory latency (with 8
+// wavefronts of 64 x 128 and a k-tile of 32, half as many, the product ran at 4.1 TB/s).
 template <bool BIG>
-__global__ void __launch_bounds__(BIG ? 512 : 256) k_gemm_tn_bf16(const GemmArgs g) {
-    constexpr int KT = 32, STR = KT + 8, BM = BIG ? 256 : 128, BN = BM, NT = BIG ? 512 : 256, HALF = NT / 2;
-    constexpr int WN = BIG ? 4 : 2;                                  // 32-column MFMA blocks per wavefront
+__global__ void __launch_bounds__(BIG ? 1024 : 256) k_gemm_tn_bf16(const GemmArgs g) {
+    constexpr int KT = BIG ? 64 : 32, KQ = KT / 4, STR = KT + 8, BM = BIG ? 256 : 128, BN = BM, NT = BIG ? 1024 : 256, HALF = NT / 2;
+    constexpr int WN = 2, WGN = BIG ? 4 : 2;                         // 32-column MFMA blocks per wavefront; wavefronts along n
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // max(tiles, output stages): see tn_lds_bytes
     bf16_t *As = reinterpret_cast<bf16_t *>(smem);
     bf16_t *Bs = As + BM * STR;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, h = lane >> 5;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WGN, wn = wave % WGN;
     int tile_m, tile_n;
     int split;
     if (!gemm_tile_of_block(g, tile_m, tile_n, split)) return;
@@ -320,7 +323,7 @@ __global__ void __launch_bounds__(BIG ? 512 : 256) k_gemm_tn_bf16(const GemmArgs
     // this thread's patch: operand (first half of the threads: A, second half: B), k-group (4 k), row
     // group (8 rows of the tile)
     const bool isB = threadIdx.x >= HALF;
-    const int t = threadIdx.x & (HALF - 1), kq = t & 7, rq = t >> 3;
+    const int t = threadIdx.x & (HALF - 1), kq = t % KQ, rq = t / KQ;
     const bf16_t *P = static_cast<const bf16_t *>(isB ? g.B : g.A);
     const int64_t ld = isB ? g.ldb : g.lda;
     const int64_t c0 = (isB ? n0 : m0) + rq * 8;              // first row (column of the stored matrix) of the patch
@@ -340,18 +343,17 @@ __global__ void __launch_bounds__(BIG ? 512 : 256) k_gemm_tn_bf16(const GemmArgs
 #pragma unroll
     for (int e = 0; e < 8; ++e) cs[e] = 0.0f;
 
-    // One register stage: the loads of the next k-tile are in flight while a tile is multiplied.  (A second
-    // stage pushed the 256 x 256 form, whose accumulators alone take 128 registers, into scratch memory:
-    // 0.52 -> 5.3 ms.)
+    // One register stage: the loads of the next k-tile are in flight while a tile is multiplied.
     uint4 r[1][4];
     bool rok[1][4];
+    const bf16_t *src = P + (kbeg + kq * 4) * ld + c0;   // this thread's patch of the tile at k0; only read where ok
     auto fetch = [&](uint4 (&rr)[4], bool (&ok)[4], int64_t k0) {
 #pragma unroll
         for (int dk = 0; dk < 4; ++dk) {
-            const int64_t k = k0 + kq * 4 + dk;
-            ok[dk] = k < kend && nv > 0;
-            rr[dk] = *reinterpret_cast<const uint4 *>(P + (ok[dk] ? k * ld + c0 : 0));   // branch free: masked at the store
+            ok[dk] = k0 + kq * 4 + dk < kend && nv > 0;
+            rr[dk] = *reinterpret_cast<const uint4 *>(ok[dk] ? src + dk * ld : P);   // branch free: masked at the store
         }
+        src += KT * ld;
     };
     auto consume = [&](const uint4 (&rr)[4], const bool (&ok)[4]) {   // registers -> LDS, transposed
         uint32_t w[4][4];
@@ -382,7 +384,7 @@ __global__ void __launch_bounds__(BIG ? 512 : 256) k_gemm_tn_bf16(const GemmArgs
     };
     auto multiply = [&]() {
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
+        for (int s = 0; s < KT / 16; ++s) {
             const int kk = s * 16 + h * 8;   // lane half h supplies k = kk .. kk + 7 of this step
             bf16x8 af[2], bfr[WN];
 #pragma unroll
@@ -406,7 +408,7 @@ __global__ void __launch_bounds__(BIG ? 512 : 256) k_gemm_tn_bf16(const GemmArgs
     }
     __syncthreads();   // every wavefront is done reading the operand tiles
     if (g.colsum && tile_m == 0) {   // uniform over the workgroup
-        // B thread (rq, kq) holds columns 8 rq .. + 7; the eight k-groups that share them are added in order
+        // B thread (rq, kq) holds columns 8 rq .. + 7; the KQ k-groups that share them are added in order
         float *red = reinterpret_cast<float *>(smem);
         if (isB) {
 #pragma unroll
@@ -416,29 +418,17 @@ __global__ void __launch_bounds__(BIG ? 512 : 256) k_gemm_tn_bf16(const GemmArgs
         if (threadIdx.x < BN) {
             const int q = threadIdx.x >> 3, e = threadIdx.x & 7;
             float sum = 0.0f;
-            for (int k = 0; k < 8; ++k) sum += red[((q << 3) + k) * 8 + e];
+            for (int k = 0; k < KQ; ++k) sum += red[(q * KQ + k) * 8 + e];
             if (n0 + threadIdx.x < g.N) g.colsum[(int64_t)split * g.N + n0 + threadIdx.x] = sum;
         }
         __syncthreads();
     }
     float *stage = reinterpret_cast<float *>(smem) + wave * GEMM_STAGE_FLOATS(2);
-    if constexpr (!BIG) {
-        gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h, stage, split);
-    } else {   // 64 x 128 per wavefront, written as two 64 x 64 halves through the same stage
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            floatx16 part[2][2];
-#pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b) part[a][b] = acc[a][half * 2 + b];
-            gemm_epilogue<2, 2>(g, part, m0 + wm * 64, n0 + wn * 128 + half * 64, l32, h, stage, split);
-        }
-    }
+    gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h, stage, split);
 }
 template <bool BIG>
 constexpr size_t tn_lds_bytes() {
-    constexpr size_t tiles = (size_t)(BIG ? 512 : 256) * 40 * 2, stages = (size_t)(BIG ? 8 : 4) * GEMM_STAGE_FLOATS(2) * 4;
+    constexpr size_t tiles = (size_t)(BIG ? 512 * 72 : 256 * 40) * 2, stages = (size_t)(BIG ? 16 : 4) * GEMM_STAGE_FLOATS(2) * 4;
     return tiles > stages ? tiles : stages;
 }
 
@@ -622,7 +612,7 @@ gt_status launch_tn256(GemmArgs g, int splits, hipStream_t st) {
     constexpr size_t lds = tn_lds_bytes<true>();
     GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_tn_bf16<true>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    k_gemm_tn_bf16<true><<<dim3(1, 1, (unsigned)splits), 512, lds, st>>>(g);
+    k_gemm_tn_bf16<true><<<dim3(1, 1, (unsigned)splits), 1024, lds, st>>>(g);
     GT_LAUNCH_CHECK("k_gemm_tn_bf16");
     return GT_OK;
 }

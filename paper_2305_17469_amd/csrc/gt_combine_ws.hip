@@ -130,7 +130,7 @@ __device__ inline void ws_epilogue(const GemmArgs &g, floatx16 (&acc)[NB], int64
 // been read) and is written row-major, eight lanes per row, so a store instruction covers whole
 // 128-byte lines of 8 rows instead of 32-byte pieces of 32 rows.  Rows past M hold the last row's
 // values (their loads were clamped to it) and are written onto the last row.
-template <bool EX, int NB>
+template <bool EX, bool MK, int NB>
 __device__ inline void ws_epilogue_rows_f32(const GemmArgs &g, floatx16 (&acc)[NB], int64_t row0, int64_t n0, int lane,
                                             float *stage) {
     constexpr int SSTR = 36;   // 32 columns + 4: the stage holds 32 x 36 floats
@@ -154,7 +154,7 @@ __device__ inline void ws_epilogue_rows_f32(const GemmArgs &g, floatx16 (&acc)[N
             float4 v = *reinterpret_cast<const float4 *>(stage + rr * SSTR + c4);
             int64_t row = row0 + rr;
             if (row >= g.M) row = g.M - 1;
-            if (EX && g.mask) {   // the host passes a mask here only when its rows allow 16-byte loads
+            if constexpr (MK) {   // the host passes a mask here only when its rows allow 16-byte loads
                 const float4 mk = *reinterpret_cast<const float4 *>(static_cast<const float *>(g.mask) + row * g.ldmask + n0 + b * 32 + c4);
                 v.x = mk.x > 0.0f ? v.x : 0.0f; v.y = mk.y > 0.0f ? v.y : 0.0f;
                 v.z = mk.z > 0.0f ? v.z : 0.0f; v.w = mk.w > 0.0f ? v.w : 0.0f;
@@ -168,7 +168,7 @@ __device__ inline void ws_epilogue_rows_f32(const GemmArgs &g, floatx16 (&acc)[N
 // The same for a bf16 C whose rows are 16-byte aligned: two 32-column groups at a time are rounded
 // to bf16, staged as 32 rows x 64 columns (128 bytes + 16 of padding per row) and written eight lanes
 // per row, 16 bytes per lane: whole 128-byte lines again.
-template <bool EX, int NB>
+template <bool EX, bool MK, int NB>
 __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[NB], int64_t row0, int64_t n0, int lane,
                                              uint32_t *stage) {
     static_assert(NB % 2 == 0, "column groups are staged in pairs");
@@ -177,7 +177,7 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
 #pragma unroll
     for (int bp = 0; bp < NB / 2; ++bp) {
         uint4 mkv[4];
-        if (EX && g.mask) {   // requested before the staging below, so that the round trip overlaps it
+        if constexpr (MK) {   // requested before the staging below, so that the round trip overlaps it
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 int64_t row = row0 + it * 8 + (lane >> 3);
@@ -209,7 +209,7 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
             uint4 v = *reinterpret_cast<const uint4 *>(stage + rr * SSTR + (lane & 7) * 4);
             int64_t row = row0 + rr;
             if (row >= g.M) row = g.M - 1;
-            if (EX && g.mask) {
+            if constexpr (MK) {
                 const uint4 mk = mkv[it];
                 v.x = ws_mask_pair(v.x, mk.x); v.y = ws_mask_pair(v.y, mk.y);
                 v.z = ws_mask_pair(v.z, mk.z); v.w = ws_mask_pair(v.w, mk.w);
@@ -249,7 +249,7 @@ constexpr int ws_per_cu() { return ws_lds_bytes<T, NB, NS, 4>() <= 80 * 1024 ? 2
 // M store the last row's values onto the last row): with control flow in the loop the compiler
 // waits for ALL outstanding memory operations before it touches a prefetched slice, i.e. also for
 // the previous block's stores, which costs a store round trip per block.
-template <typename T, int NB, int NS, bool EX, bool FAST>
+template <typename T, int NB, int NS, bool EX, bool FAST, bool MK>
 __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB, NS>())) k_gemm_ws(const GemmArgs g, const int transB) {
     constexpr int NW = ws_waves<T, NB, NS>(), NT = NW * 64;
     constexpr int CK = WsGeom<T>::CK, HK = WsGeom<T>::HK, SK = WsGeom<T>::SK;
@@ -340,7 +340,6 @@ __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB
     __syncthreads();
 
     const bool out_vec = (g.ldc % 4 == 0) && (((uintptr_t)g.C & 15) == 0);   // 4-column groups of C are aligned
-    const bool wide_rows = out_vec && (g.ldc % 8 == 0);                       // ... and 8-column groups of a bf16 C
     const int64_t nrb = (g.M + 31) / 32;
     const int64_t stride = (int64_t)gridDim.x * NW;
     int64_t rb = (int64_t)blockIdx.x * NW + wave;
@@ -425,9 +424,8 @@ __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB
             }
         }
         const int64_t row = rb * 32 + l32;
-        if constexpr (FAST && sizeof(T) == 4) ws_epilogue_rows_f32<EX, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<float *>(As));
-        else if (FAST && wide_rows) ws_epilogue_rows_bf16<EX, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<uint32_t *>(As));
-        else if (FAST) ws_epilogue<sizeof(T) == 2, EX, true, NB>(g, acc, row < g.M ? row : g.M - 1, n0, h, false);
+        if constexpr (FAST && sizeof(T) == 4) ws_epilogue_rows_f32<EX, MK, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<float *>(As));
+        else if constexpr (FAST) ws_epilogue_rows_bf16<EX, MK, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<uint32_t *>(As));
         else if (row < g.M) ws_epilogue<sizeof(T) == 2, EX, false, NB>(g, acc, row, n0, h, out_vec);
     }
 }
@@ -457,7 +455,7 @@ constexpr size_t ws_x3_lds_bytes() {
 template <int NB, int NS>
 constexpr int ws_x3_per_cu() { return ws_x3_lds_bytes<NB, NS>() <= 80 * 1024 ? 2 : 1; }
 
-template <int NB, int NS, bool EX, bool FAST>
+template <int NB, int NS, bool EX, bool FAST, bool MK>
 __global__ void __launch_bounds__(256, (ws_x3_per_cu<NB, NS>())) k_gemm_ws_x3(const GemmArgs g, const int transB) {
     constexpr int SK = 32;                      // k per slice (128 bytes of fp32)
     constexpr int KP = NS * SK;                 // K capacity of this instance
@@ -612,16 +610,16 @@ __global__ void __launch_bounds__(256, (ws_x3_per_cu<NB, NS>())) k_gemm_ws_x3(co
             }
         }
         const int64_t row = rb * 32 + l32;
-        if constexpr (FAST) ws_epilogue_rows_f32<EX, NB>(g, acc, rb * 32, n0, lane, As);
+        if constexpr (FAST) ws_epilogue_rows_f32<EX, MK, NB>(g, acc, rb * 32, n0, lane, As);
         else if (row < g.M) ws_epilogue<false, EX, false, NB>(g, acc, row, n0, h, out_vec);
     }
 }
 
-template <int NB, int NS, bool EX, bool FAST>
+template <int NB, int NS, bool EX, bool FAST, bool MK = false>
 gt_status ws_x3_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     constexpr size_t lds = ws_x3_lds_bytes<NB, NS>();
     if (lds > 64 * 1024) {
-        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws_x3<NB, NS, EX, FAST>),
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws_x3<NB, NS, EX, FAST, MK>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     }
     const int64_t nrb = (g.M + 31) / 32;
@@ -629,7 +627,7 @@ gt_status ws_x3_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     int64_t gx = (nrb + 3) / 4;
     if (gx > 256 * per_cu) gx = 256 * per_cu;
     dim3 grid((unsigned)gx, (unsigned)((g.N + NB * 32 - 1) / (NB * 32)), 1);
-    k_gemm_ws_x3<NB, NS, EX, FAST><<<grid, 256, lds, st>>>(g, transB);
+    k_gemm_ws_x3<NB, NS, EX, FAST, MK><<<grid, 256, lds, st>>>(g, transB);
     GT_LAUNCH_CHECK("k_gemm_ws_x3");
     return GT_OK;
 }
@@ -641,14 +639,15 @@ gt_status ws_x3_launch(const GemmArgs &g, int transB, hipStream_t st) {
         const bool fast = g.N % (NB * 32) == 0 && g.ldc % 4 == 0 && (((uintptr_t)g.C & 15) == 0) &&
                           (!g.mask || (g.ldmask % 8 == 0 && ((uintptr_t)g.mask & 15) == 0));
         if (fast)
-            return extras ? ws_x3_launch_ex<NB, NS, true, true>(g, transB, st)
+            return g.mask ? ws_x3_launch_ex<NB, NS, true, true, true>(g, transB, st)
+                 : extras ? ws_x3_launch_ex<NB, NS, true, true>(g, transB, st)
                           : ws_x3_launch_ex<NB, NS, false, true>(g, transB, st);
     }
     return extras ? ws_x3_launch_ex<NB, NS, true, false>(g, transB, st)
                   : ws_x3_launch_ex<NB, NS, false, false>(g, transB, st);
 }
 
-template <typename T, int NB, int NS, bool EX, bool FAST>
+template <typename T, int NB, int NS, bool EX, bool FAST, bool MK = false>
 gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     constexpr int NW = ws_waves<T, NB, NS>();
     constexpr size_t lds = ws_lds_bytes<T, NB, NS, NW>();
@@ -656,7 +655,7 @@ gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     // it (a host-side setting, no stream operation), so the first launch of an instance behaves
     // like any other, also under stream capture.
     if (lds > 64 * 1024) {
-        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX, FAST>),
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX, FAST, MK>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     }
     const int64_t nrb = (g.M + 31) / 32;
@@ -664,7 +663,7 @@ gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     int64_t gx = (nrb + NW - 1) / NW;
     if (gx > 256 * per_cu) gx = 256 * per_cu;
     dim3 grid((unsigned)gx, (unsigned)((g.N + NB * 32 - 1) / (NB * 32)), 1);
-    k_gemm_ws<T, NB, NS, EX, FAST><<<grid, NW * 64, lds, st>>>(g, transB);
+    k_gemm_ws<T, NB, NS, EX, FAST, MK><<<grid, NW * 64, lds, st>>>(g, transB);
     GT_LAUNCH_CHECK("k_gemm_ws");
     return GT_OK;
 }
@@ -673,10 +672,12 @@ template <typename T, int NB, int NS>
 gt_status ws_launch(const GemmArgs &g, int transB, hipStream_t st) {
     const bool extras = g.bias || g.relu || g.mask;
     if constexpr (NB >= 4) {   // the branch-free form exists for the wide slices, where the stores dominate
-        const bool fast = g.N % (NB * 32) == 0 && g.ldc % 4 == 0 && (((uintptr_t)g.C & 15) == 0) &&
+        // (a bf16 C is written 16 bytes, eight columns, per lane)
+        const bool fast = g.N % (NB * 32) == 0 && g.ldc % (sizeof(T) == 2 ? 8 : 4) == 0 && (((uintptr_t)g.C & 15) == 0) &&
                           (!g.mask || (g.ldmask % 8 == 0 && ((uintptr_t)g.mask & 15) == 0));
         if (fast)
-            return extras ? ws_launch_ex<T, NB, NS, true, true>(g, transB, st)
+            return g.mask ? ws_launch_ex<T, NB, NS, true, true, true>(g, transB, st)
+                 : extras ? ws_launch_ex<T, NB, NS, true, true>(g, transB, st)
                           : ws_launch_ex<T, NB, NS, false, true>(g, transB, st);
     }
     return extras ? ws_launch_ex<T, NB, NS, true, false>(g, transB, st)
