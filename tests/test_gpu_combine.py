@@ -26,7 +26,10 @@ SHAPES = [(1, 1, 1), (300, 64, 64), (257, 16, 100), (515, 41, 128), (130, 47, 25
           # tall with a small weight matrix: the weight-stationary kernel (row blocks with a ragged end,
           # K and N off the chunk sizes, N beyond one column slice, K at both capacities)
           (9001, 41, 128), (8200, 128, 41), (8300, 256, 256), (10007, 47, 100), (8193, 1024, 16), (12000, 300, 37),
-          (8192, 3, 5), (9000, 70, 250),
+          (8192, 3, 5), (9000, 70, 250), (9000, 200, 100), (8500, 256, 128),
+          # tall, wide fp32 rows onto at most 32 columns: the streaming form (16 and 32 weight rows kept, K a
+          # multiple of the 128-column pass and off it, K off the 16-byte vector)
+          (9000, 16, 1024), (8200, 29, 333), (20011, 7, 200), (8250, 32, 514),
           # the layers of a sampled batch: few rows, 64 x 64 tiles with a finely cut reduction; and a shape just
           # large enough to keep the big tiles
           (1024, 47, 256), (1100, 256, 47), (3000, 200, 300),
