@@ -179,7 +179,7 @@ def measure_traffic(args):
     with open(os.path.join(out_dir, "%s_kernel_stats.txt" % tag), "w") as f:
         f.write("rocprofv3 kernel-trace summary (made by: python3 bench.py --config %s --measure-traffic%s)\n" % (
             cfg, "" if tag == cfg else " --fwd-order %s --bwd-order %s" % (args.fwd_order, args.bwd_order)))
-        f.write("command: cd /tmp && TMPDIR=/tmp %s\n" % cmds[2])
+        f.write("command: cd /tmp && TMPDIR=/tmp %s\n" % next(c for c in cmds if "--kernel-trace" in c))
         f.write("bench line of the plain run that followed: ms_per_step %.4f, value %.4e %s, roofline kernel '%s' avg_launch_ms %.4f\n\n" % (
             plain["ms_per_step"], plain["value"], plain["unit"], plain["roofline"]["kernel"], plain["roofline"]["avg_launch_ms"]))
         f.write("%-100s %6s %12s %12s %7s\n" % ("kernel", "calls", "avg_us", "total_ms", "pct"))

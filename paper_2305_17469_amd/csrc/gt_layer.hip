@@ -26,8 +26,8 @@ typedef uint16_t bf16_t;
 // Coefficients in seconds, one set per data type (index: gt_dtype).  Defaults are the values
 // gt_calibrate fitted on an MI355X; gt_calibrate replaces them with values fitted on the device
 // at hand.
-gt_cost_coeffs g_cost[2] = {{1.12e-14, 1.25e-12, 4.89e-13, 1.04e-12, 9.1e-15, 1.58e-12, 4.49e-13, 1.26e-12, 4.2e-6},
-                            {7.85e-15, 9.95e-13, 2.33e-13, 7.3e-13, 4.05e-15, 1.0e-12, 1.94e-13, 1.03e-12, 4.6e-6}};
+gt_cost_coeffs g_cost[2] = {{1.06e-14, 1.39e-12, 4.87e-13, 1.06e-12, 8.78e-15, 1.66e-12, 4.48e-13, 1.27e-12, 4.3e-6},
+                            {7.03e-15, 9.42e-13, 2.32e-13, 6.93e-13, 4.18e-15, 9.19e-13, 1.95e-13, 9.42e-13, 4.6e-6}};
 const gt_cost_coeffs &cost_of(gt_dtype t) { return g_cost[t == GT_BF16 ? 1 : 0]; }
 
 // An aggregation launch cannot finish faster than the chain of dependent loads of one work item

@@ -155,3 +155,32 @@ def test_empty_rows_only():
     for reduce in ("sum", "mean"):
         assert torch.count_nonzero(B.gt_aggregate_fwd(g, reduce, X)) == 0
         assert torch.count_nonzero(B.gt_aggregate_bwd(g, reduce, up_feat(tensors.normal((7, 12), seed=2), "f32"))) == 0
+
+
+def test_bf16_outputs_round_to_nearest_even_bit_for_bit():
+    """Rows of two in-edges whose two bf16 terms differ by at most 8 binades: the fp32 sum is exact,
+    so the bf16 output must be THE nearest-even rounding of the exact sum, ties included (a large
+    share of such sums are ties), down to subnormal results and up to overflow."""
+    from paper_2305_17469_amd import binding as B
+    n, F = 8192, 8
+    rng = np.random.default_rng(77)
+    ea = rng.integers(90, 160, size=(n, F))
+    ea[:64] = rng.integers(0, 3, size=(64, F))          # subnormal and smallest normal terms
+    ea[64:128] = 254                                    # largest binade: same-sign sums overflow
+    eb = np.maximum(ea - rng.integers(0, 9, size=(n, F)), 0)
+    bits_a = (rng.integers(0, 2, size=(n, F)) << 15) | (ea << 7) | rng.integers(0, 128, size=(n, F))
+    bits_b = (rng.integers(0, 2, size=(n, F)) << 15) | (eb << 7) | rng.integers(0, 128, size=(n, F))
+    a = tensors.from_bf16_bits(bits_a.astype(np.uint16))
+    b = tensors.from_bf16_bits(bits_b.astype(np.uint16))
+    X = np.empty((2 * n, F), dtype=np.float32)
+    X[0::2], X[1::2] = a, b
+    assert np.array_equal(tensors.bf16_values(X), X)
+    exact = a.astype(np.float64) + b.astype(np.float64)
+    ref = oracle.round_bf16(exact)
+    assert (ref != exact).mean() > 0.3                                  # most sums do need rounding
+    g = B.Graph(up_i32(np.arange(0, 2 * n + 1, 2)), up_i32(np.arange(2 * n)), 2 * n)
+    announce("aggregate bf16 rounding", n, F)
+    got = down(B.gt_aggregate_fwd(g, "sum", up_feat(X, "bf16")))
+    assert np.isinf(ref).any() and not np.isnan(ref).any()
+    bad = got != ref
+    assert not bad.any(), (int(bad.sum()), exact[bad][:4], got[bad][:4], ref[bad][:4])
