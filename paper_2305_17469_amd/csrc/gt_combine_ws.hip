@@ -249,9 +249,12 @@ constexpr int ws_per_cu() { return ws_lds_bytes<T, NB, NS, 4>() <= 80 * 1024 ? 2
 // M store the last row's values onto the last row): with control flow in the loop the compiler
 // waits for ALL outstanding memory operations before it touches a prefetched slice, i.e. also for
 // the previous block's stores, which costs a store round trip per block.
-template <typename T, int NB, int NS, bool EX, bool FAST, bool MK>
+// HALF (one-slice instances): K is at most half a slice, the MFMA steps of the empty half are left out
+// (2^20 x 16 -> 1024 fp32 spent 0.44 of its 1.0 ms multiplying zeros).
+template <typename T, int NB, int NS, bool EX, bool FAST, bool MK, bool HALF>
 __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB, NS>())) k_gemm_ws(const GemmArgs g, const int transB) {
     constexpr int NW = ws_waves<T, NB, NS>(), NT = NW * 64;
+    static_assert(!HALF || NS == 1, "HALF is a form of the one-slice instances");
     constexpr int CK = WsGeom<T>::CK, HK = WsGeom<T>::HK, SK = WsGeom<T>::SK;
     constexpr int KP = NS * SK;                 // K capacity of this instance
     constexpr int WSTR = KP + WsGeom<T>::PAD;   // LDS row stride: 16 bytes past a multiple of 128
@@ -395,7 +398,7 @@ __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB
                 ws_load_slice<T>(R[s], A, g.lda, rb + stride, s, g.M, g.K, lane);
             }
 #pragma unroll
-            for (int c = 0; c < SK / CK; ++c) {
+            for (int c = 0; c < (HALF ? SK / CK / 2 : SK / CK); ++c) {
                 if (!FAST && (int64_t)s * SK + c * CK >= g.K) continue;   // uniform: nothing left in this slice
                 const uint4 a = *reinterpret_cast<const uint4 *>(As + l32 * ASTR + c * CK + h * HK);
                 const T *wrow = Ws + l32 * WSTR + s * SK + c * CK + h * HK;
@@ -793,7 +796,7 @@ gt_status ws_x3_launch(const GemmArgs &g, int transB, hipStream_t st) {
                   : ws_x3_launch_ex<NB, NS, false, false>(g, transB, st);
 }
 
-template <typename T, int NB, int NS, bool EX, bool FAST, bool MK = false>
+template <typename T, int NB, int NS, bool EX, bool FAST, bool MK = false, bool HALF = false>
 gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     constexpr int NW = ws_waves<T, NB, NS>();
     constexpr size_t lds = ws_lds_bytes<T, NB, NS, NW>();
@@ -801,7 +804,7 @@ gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     // it (a host-side setting, no stream operation), so the first launch of an instance behaves
     // like any other, also under stream capture.
     if (lds > 64 * 1024) {
-        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX, FAST, MK>),
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX, FAST, MK, HALF>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     }
     const int64_t nrb = (g.M + 31) / 32;
@@ -809,7 +812,7 @@ gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     int64_t gx = (nrb + NW - 1) / NW;
     if (gx > 256 * per_cu) gx = 256 * per_cu;
     dim3 grid((unsigned)gx, (unsigned)((g.N + NB * 32 - 1) / (NB * 32)), 1);
-    k_gemm_ws<T, NB, NS, EX, FAST, MK><<<grid, NW * 64, lds, st>>>(g, transB);
+    k_gemm_ws<T, NB, NS, EX, FAST, MK, HALF><<<grid, NW * 64, lds, st>>>(g, transB);
     GT_LAUNCH_CHECK("k_gemm_ws");
     return GT_OK;
 }
@@ -821,6 +824,12 @@ gt_status ws_launch(const GemmArgs &g, int transB, hipStream_t st) {
         // (a bf16 C is written 16 bytes, eight columns, per lane)
         const bool fast = g.N % (NB * 32) == 0 && g.ldc % (sizeof(T) == 2 ? 8 : 4) == 0 && (((uintptr_t)g.C & 15) == 0) &&
                           (!g.mask || (g.ldmask % 8 == 0 && ((uintptr_t)g.mask & 15) == 0));
+        if constexpr (NS == 1) {
+            if (fast && g.K <= WsGeom<T>::SK / 2)
+                return g.mask ? ws_launch_ex<T, NB, NS, true, true, true, true>(g, transB, st)
+                     : extras ? ws_launch_ex<T, NB, NS, true, true, false, true>(g, transB, st)
+                              : ws_launch_ex<T, NB, NS, false, true, false, true>(g, transB, st);
+        }
         if (fast)
             return g.mask ? ws_launch_ex<T, NB, NS, true, true, true>(g, transB, st)
                  : extras ? ws_launch_ex<T, NB, NS, true, true>(g, transB, st)
