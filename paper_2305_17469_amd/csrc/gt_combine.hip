@@ -522,7 +522,7 @@ TileShape pick_tile(int64_t M, int64_t N, int64_t K) {
 // 0.093 -> 0.06 ms).
 bool use_x3(gt_dtype dtype, int transA, int64_t M, int64_t N, int64_t K) {
     const bool big = (double)M * (double)N * (double)K >= 268435456.0;
-    return dtype == GT_F32 && K >= 64 && big && (N > 32 || (transA && N >= 32 && M <= 256));
+    return dtype == GT_F32 && K >= 64 && big && (N > 32 || (transA && N >= 32 && M <= 256) || (transA && M >= 256 && K >= 8192));
 }
 
 struct SplitPlan { int splits; int64_t k_per_split; };

@@ -158,18 +158,23 @@ struct LoadKM {
 
 // Workgroup tile: WGM x WGN wavefronts of 64 x 64 accumulators each: 128 x 128 (2 x 2) in general,
 // 256 x 64 (4 x 1) for outputs of at most 64 columns, where half of a 128-wide tile would be padding.
-template <int WGM, int WGN>
-constexpr size_t x3_lds_bytes() { return (size_t)3 * (WGM + WGN) * 64 * STR * 2; }
+// A wavefront holds TMW x TNW blocks of 32 x 32 (2 x 2 in those shapes); 32 x 256 (1 x 4 wavefronts of 1 x 2
+// blocks) serves weight gradients with at most 32 rows, whose 64-row tile was three quarters padding.
+template <int WGM, int WGN, int TMW, int TNW>
+constexpr size_t x3_lds_bytes() {
+    constexpr size_t planes = (size_t)3 * (WGM * TMW + WGN * TNW) * 32 * STR * 2, stages = (size_t)4 * GEMM_STAGE_FLOATS(TNW) * 4;
+    return planes > stages ? planes : stages;
+}
 
-template <bool TA, bool TB, bool VA, bool VB, int WGM, int WGN>
+template <bool TA, bool TB, bool VA, bool VB, int WGM, int WGN, int TMW, int TNW>
 __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
     static_assert(WGM * WGN == 4, "four wavefronts per workgroup");
-    constexpr int BM = WGM * 64, BN = WGN * 64;
+    constexpr int BM = WGM * TMW * 32, BN = WGN * TNW * 32;
     constexpr int PLANE_A = BM * STR, PLANE_B = BN * STR;
     // one LDS buffer: operand planes during the k-loop, the per-wavefront output stages afterwards
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     gemm_bf16_t *smem = reinterpret_cast<gemm_bf16_t *>(smem_raw);
-    static_assert(x3_lds_bytes<WGM, WGN>() >= 4 * GEMM_STAGE_FLOATS(2) * 4, "output stages must fit");
+    static_assert(x3_lds_bytes<WGM, WGN, TMW, TNW>() >= 4 * GEMM_STAGE_FLOATS(TNW) * 4, "output stages must fit");
     gemm_bf16_t *As = smem, *Bs = smem + 3 * PLANE_A;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, h = lane >> 5;
@@ -183,11 +188,11 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
     const float *A = static_cast<const float *>(g.A);
     const float *B = static_cast<const float *>(g.B);
 
-    floatx16 acc[2][2];
+    floatx16 acc[TMW][TNW];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < TMW; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < TNW; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
 
@@ -223,25 +228,25 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             const int kk = s * 16 + h * 8;   // lane half h supplies k = kk .. kk+7 of this step
-            bf16x8 af[2][3], bf[2][3];
+            bf16x8 af[TMW][3], bf[TNW][3];
 #pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                const int i = (wm * 2 + a) * 32 + l32;
+            for (int a = 0; a < TMW; ++a) {
+                const int i = (wm * TMW + a) * 32 + l32;
 #pragma unroll
                 for (int p = 0; p < 3; ++p)
                     af[a][p] = *reinterpret_cast<const bf16x8 *>(&As[p * PLANE_A + i * STR + kk]);
             }
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                const int j = (wn * 2 + b) * 32 + l32;
+            for (int b = 0; b < TNW; ++b) {
+                const int j = (wn * TNW + b) * 32 + l32;
 #pragma unroll
                 for (int p = 0; p < 3; ++p)
                     bf[b][p] = *reinterpret_cast<const bf16x8 *>(&Bs[p * PLANE_B + j * STR + kk]);
             }
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < TMW; ++a)
 #pragma unroll
-                for (int b = 0; b < 2; ++b) {
+                for (int b = 0; b < TNW; ++b) {
                     floatx16 c = acc[a][b];
                     // smallest terms first: lo*hi, hi*lo, mid*mid, then mid*hi, hi*mid, then hi*hi
                     c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a][2], bf[b][0], c, 0, 0, 0);
@@ -259,7 +264,7 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
         if (do_cs) {   // uniform over the workgroup
             // thread t holds, per patch q, columns 4 ((t >> 3) + 32 q) ..; the eight threads t & 7 that share
             // them (they loaded different k) are added in thread order
-            static_assert((size_t)256 * NPB * 4 * 4 <= x3_lds_bytes<WGM, WGN>(), "column-sum staging");
+            static_assert((size_t)256 * NPB * 4 * 4 <= x3_lds_bytes<WGM, WGN, TMW, TNW>(), "column-sum staging");
             float *red = reinterpret_cast<float *>(smem_raw);
 #pragma unroll
             for (int q = 0; q < NPB; ++q)
@@ -275,37 +280,37 @@ __global__ void __launch_bounds__(256) k_gemm_x3(const GemmArgs g) {
             __syncthreads();
         }
     }
-    gemm_epilogue<2, 2>(g, acc, m0 + wm * 64, n0 + wn * 64, l32, h,
-                        reinterpret_cast<float *>(smem_raw) + wave * GEMM_STAGE_FLOATS(2), split);
+    gemm_epilogue<TMW, TNW>(g, acc, m0 + wm * TMW * 32, n0 + wn * TNW * 32, l32, h,
+                            reinterpret_cast<float *>(smem_raw) + wave * GEMM_STAGE_FLOATS(TNW), split);
 }
 
 
-template <bool TA, bool TB, bool VA, bool VB, int WGM, int WGN>
+template <bool TA, bool TB, bool VA, bool VB, int WGM, int WGN, int TMW, int TNW>
 gt_status x3_launch_one(const GemmArgs &g, dim3 grid, hipStream_t st) {
-    constexpr size_t lds = x3_lds_bytes<WGM, WGN>();
+    constexpr size_t lds = x3_lds_bytes<WGM, WGN, TMW, TNW>();
     if (lds > 64 * 1024) {   // host-side setting, no stream operation (also fine under stream capture)
-        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_x3<TA, TB, VA, VB, WGM, WGN>),
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_x3<TA, TB, VA, VB, WGM, WGN, TMW, TNW>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     }
-    k_gemm_x3<TA, TB, VA, VB, WGM, WGN><<<grid, 256, lds, st>>>(g);
+    k_gemm_x3<TA, TB, VA, VB, WGM, WGN, TMW, TNW><<<grid, 256, lds, st>>>(g);
     GT_LAUNCH_CHECK("k_gemm_x3");
     return GT_OK;
 }
 
-template <int WGM, int WGN>
+template <int WGM, int WGN, int TMW = 2, int TNW = 2>
 gt_status x3_launch_shape(const GemmArgs &g_in, int transA, int transB, int splits, hipStream_t st) {
     GemmArgs g = g_in;
-    constexpr int BM = WGM * 64, BN = WGN * 64;
+    constexpr int BM = WGM * TMW * 32, BN = WGN * TNW * 32;
     g.ntn = (int)((g.N + BN - 1) / BN);
     g.ntm = (int)((g.M + BM - 1) / BM);
     dim3 grid(gemm_grid_x(g.ntm, g.ntn), 1, (unsigned)splits);
     g.split_xcd = gemm_split_xcd(g.ntm, g.ntn, splits);
 #define GT_X3(TA_, TB_)                                                                                   \
     do {                                                                                                  \
-        if (g.vecA && g.vecB) return x3_launch_one<TA_, TB_, true, true, WGM, WGN>(g, grid, st);          \
-        else if (g.vecA) return x3_launch_one<TA_, TB_, true, false, WGM, WGN>(g, grid, st);              \
-        else if (g.vecB) return x3_launch_one<TA_, TB_, false, true, WGM, WGN>(g, grid, st);              \
-        else return x3_launch_one<TA_, TB_, false, false, WGM, WGN>(g, grid, st);                         \
+        if (g.vecA && g.vecB) return x3_launch_one<TA_, TB_, true, true, WGM, WGN, TMW, TNW>(g, grid, st);          \
+        else if (g.vecA) return x3_launch_one<TA_, TB_, true, false, WGM, WGN, TMW, TNW>(g, grid, st);              \
+        else if (g.vecB) return x3_launch_one<TA_, TB_, false, true, WGM, WGN, TMW, TNW>(g, grid, st);              \
+        else return x3_launch_one<TA_, TB_, false, false, WGM, WGN, TMW, TNW>(g, grid, st);                         \
     } while (0)
     if (!transA && !transB) GT_X3(false, false);
     else if (!transA && transB) GT_X3(false, true);
@@ -319,14 +324,22 @@ gt_status x3_launch_shape(const GemmArgs &g_in, int transA, int transB, int spli
 // Tile of the split-bf16 kernel for an M x N output: 256 x 64 for at most 64 columns, 64 x 256 for at
 // most 64 rows (the weight gradient of a layer with a narrow input: a 128-row tile would be mostly
 // padding, and the padding is multiplied like everything else), 128 x 128 otherwise.
+// up to this many rows a 256 x 64 tiling leaves the CUs unevenly loaded (fewer than two rounds of tiles)
+#define X3_SHORT_ROWS 196608
 void gt_gemm_x3_tile(int64_t M, int64_t N, int64_t *bm, int64_t *bn) {
-    if (N <= 64) { *bm = 256; *bn = 64; }
+    if (N <= 32) { *bm = 256; *bn = 32; }
+    else if (N <= 64 && M <= X3_SHORT_ROWS) { *bm = 128; *bn = 64; }
+    else if (N <= 64) { *bm = 256; *bn = 64; }
+    else if (M <= 32) { *bm = 32; *bn = 256; }
     else if (M <= 64) { *bm = 64; *bn = 256; }
     else { *bm = 128; *bn = 128; }
 }
 
 gt_status gt_gemm_x3_launch(const GemmArgs &g, int transA, int transB, int splits, hipStream_t st) {
+    if (g.N <= 32) return x3_launch_shape<4, 1, 2, 1>(g, transA, transB, splits, st);
+    if (g.N <= 64 && g.M <= X3_SHORT_ROWS) return x3_launch_shape<4, 1, 1, 2>(g, transA, transB, splits, st);
     if (g.N <= 64) return x3_launch_shape<4, 1>(g, transA, transB, splits, st);
+    if (g.M <= 32) return x3_launch_shape<1, 4, 1, 2>(g, transA, transB, splits, st);
     if (g.M <= 64) return x3_launch_shape<1, 4>(g, transA, transB, splits, st);
     return x3_launch_shape<2, 2>(g, transA, transB, splits, st);
 }

@@ -35,6 +35,10 @@ SHAPES = [(1, 1, 1), (300, 64, 64), (257, 16, 100), (515, 41, 128), (130, 47, 25
           (1024, 47, 256), (1100, 256, 47), (3000, 200, 300),
           # at most 64 output rows over a long reduction: 64 x 256 tiles of the split-bf16 kernel
           (48, 300, 20000),
+          # at most 32 output rows: 32 x 256 tiles
+          (16, 1024, 30000), (30, 260, 20000),
+          # ... and at most 32 columns under many rows: 256 x 32 tiles
+          (1024, 16, 30000), (300, 29, 20000),
           # weight-gradient shapes over a long reduction, split over workgroups (bf16: the transposing-load kernel)
           (256, 256, 20000), (100, 250, 12000), (200, 130, 11000)]
 
