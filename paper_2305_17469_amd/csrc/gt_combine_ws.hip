@@ -619,28 +619,29 @@ __global__ void __launch_bounds__(256, (ws_x3_per_cu<NB, NS>())) k_gemm_ws_x3(co
 }
 
 // ---------------------------------------------------------------------------------------------
-// Wide fp32 rows onto a narrow output: C[M, N] = act(A[M, K] op(B) + bias) with N <= 32 and K in the
-// hundreds up to about a thousand (a first layer that shrinks a wide input).  The product is bound
-// by reading A once.  Same scheme as above (three bf16 weight planes resident in LDS, wavefronts
-// working alone on 32-row blocks through a private stage), but a row no longer fits the registers,
-// so a wavefront streams it in slices of 128 bytes with four slices (16 KB) of loads in flight; the
-// ring of four register sets is addressed statically by unrolling four slices per pass of the
-// k-loop, which has no branch in it.  One 32-column MFMA block; for N <= 16 only 16 weight rows
-// are kept (lanes 16..31 of the weight operand re-read rows 0..15; their output columns are never
-// stored), which is what lets K = 1024 fit: 3 x 16 x 1032 x 2 bytes = 97 KB.
-// NR: weight rows kept (16 or 32); nsp: slices per row, padded to a multiple of four (padding
-// slices re-read the row's first chunk and are staged as zeros).
+// Wide fp32 rows onto a narrow output: C[M, N] = act(A[M, K] op(B) + bias) with N <= 32 and K from
+// 129 to 1,024 (a first layer that shrinks a wide input).  The product is bound by reading A once.
+// Same scheme as above (three bf16 weight planes resident in LDS, wavefronts working alone on 32-row
+// blocks through a private stage), but a row no longer fits the registers, so a wavefront streams
+// it in slices of 128 bytes with four slices (16 KB) of loads in flight, held in a ring of four
+// register sets.  The slice loop is unrolled completely (NSP = 8, 16 or 32 slices, K rounded up; a
+// padding slice re-reads the row's first chunk and is staged as zeros): with a run-time loop the
+// compiler drains every outstanding load at the loop head, which leaves one slice of work to hide
+// a memory latency.  One 32-column MFMA block; for N <= 16 only 16 weight rows are kept (lanes
+// 16..31 of the weight operand re-read rows 0..15; their output columns are never stored), which
+// is what lets K = 1,024 fit: 3 x 16 x 1032 x 2 bytes = 97 KB.
+// KFULL: K = 32 NSP, so no slice needs masking or clamping.  NR: weight rows kept (16 or 32).
 // ---------------------------------------------------------------------------------------------
 constexpr int WS_STREAM_WAVES = 8, WS_STREAM_PD = 4;
-static size_t ws_stream_lds_bytes(int NR, int nsp) {
-    return (size_t)3 * NR * (nsp * 32 + 8) * 2 + (size_t)WS_STREAM_WAVES * GEMM_STAGE_FLOATS(1) * 4 + 32 * 4;
+static size_t ws_stream_lds_bytes(int NR, int64_t K) {
+    const int64_t kr = (K + 31) / 32 * 32;
+    return (size_t)3 * NR * (kr + 8) * 2 + (size_t)WS_STREAM_WAVES * GEMM_STAGE_FLOATS(1) * 4 + 32 * 4;
 }
 
-template <bool EX>
-__global__ void __launch_bounds__(WS_STREAM_WAVES * 64, 1) k_gemm_ws_stream_x3(const GemmArgs g, const int transB, const int NR,
-                                                                              const int nsp) {
+template <bool EX, bool KFULL, int NSP>
+__global__ void __launch_bounds__(WS_STREAM_WAVES * 64, 1) k_gemm_ws_stream_x3(const GemmArgs g, const int transB, const int NR) {
     constexpr int SK = 32, ASTR = SK + 4, NW = WS_STREAM_WAVES, NT = NW * 64, PD = WS_STREAM_PD;
-    const int KP = nsp * SK, WSTR = KP + 8, PLANE = NR * WSTR;
+    const int KR = (int)((g.K + SK - 1) / SK) * SK, WSTR = KR + 8, PLANE = NR * WSTR;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *Wp = reinterpret_cast<bf16_t *>(smem);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -651,9 +652,9 @@ __global__ void __launch_bounds__(WS_STREAM_WAVES * 64, 1) k_gemm_ws_stream_x3(c
     const float *B = static_cast<const float *>(g.B);
     if (threadIdx.x < 32) bias_lds[threadIdx.x] = (g.bias && threadIdx.x < g.N) ? g.bias[threadIdx.x] : 0.0f;
     // the weights, once per workgroup, as three planes Wp[plane][n][k], zero outside (K, N)
-    for (int idx = threadIdx.x; idx < NR * KP; idx += NT) {
+    for (int idx = threadIdx.x; idx < NR * KR; idx += NT) {
         int n, k;
-        if (transB) { n = idx / KP; k = idx % KP; } else { k = idx / NR; n = idx % NR; }
+        if (transB) { n = idx / KR; k = idx % KR; } else { k = idx / NR; n = idx % NR; }
         const bool ok = n < g.N && k < g.K;
         const float x = ok ? B[transB ? (int64_t)n * g.ldb + k : (int64_t)k * g.ldb + n] : 0.0f;
         uint32_t hi, mi, lo;
@@ -670,98 +671,133 @@ __global__ void __launch_bounds__(WS_STREAM_WAVES * 64, 1) k_gemm_ws_stream_x3(c
     const int64_t stride = (int64_t)gridDim.x * NW;
     int64_t rb = (int64_t)blockIdx.x * NW + wave;
     if (rb >= nrb) return;   // no workgroup barrier below this point
+    // this lane's four rows of a block (lane / 8 + 8 i, clamped to the last row) at its 16-byte chunk of a slice
+    auto row_ptrs = [&](const float *(&rp)[4], int64_t blk) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int64_t row = blk * 32 + (lane >> 3) + 8 * i;
+            if (row >= g.M) row = g.M - 1;
+            rp[i] = A + row * g.lda + (lane & 7) * 4;
+        }
+    };
+    // kb: this lane's element offset inside a slice, (lane & 7) * 4.  The loop below passes it through an empty
+    // asm statement once per block: otherwise the compiler computes the masks of all NSP slices once, ahead of
+    // the block loop, and keeps them in registers (spilling them when NSP = 32)
+    auto load_slice = [&](uint4 (&r)[4], const float *const (&rp)[4], int s, int kb) {
+        int k = s * SK;
+        if (!KFULL && k + kb >= g.K) k = -kb;   // chunks at or past K re-read the row's first chunk
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = *reinterpret_cast<const uint4 *>(rp[i] + k);
+    };
+    const float *rp[4], *rpn[4];
+    row_ptrs(rp, rb);
     uint4 R[PD][4];
 #pragma unroll
-    for (int j = 0; j < PD; ++j) ws_load_slice<float>(R[j], A, g.lda, rb, j, g.M, g.K, lane);
+    for (int j = 0; j < PD; ++j) load_slice(R[j], rp, j, (lane & 7) * 4);
     const bf16_t *wlane = Wp + (l32 & (NR - 1)) * WSTR + h * 8;
     for (; rb < nrb; rb += stride) {
         const int64_t rb_next = rb + stride < nrb ? rb + stride : rb;
+        row_ptrs(rpn, rb_next);
+        int kb = (lane & 7) * 4;
+        if (!KFULL) __asm__ volatile("" : "+v"(kb));
         floatx16 acc[1];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const float4 c = *reinterpret_cast<const float4 *>(bias_lds + 8 * q + 4 * h);
             acc[0][4 * q] = c.x; acc[0][4 * q + 1] = c.y; acc[0][4 * q + 2] = c.z; acc[0][4 * q + 3] = c.w;
         }
-        for (int s0 = 0; s0 < nsp; s0 += PD) {
 #pragma unroll
-            for (int j = 0; j < PD; ++j) {
-                const int s = s0 + j;
-                __asm__ volatile("" ::: "memory");     // stage writes stay below the previous slice's fragment reads
-                const int64_t left = g.K - ((int64_t)s * SK + (lane & 7) * 4);
-                const int nv = left >= 4 ? 4 : (left > 0 ? (int)left : 0);
+        for (int s = 0; s < NSP; ++s) {
+            const int j = s % PD;
+            __asm__ volatile("" ::: "memory");     // stage writes stay below the previous slice's fragment reads
+            const int left = (int)g.K - (s * SK + kb);
+            const int nv = left >= 4 ? 4 : (left > 0 ? left : 0);
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    *reinterpret_cast<uint4 *>(As + ((lane >> 3) + 8 * i) * ASTR + (lane & 7) * 4) = ws_mask<float>(R[j][i], nv);
-                // refill: four slices ahead, which is the next block's row once this one's slices are all requested
-                const bool wrap = s + PD >= nsp;
-                ws_load_slice<float>(R[j], A, g.lda, wrap ? rb_next : rb, wrap ? s + PD - nsp : s + PD, g.M, g.K, lane);
+            for (int i = 0; i < 4; ++i)
+                *reinterpret_cast<uint4 *>(As + ((lane >> 3) + 8 * i) * ASTR + (lane & 7) * 4) =
+                    KFULL ? R[j][i] : ws_mask<float>(R[j][i], nv);
+            // refill: four slices ahead, which is the next block's row once this one's slices are all requested
+            if (s + PD < NSP) load_slice(R[j], rp, s + PD, kb);
+            else load_slice(R[j], rpn, s + PD - NSP, kb);
+            // a padding slice (all zeros in the stage) multiplies the last real slice's weights
+            const int ks = KFULL ? s * SK : (s * SK < KR ? s * SK : KR - SK);
 #pragma unroll
-                for (int t = 0; t < SK / 16; ++t) {    // MFMA steps of 16 k: lane half h supplies k = 16 t + 8 h .. + 7
-                    const float *ap = As + l32 * ASTR + t * 16 + h * 8;
-                    const float4 a0 = *reinterpret_cast<const float4 *>(ap), a1 = *reinterpret_cast<const float4 *>(ap + 4);
-                    const float x[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-                    uint32_t hi[8], mi[8], lo[8];
+            for (int t = 0; t < SK / 16; ++t) {    // MFMA steps of 16 k: lane half h supplies k = 16 t + 8 h .. + 7
+                const float *ap = As + l32 * ASTR + t * 16 + h * 8;
+                const float4 a0 = *reinterpret_cast<const float4 *>(ap), a1 = *reinterpret_cast<const float4 *>(ap + 4);
+                const float x[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                uint32_t hi[8], mi[8], lo[8];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) ws_split3(x[q], hi[q], mi[q], lo[q]);
-                    uint4 ph, pm, pl;
-                    ph = make_uint4(ws_pack_hi16(hi[0], hi[1]), ws_pack_hi16(hi[2], hi[3]), ws_pack_hi16(hi[4], hi[5]), ws_pack_hi16(hi[6], hi[7]));
-                    pm = make_uint4(ws_pack_hi16(mi[0], mi[1]), ws_pack_hi16(mi[2], mi[3]), ws_pack_hi16(mi[4], mi[5]), ws_pack_hi16(mi[6], mi[7]));
-                    pl = make_uint4(ws_pack_hi16(lo[0], lo[1]), ws_pack_hi16(lo[2], lo[3]), ws_pack_hi16(lo[4], lo[5]), ws_pack_hi16(lo[6], lo[7]));
-                    bf16x8 ah, am, al;
-                    __builtin_memcpy(&ah, &ph, 16);
-                    __builtin_memcpy(&am, &pm, 16);
-                    __builtin_memcpy(&al, &pl, 16);
-                    const bf16_t *wrow = wlane + s * SK + t * 16;
-                    const bf16x8 wh = *reinterpret_cast<const bf16x8 *>(wrow);
-                    const bf16x8 wm = *reinterpret_cast<const bf16x8 *>(wrow + PLANE);
-                    const bf16x8 wl = *reinterpret_cast<const bf16x8 *>(wrow + 2 * PLANE);
-                    floatx16 cc = acc[0];
-                    // smallest terms first: lo*hi, hi*lo, mid*mid, then mid*hi, hi*mid, then hi*hi
-                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wl, ah, cc, 0, 0, 0);
-                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh, al, cc, 0, 0, 0);
-                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wm, am, cc, 0, 0, 0);
-                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wm, ah, cc, 0, 0, 0);
-                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh, am, cc, 0, 0, 0);
-                    cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh, ah, cc, 0, 0, 0);
-                    acc[0] = cc;
-                }
+                for (int q = 0; q < 8; ++q) ws_split3(x[q], hi[q], mi[q], lo[q]);
+                uint4 ph, pm, pl;
+                ph = make_uint4(ws_pack_hi16(hi[0], hi[1]), ws_pack_hi16(hi[2], hi[3]), ws_pack_hi16(hi[4], hi[5]), ws_pack_hi16(hi[6], hi[7]));
+                pm = make_uint4(ws_pack_hi16(mi[0], mi[1]), ws_pack_hi16(mi[2], mi[3]), ws_pack_hi16(mi[4], mi[5]), ws_pack_hi16(mi[6], mi[7]));
+                pl = make_uint4(ws_pack_hi16(lo[0], lo[1]), ws_pack_hi16(lo[2], lo[3]), ws_pack_hi16(lo[4], lo[5]), ws_pack_hi16(lo[6], lo[7]));
+                bf16x8 ah, am, al;
+                __builtin_memcpy(&ah, &ph, 16);
+                __builtin_memcpy(&am, &pm, 16);
+                __builtin_memcpy(&al, &pl, 16);
+                const bf16_t *wrow = wlane + ks + t * 16;
+                const bf16x8 wh = *reinterpret_cast<const bf16x8 *>(wrow);
+                const bf16x8 wm = *reinterpret_cast<const bf16x8 *>(wrow + PLANE);
+                const bf16x8 wl = *reinterpret_cast<const bf16x8 *>(wrow + 2 * PLANE);
+                floatx16 cc = acc[0];
+                // smallest terms first: lo*hi, hi*lo, mid*mid, then mid*hi, hi*mid, then hi*hi
+                cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wl, ah, cc, 0, 0, 0);
+                cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh, al, cc, 0, 0, 0);
+                cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wm, am, cc, 0, 0, 0);
+                cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wm, ah, cc, 0, 0, 0);
+                cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh, am, cc, 0, 0, 0);
+                cc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wh, ah, cc, 0, 0, 0);
+                acc[0] = cc;
             }
         }
         const int64_t row = rb * 32 + l32;
         if (row < g.M) ws_epilogue<false, EX, false, 1>(g, acc, row, 0, h, out_vec);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) rp[i] = rpn[i];
     }
 }
 
-// shapes of the streaming kernel: fp32, N <= 32, rows longer than the register-resident kernels take
-// and short enough for the three weight planes to fit in LDS beside the stages
+// shapes of the streaming kernel: fp32, N <= 32, rows longer than the register-resident kernels take,
+// at most 1,024 elements, and short enough for the three weight planes to fit in LDS beside the stages
 static bool ws_stream_shape(gt_dtype dtype, int64_t N, int64_t K, int *NR, int *nsp) {
-    if (dtype != GT_F32 || N > 32 || K <= 4 * WsGeom<float>::SK || K > 4096) return false;
+    if (dtype != GT_F32 || N > 32 || K <= 4 * WsGeom<float>::SK || K > 1024) return false;
     const int nr = N <= 16 ? 16 : 32;
-    const int ns = (int)((K + 127) / 128) * 4;
-    if (ws_stream_lds_bytes(nr, ns) > 160 * 1024) return false;
-    *NR = nr; *nsp = ns;
+    if (ws_stream_lds_bytes(nr, K) > 160 * 1024) return false;
+    *NR = nr; *nsp = K <= 256 ? 8 : (K <= 512 ? 16 : 32);
     return true;
+}
+
+template <int NSP>
+static gt_status ws_stream_launch_n(const GemmArgs &g, int transB, int NR, hipStream_t st) {
+    const size_t lds = ws_stream_lds_bytes(NR, g.K);
+    const bool extras = g.bias || g.relu || g.mask;
+    const int64_t nrb = (g.M + 31) / 32;
+    int64_t gx = (nrb + WS_STREAM_WAVES - 1) / WS_STREAM_WAVES;
+    if (gx > 256) gx = 256;
+    const bool kfull = g.K == 32 * NSP;
+#define GT_WS_STREAM(EX_, KF_)                                                                                       \
+    do {                                                                                                             \
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws_stream_x3<EX_, KF_, NSP>),              \
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                           \
+        k_gemm_ws_stream_x3<EX_, KF_, NSP><<<(unsigned)gx, WS_STREAM_WAVES * 64, lds, st>>>(g, transB, NR);          \
+    } while (0)
+    if (extras && kfull) GT_WS_STREAM(true, true);
+    else if (extras) GT_WS_STREAM(true, false);
+    else if (kfull) GT_WS_STREAM(false, true);
+    else GT_WS_STREAM(false, false);
+#undef GT_WS_STREAM
+    GT_LAUNCH_CHECK("k_gemm_ws_stream_x3");
+    return GT_OK;
 }
 
 static gt_status ws_stream_launch(const GemmArgs &g, int transB, hipStream_t st) {
     int NR = 0, nsp = 0;
     if (!ws_stream_shape(GT_F32, g.N, g.K, &NR, &nsp)) return gt_fail(GT_ERR_INTERNAL, "ws_stream_launch: shape not supported");
-    const size_t lds = ws_stream_lds_bytes(NR, nsp);
-    const bool extras = g.bias || g.relu || g.mask;
-    const int64_t nrb = (g.M + 31) / 32;
-    int64_t gx = (nrb + WS_STREAM_WAVES - 1) / WS_STREAM_WAVES;
-    if (gx > 256) gx = 256;
-    if (extras) {
-        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws_stream_x3<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        k_gemm_ws_stream_x3<true><<<(unsigned)gx, WS_STREAM_WAVES * 64, lds, st>>>(g, transB, NR, nsp);
-    } else {
-        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws_stream_x3<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        k_gemm_ws_stream_x3<false><<<(unsigned)gx, WS_STREAM_WAVES * 64, lds, st>>>(g, transB, NR, nsp);
-    }
-    GT_LAUNCH_CHECK("k_gemm_ws_stream_x3");
-    return GT_OK;
+    if (nsp == 8) return ws_stream_launch_n<8>(g, transB, NR, st);
+    if (nsp == 16) return ws_stream_launch_n<16>(g, transB, NR, st);
+    return ws_stream_launch_n<32>(g, transB, NR, st);
 }
 
 template <int NB, int NS, bool EX, bool FAST, bool MK = false>
