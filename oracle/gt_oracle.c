@@ -13,7 +13,7 @@
  *   - the combination (MLP: linear transform, bias, non-linearity; paper "Algorithm model"
  *     and the GNN Kernel Orchestrator section's sigma(W f(h(X)) + b)).
  *
- * Readings the paper leaves open (all listed in the design notes of this repository):
+ * Readings the paper leaves open:
  *   mean divides by the number of in-edges of the row (empty row -> 0); the symmetric
  *   normalisation uses 1/sqrt(d(u) d(v)) with d = in-degree taken from the given CSR for both
  *   ends (square graphs only); a per-edge scalar weight multiplies each term in every mode.

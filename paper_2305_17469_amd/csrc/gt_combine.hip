@@ -289,10 +289,9 @@ __global__ void __launch_bounds__(256) k_gemm(const GemmArgs g) {
 // k of one row.  The general kernel above leaves the tiles k-major in LDS and builds every fragment
 // from eight 2-byte LDS reads; here a thread loads a 4 (k) x 8 (row) patch (four 16-byte loads),
 // transposes it in registers and writes eight 8-byte k-runs, so the tiles sit in LDS as [row][k] and a
-// fragment is one 16-byte read (a quarter of the LDS instructions; measured on MI355X, 256 x 256 over
-// 2^21 rows: see the design notes).  128 x 128 workgroup tile, 4 wavefronts of 64 x 64, k-tile 32:
-// threads 0..127 load the A tile, 128..255 the B tile.  Split over k like k_gemm (partials in g.C when
-// gridDim.z > 1), same epilogue, same column-sum by-product.
+// fragment is one 16-byte read (a quarter of the LDS instructions).  The first half of the threads loads
+// the A tile, the second half the B tile.  Split over k like k_gemm (partials in g.C when gridDim.z > 1),
+// same epilogue, same column-sum by-product.
 __device__ inline uint32_t tn_lo(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }   // lo16(a) | lo16(b) << 16
 __device__ inline uint32_t tn_hi(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }   // hi16(a) | hi16(b) << 16
 
@@ -516,10 +515,11 @@ TileShape pick_tile(int64_t M, int64_t N, int64_t K) {
 // (3/8 of the fp32 MFMA cost at fp32-level accuracy): 128 x 128 tiles in general, 256 x 64 tiles for
 // outputs of 33..64 columns (a sampled block's 91 K x 602 -> 64 product: 111 -> 80 us; the plain kernel's
 // 357 tiles of slow fp32 MFMA, four wavefronts each, passed over the 1,024 SIMDs twice), 64 x 256 tiles
-// for outputs of at most 64 rows.  Narrower outputs keep the plain fp32 MFMA (256 x 32 tiles), except a
-// small weight gradient (at most 256 x 64 outputs over a long reduction), where the plain kernel's tile
-// is mostly padding and the slow fp32 MFMA makes that padding the bottleneck (config 2, 128 x 41:
-// 0.093 -> 0.06 ms).
+// for outputs of at most 64 rows (32 x 256 for at most 32).  Narrower outputs keep the plain fp32 MFMA
+// (256 x 32 tiles), except weight gradients: a small one (at most 256 x 64 outputs over a long reduction),
+// where the plain kernel's tile is mostly padding and the slow fp32 MFMA makes that padding the bottleneck
+// (config 2, 128 x 41: 0.093 -> 0.06 ms), and one of at most 32 columns under at least 256 rows over a
+// long reduction (256 x 32 split-bf16 tiles; 1024 x 16 over 2^20 rows: 0.87 -> 0.85 ms).
 bool use_x3(gt_dtype dtype, int transA, int64_t M, int64_t N, int64_t K) {
     const bool big = (double)M * (double)N * (double)K >= 268435456.0;
     return dtype == GT_F32 && K >= 64 && big && (N > 32 || (transA && N >= 32 && M <= 256) || (transA && M >= 256 && K >= 8192));

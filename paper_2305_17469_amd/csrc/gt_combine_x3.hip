@@ -10,7 +10,8 @@
 // the shapes of the combination that are bound by matrix throughput (wide K and N); the skinny,
 // memory-bound shapes stay on the plain fp32 MFMA kernel.
 //
-// Layout: 128 x 128 workgroup tile, 4 wavefronts of 64 x 64 accumulators, k-tile 32.  Both
+// Layout: 4 wavefronts, in general 64 x 64 accumulators each on a 128 x 128 workgroup tile (other
+// tiles: see x3_lds_bytes), k-tile 32.  Both
 // operands are converted and split while they are stored to LDS, k-contiguous per row
 // ([row][k], three planes), so every MFMA fragment is one ds_read_b128.  Operands whose global
 // layout is k-major (the weight matrix, both operands of the weight gradient) are transposed on
