@@ -132,3 +132,52 @@ def test_weight_gradient_shape_split_reduction(dtype):
     st = B.lib.gt_combine(0, 1, 0, fi, fo, rows, Ad.data_ptr(), Ad.stride(0), Gd.data_ptr(), Gd.stride(0), None, 0,
                           C1.data_ptr(), fo, 0, None, 0, None) if dtype == "f32" else 3
     assert st == 3   # the split reduction needs its workspace
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_combine_random_shapes_around_the_kernel_boundaries(seed):
+    """Seeded random (M, N, K, transposes, padding, epilogue) drawn from the sizes at which the library
+    changes kernel or tile: row lengths around the slice and capacity limits of the weight-stationary
+    and streaming forms, widths around the 32 / 64 / 128 / 256-column tiles, tall outputs, long
+    reductions (split over workgroups)."""
+    from paper_2305_17469_amd import binding as B
+    rng = np.random.default_rng(seed)
+    Ks = [1, 5, 16, 17, 32, 33, 47, 64, 65, 100, 128, 129, 200, 256, 257, 333, 512, 514, 602, 1000, 1024, 1025]
+    Ns = [1, 3, 7, 16, 17, 29, 32, 33, 41, 47, 64, 65, 100, 128, 129, 200, 256, 257, 300, 512, 1024]
+    for it in range(60):
+        kind = it % 3
+        dtype = "bf16" if rng.random() < 0.5 else "f32"
+        if kind == 0:      # tall forward shapes
+            M, N, K, tA = int(rng.choice([8192, 8193, 9000, 12345, 20011])), int(rng.choice(Ns)), int(rng.choice(Ks)), False
+        elif kind == 1:    # weight-gradient shapes
+            M, N, K, tA = int(rng.choice(Ns)), int(rng.choice(Ns)), int(rng.choice([8192, 9001, 20000, 30011])), True
+        else:
+            M, N, K, tA = int(rng.integers(1, 700)), int(rng.choice(Ns)), int(rng.choice(Ks)), bool(rng.integers(0, 2))
+        tB, padded, extras = bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        if M * N * K > 2e9:
+            continue
+        A = tensors.normal((M, K), seed=1000 * seed + it * 3)
+        Bm = tensors.normal((K, N), seed=1000 * seed + it * 3 + 1)
+        bias = tensors.normal((N,), seed=1000 * seed + it * 3 + 2)
+        if dtype == "bf16":
+            A, Bm = tensors.bf16_values(A), tensors.bf16_values(Bm)
+        a_host = A.T.copy() if tA else A
+        b_host = Bm.T.copy() if tB else Bm
+        v = 8 if dtype == "bf16" else 4
+        lda = (a_host.shape[1] + v - 1) // v * v if padded else a_host.shape[1]
+        ldb = (b_host.shape[1] + v - 1) // v * v if padded else b_host.shape[1]
+        announce("combine random", seed, it, dtype, (M, N, K), "tA", tA, "tB", tB, "padded", padded, "extras", extras)
+        Ad, Bd = up_feat(a_host, dtype, lda), up_feat(b_host, dtype, ldb)
+        absr = oracle.combine(np.abs(A), np.abs(Bm))
+        if extras:
+            C = B.gt_combine(Ad, Bd, torch.from_numpy(bias).cuda(), relu=True, transA=tA, transB=tB)
+            ref = oracle.combine(A, Bm, bias, relu=True)
+            absr = absr + np.abs(bias)[None, :]
+        else:
+            C = B.gt_combine(Ad, Bd, transA=tA, transB=tB)
+            ref = oracle.combine(A, Bm)
+        ref = oracle.round_bf16(ref) if dtype == "bf16" else ref
+        got = down(C)
+        bound = 1e-5 * absr + 1e-30 + (2.0 ** -7 * np.abs(ref) if dtype == "bf16" else 0.0)
+        bad = ~(np.abs(got - ref) <= bound)
+        assert not bad.any(), ((M, N, K), dtype, tA, tB, padded, extras, int(bad.sum()), float(np.nanmax(np.abs(got - ref))))
