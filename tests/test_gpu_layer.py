@@ -15,7 +15,9 @@ pytestmark = pytest.mark.gpu
 def small_workloads():
     return [configs.tiny(), configs.reddit_like(11), configs.products_like(12), configs.sage_minibatch(13, 128),
             configs.reorder_stress(11, True, "sum"), configs.reorder_stress(11, False, "mean"),
-            configs.reorder_stress(11, True, "mean", 100, 47)]
+            configs.reorder_stress(11, True, "mean", 100, 47),
+            # 16,384 vertices: tall enough for the weight-stationary, streaming and one-tile weight-gradient kernels
+            configs.reorder_stress(14, True, "sum"), configs.reorder_stress(14, False, "mean"), configs.products_like(14)]
 
 
 def run_model(cfg, fwd_order, bwd_order, pad=True, ref=None, fold=False):
