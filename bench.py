@@ -42,6 +42,10 @@ def build_workload(name, scale):
         return configs.reorder_stress(scale or 20, True, "sum")
     if name == "c5b":
         return configs.reorder_stress(scale or 20, False, "sum")
+    if name == "c5a_mean":
+        return configs.reorder_stress(scale or 20, True, "mean")
+    if name == "c5b_mean":
+        return configs.reorder_stress(scale or 20, False, "mean")
     if name == "c6a":
         return configs.paper_batch("light")
     if name == "c6b":
@@ -473,7 +477,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", default="c3")
+    ap.add_argument("--config", default="c3", help="c1 c2 c3 c4 c5a c5b c5a_mean c5b_mean c6a c6b")
     ap.add_argument("--scale", type=int, default=0, help="override the vertex-count exponent (testing)")
     ap.add_argument("--fwd-order", default="auto")
     ap.add_argument("--bwd-order", default="auto")
