@@ -564,7 +564,7 @@ SplitPlan plan_split(int transA, int64_t M, int64_t N, int64_t K, bool x3, bool 
         // reduction all run equally long, so a few left over once the places are full double the kernel's
         // time (5 tiles x 103 ranges = 515 blocks took 0.31 ms, 5 x 102 = 510 take 0.17 ms)
         // (three per CU for the 128 x 64 tile of the split-bf16 kernel: 46 KB of LDS, 134 registers)
-        want = ((x3 && t.bm * t.bn <= 128 * 64) ? 768 : 512) / tiles;
+        want = ((x3 && t.bm == 128 && t.bn == 64) ? 768 : 512) / tiles;
         max_by_len = K / (4 * KT);                            // at least 4 k-tiles per split
     }
     if (want > max_by_len) want = max_by_len;

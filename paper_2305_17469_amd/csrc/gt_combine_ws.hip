@@ -168,7 +168,9 @@ __device__ inline void ws_epilogue_rows_f32(const GemmArgs &g, floatx16 (&acc)[N
 // The same for a bf16 C whose rows are 16-byte aligned: two 32-column groups at a time are rounded
 // to bf16, staged as 32 rows x 64 columns (128 bytes + 16 of padding per row) and written eight lanes
 // per row, 16 bytes per lane: whole 128-byte lines again.
-template <bool EX, bool MK, int NB>
+// LATE: the mask vectors are requested when they are needed instead of before the round is staged (the
+// instances with two wavefronts per SIMD have no 16 registers to hold them meanwhile).
+template <bool EX, bool MK, bool LATE, int NB>
 __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[NB], int64_t row0, int64_t n0, int lane,
                                              uint32_t *stage) {
     static_assert(NB % 2 == 0, "column groups are staged in pairs");
@@ -177,7 +179,7 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
 #pragma unroll
     for (int bp = 0; bp < NB / 2; ++bp) {
         uint4 mkv[4];
-        if constexpr (MK) {   // requested before the staging below, so that the round trip overlaps it
+        if constexpr (MK && !LATE) {   // requested before the staging below, so that the round trip overlaps it
 #pragma unroll
             for (int it = 0; it < 4; ++it) {
                 int64_t row = row0 + it * 8 + (lane >> 3);
@@ -210,7 +212,9 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
             int64_t row = row0 + rr;
             if (row >= g.M) row = g.M - 1;
             if constexpr (MK) {
-                const uint4 mk = mkv[it];
+                const uint4 mk = LATE ? *reinterpret_cast<const uint4 *>(static_cast<const gemm_bf16_t *>(g.mask) + row * g.ldmask +
+                                                                         n0 + bp * 64 + (lane & 7) * 8)
+                                      : mkv[it];
                 v.x = ws_mask_pair(v.x, mk.x); v.y = ws_mask_pair(v.y, mk.y);
                 v.z = ws_mask_pair(v.z, mk.z); v.w = ws_mask_pair(v.w, mk.w);
             }
@@ -244,11 +248,13 @@ constexpr int ws_per_cu() { return ws_lds_bytes<T, NB, NS, 4>() <= 80 * 1024 ? 2
 
 // EX: bias and / or ReLU present.  C has the element type of A; products with a row scale or an
 // addend stay on the tiled kernel.
-// FAST: N is a multiple of the slice width and C allows vector stores.  Then the row loop is kept
-// free of branches (loads past the end re-read the last block, masks are always applied, rows past
-// M store the last row's values onto the last row): with control flow in the loop the compiler
-// waits for ALL outstanding memory operations before it touches a prefetched slice, i.e. also for
-// the previous block's stores, which costs a store round trip per block.
+// The slice loop is free of branches for every shape (loads past the end re-read the last block,
+// slices and chunks at or past K re-read the row's first chunk and are staged as zeros, masks are
+// always applied): with control flow in it the compiler waits for ALL outstanding memory
+// operations before it touches a prefetched slice.
+// FAST: N is a multiple of the slice width and C allows vector stores; then the epilogue is
+// straight-line code as well (rows past M store the last row's values onto the last row), and the
+// wait at the head of the row loop does not include the previous block's stores.
 // HALF (one-slice instances): K is at most half a slice, the MFMA steps of the empty half are left out
 // (2^20 x 16 -> 1024 fp32 spent 0.44 of its 1.0 ms multiplying zeros).
 template <typename T, int NB, int NS, bool EX, bool FAST, bool MK, bool HALF>
@@ -272,7 +278,6 @@ __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB
     const T *B = static_cast<const T *>(g.B);
     const int64_t n0 = (int64_t)blockIdx.y * BN;
     for (int n = threadIdx.x; n < BN; n += NT) bias_lds[n] = (g.bias && n0 + n < g.N) ? g.bias[n0 + n] : 0.0f;
-    const int nslices = (int)((g.K + SK - 1) / SK);
 
     // the weight slice, once: Ws[n][k] = op(B)(k, n0 + n), zero outside (K, N).  16-byte loads,
     // several in flight per thread (the matrix is small, but one dependent load per element would
@@ -349,14 +354,19 @@ __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB
     if (rb >= nrb) return;   // no workgroup barrier below this point
     // PD slices of loads are in flight per wavefront: the whole next block where the registers allow
     // it; with two wavefronts per SIMD (256 registers each) and four slices, two slices ahead
-    constexpr int PD = (FAST && NS == 4 && NW > 4) ? 2 : NS;
+    constexpr int PD = (NS == 4 && NW > 4) ? 2 : NS;
     uint4 R[PD][4];
 #pragma unroll
     for (int s = 0; s < PD; ++s)
-        if (FAST || s < nslices) ws_load_slice<T>(R[s], A, g.lda, rb, s, g.M, g.K, lane);
+        ws_load_slice<T>(R[s], A, g.lda, rb, s, g.M, g.K, lane);
     for (; rb < nrb; rb += stride) {
         const bool more = rb + stride < nrb;
         const int64_t rb_next = more ? rb + stride : rb;
+        // this lane's element offset inside a slice.  Where registers are tight it passes through an empty
+        // asm statement once per block: otherwise the compiler computes the masks of all slices ahead of
+        // the row loop, keeps them in registers and spills
+        int kb = (lane & 7) * HK;
+        if (NW > 4) __asm__ volatile("" : "+v"(kb));
         // accumulators start from the bias of their columns (register r of lane half h: column
         // 8 (r / 4) + 4 h + r % 4 of the group), so the epilogue has nothing to add
         floatx16 acc[NB];
@@ -377,29 +387,21 @@ __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB
         }
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            if (!FAST && s >= nslices) continue;   // uniform
             // LDS operations of one wavefront execute in program order; the compiler must not move
             // this slice's stage writes above the previous slice's fragment reads
             __asm__ volatile("" ::: "memory");
             // registers -> stage (row-major, elements at or past K zeroed), then refill the registers
-            const int64_t left = g.K - ((int64_t)s * SK + (lane & 7) * HK);
-            const int nv = left >= HK ? HK : (left > 0 ? (int)left : 0);
+            const int left = (int)g.K - (s * SK + kb);
+            const int nv = left >= HK ? HK : (left > 0 ? left : 0);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                uint4 v = R[s % PD][j];
-                if (FAST) v = ws_mask<T>(v, nv);
-                else if (nv < HK) v = ws_mask<T>(v, nv);
+                const uint4 v = ws_mask<T>(R[s % PD][j], nv);
                 *reinterpret_cast<uint4 *>(As + ((lane >> 3) + 8 * j) * ASTR + (lane & 7) * HK) = v;
             }
-            if (FAST) {
-                if (s + PD < NS) ws_load_slice<T>(R[s % PD], A, g.lda, rb, s + PD, g.M, g.K, lane);
-                else ws_load_slice<T>(R[s % PD], A, g.lda, rb_next, s + PD - NS, g.M, g.K, lane);
-            } else if (more) {
-                ws_load_slice<T>(R[s], A, g.lda, rb + stride, s, g.M, g.K, lane);
-            }
+            if (s + PD < NS) ws_load_slice<T>(R[s % PD], A, g.lda, rb, s + PD, g.M, g.K, lane);
+            else ws_load_slice<T>(R[s % PD], A, g.lda, rb_next, s + PD - NS, g.M, g.K, lane);
 #pragma unroll
             for (int c = 0; c < (HALF ? SK / CK / 2 : SK / CK); ++c) {
-                if (!FAST && (int64_t)s * SK + c * CK >= g.K) continue;   // uniform: nothing left in this slice
                 const uint4 a = *reinterpret_cast<const uint4 *>(As + l32 * ASTR + c * CK + h * HK);
                 const T *wrow = Ws + l32 * WSTR + s * SK + c * CK + h * HK;
                 if constexpr (sizeof(T) == 4) {
@@ -428,7 +430,7 @@ __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB
         }
         const int64_t row = rb * 32 + l32;
         if constexpr (FAST && sizeof(T) == 4) ws_epilogue_rows_f32<EX, MK, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<float *>(As));
-        else if constexpr (FAST) ws_epilogue_rows_bf16<EX, MK, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<uint32_t *>(As));
+        else if constexpr (FAST) ws_epilogue_rows_bf16<EX, MK, (NW > 4), NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<uint32_t *>(As));
         else if (row < g.M) ws_epilogue<sizeof(T) == 2, EX, false, NB>(g, acc, row, n0, h, out_vec);
     }
 }
@@ -476,7 +478,6 @@ __global__ void __launch_bounds__(256, (ws_x3_per_cu<NB, NS>())) k_gemm_ws_x3(co
     const float *B = static_cast<const float *>(g.B);
     const int64_t n0 = (int64_t)blockIdx.y * BN;
     for (int n = threadIdx.x; n < BN; n += 256) bias_lds[n] = (g.bias && n0 + n < g.N) ? g.bias[n0 + n] : 0.0f;
-    const int nslices = (int)((g.K + SK - 1) / SK);
 
     // the weight slice, once, as three planes: Wp[plane][n][k] = piece of op(B)(k, n0 + n), zero
     // outside (K, N).  A thread takes quads of four elements that are consecutive in memory, eight
@@ -544,7 +545,7 @@ __global__ void __launch_bounds__(256, (ws_x3_per_cu<NB, NS>())) k_gemm_ws_x3(co
     uint4 R[NS][4];
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-        if (FAST || s < nslices) ws_load_slice<float>(R[s], A, g.lda, rb, s, g.M, g.K, lane);
+        ws_load_slice<float>(R[s], A, g.lda, rb, s, g.M, g.K, lane);
     for (; rb < nrb; rb += stride) {
         const bool more = rb + stride < nrb;
         const int64_t rb_next = more ? rb + stride : rb;
@@ -564,22 +565,17 @@ __global__ void __launch_bounds__(256, (ws_x3_per_cu<NB, NS>())) k_gemm_ws_x3(co
         }
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            if (!FAST && s >= nslices) continue;   // uniform
             __asm__ volatile("" ::: "memory");     // stage writes stay below the previous slice's fragment reads
             const int64_t left = g.K - ((int64_t)s * SK + (lane & 7) * 4);
             const int nv = left >= 4 ? 4 : (left > 0 ? (int)left : 0);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                uint4 v = R[s][j];
-                if (FAST) v = ws_mask<float>(v, nv);
-                else if (nv < 4) v = ws_mask<float>(v, nv);
+                const uint4 v = ws_mask<float>(R[s][j], nv);
                 *reinterpret_cast<uint4 *>(As + ((lane >> 3) + 8 * j) * ASTR + (lane & 7) * 4) = v;
             }
-            if (FAST) ws_load_slice<float>(R[s], A, g.lda, rb_next, s, g.M, g.K, lane);
-            else if (more) ws_load_slice<float>(R[s], A, g.lda, rb + stride, s, g.M, g.K, lane);
+            ws_load_slice<float>(R[s], A, g.lda, rb_next, s, g.M, g.K, lane);
 #pragma unroll
             for (int t = 0; t < SK / 16; ++t) {    // MFMA steps of 16 k: lane half h supplies k = 16 t + 8 h .. + 7
-                if (!FAST && (int64_t)s * SK + t * 16 >= g.K) continue;   // uniform: nothing left in this slice
                 const float *ap = As + l32 * ASTR + t * 16 + h * 8;
                 const float4 a0 = *reinterpret_cast<const float4 *>(ap), a1 = *reinterpret_cast<const float4 *>(ap + 4);
                 const float x[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
