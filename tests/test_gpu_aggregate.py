@@ -184,3 +184,46 @@ def test_bf16_outputs_round_to_nearest_even_bit_for_bit():
     assert np.isinf(ref).any() and not np.isnan(ref).any()
     bad = got != ref
     assert not bad.any(), (int(bad.sum()), exact[bad][:4], got[bad][:4], ref[bad][:4])
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_aggregate_random_graphs(seed):
+    """Seeded random bipartite and square graphs (empty graphs, single rows, empty rows, one row holding
+    most of the edges so that it is split, duplicate-free random edges), random widths and strides,
+    with and without per-edge weights, every reduction, both directions."""
+    from paper_2305_17469_amd import binding as B
+    rng = np.random.default_rng(seed)
+    for it in range(24):
+        n_dst = int(rng.choice([1, 2, 7, 64, 257, 1000, 5000]))
+        n_src = n_dst if it % 3 == 0 else int(rng.choice([1, 3, 50, 333, 4096]))
+        n_e = int(rng.choice([0, 1, 5, 200, 3000, 40000]))
+        n_e = min(n_e, n_dst * n_src)
+        src = rng.integers(0, n_src, n_e)
+        dst = rng.integers(0, n_dst, n_e)
+        if n_e >= 3000 and n_src >= 333:      # a hub: one destination takes a long run of distinct sources
+            k = min(n_src, 2500)
+            src = np.concatenate([src, rng.permutation(n_src)[:k]])
+            dst = np.concatenate([dst, np.full(k, int(rng.integers(0, n_dst)))])
+        rp, ci = graphs.csr_from_pairs(src, dst, n_dst, n_src)
+        F = int(rng.choice([1, 2, 5, 8, 16, 31, 64, 100, 130, 256, 300]))
+        dtype = "bf16" if rng.random() < 0.5 else "f32"
+        ld = F if rng.random() < 0.5 else pad_to(F, dtype) + int(rng.choice([0, 8]))
+        ew = rng.uniform(0.25, 2.0, ci.size).astype(np.float32) if rng.random() < 0.5 else None
+        g = B.Graph(up_i32(rp), up_i32(ci), n_src, None if ew is None else torch.from_numpy(ew).cuda())
+        X = tensors.normal((n_src, F), seed=seed * 100 + it)
+        G = tensors.normal((n_dst, F), seed=seed * 100 + it + 50)
+        if dtype == "bf16":
+            X, G = tensors.bf16_values(X), tensors.bf16_values(G)
+        modes = ("sum", "mean", "symnorm") if n_src == n_dst else ("sum", "mean")
+        for reduce in modes:
+            announce("aggregate random", seed, it, dtype, (n_dst, n_src, int(ci.size)), "F", F, "ld", ld, reduce, "ew", ew is not None)
+            Y = empty_feat(n_dst, F, dtype, ld)
+            B.gt_aggregate_fwd(g, reduce, up_feat(X, dtype, ld), out=Y)
+            ref = oracle.aggregate_fwd(rp, ci, n_src, X, reduce, ew)
+            absr = oracle.aggregate_fwd(rp, ci, n_src, np.abs(X), reduce, ew)
+            _check(down(Y), oracle.round_bf16(ref) if dtype == "bf16" else ref, absr, dtype, ("fwd", it, reduce))
+            dX = empty_feat(n_src, F, dtype, ld)
+            B.gt_aggregate_bwd(g, reduce, up_feat(G, dtype, ld), out=dX)
+            ref = oracle.aggregate_bwd(rp, ci, n_src, G, reduce, ew)
+            absr = oracle.aggregate_bwd(rp, ci, n_src, np.abs(G), reduce, ew)
+            _check(down(dX), oracle.round_bf16(ref) if dtype == "bf16" else ref, absr, dtype, ("bwd", it, reduce))
