@@ -397,13 +397,16 @@ __global__ void __launch_bounds__(256) k_reduce_partials(const AggArgs a) {
 #pragma unroll
         for (int i = 0; i < V; ++i) msk[p][i] = 1.0f;
     if (a.mask) load_mask_row<T, V, G, NP>(a, s.row, gl, col0, msk);
-    // Four partial rows are requested at a time (branch free: a request past the end re-reads the
+    // UR partial rows are requested at a time (branch free: a request past the end re-reads the
     // last row and is discarded) and added in chunk order.  Partial rows are padded to a multiple
-    // of 8 floats, so whole vectors can be read; padding lanes are never stored.
-    for (int k = 0; k < s.count; k += 4) {
-        float t[4][NP][V];
+    // of 8 floats, so whole vectors can be read; padding lanes are never stored.  The kernel runs as
+    // long as its longest row (a hub of 86 K entries has 170 partial rows), one memory round trip
+    // per UR rows: sixteen at a time where the registers allow it.
+    constexpr int UR = NP * V <= 8 ? 16 : (NP * V <= 16 ? 8 : 4);
+    for (int k = 0; k < s.count; k += UR) {
+        float t[UR][NP][V];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < UR; ++u) {
             const int kk = (k + u < s.count) ? k + u : s.count - 1;
             const float *P = a.partials + (int64_t)(s.first + kk) * a.ldp;
 #pragma unroll
@@ -423,7 +426,7 @@ __global__ void __launch_bounds__(256) k_reduce_partials(const AggArgs a) {
             }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < UR; ++u) {
             const bool live = k + u < s.count;
 #pragma unroll
             for (int p = 0; p < NP; ++p)
