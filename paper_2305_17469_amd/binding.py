@@ -33,7 +33,8 @@ STATUS_NAME = {0: "GT_OK", 1: "GT_ERR_INVALID_ARG", 2: "GT_ERR_UNSUPPORTED", 3: 
 
 class gt_layer_desc(ctypes.Structure):
     _fields_ = [("reduce", c_int), ("dtype", c_int), ("act", c_int), ("in_dim", c_int64), ("out_dim", c_int64),
-                ("has_root", c_int), ("need_dx", c_int), ("in_act", c_int), ("dy_is_dz", c_int)]
+                ("has_root", c_int), ("need_dx", c_int), ("in_act", c_int), ("dy_is_dz", c_int),
+                ("pad_writable", c_int)]
 
 
 class gt_cost_coeffs(ctypes.Structure):
@@ -323,7 +324,8 @@ def gt_pull_bwd(g: Graph, reduce, h, dY, Xs, W, out_dXs=None, out_dW=None):
     return dXs, dW
 
 
-def make_desc(reduce, dtype, relu, in_dim, out_dim, has_root=False, need_dx=True, in_relu=False, dy_is_dz=False):
+def make_desc(reduce, dtype, relu, in_dim, out_dim, has_root=False, need_dx=True, in_relu=False, dy_is_dz=False,
+              pad_writable=False):
     d = gt_layer_desc()
     d.reduce = REDUCE[reduce]
     if dtype in (torch.bfloat16, "bf16"):
@@ -336,6 +338,7 @@ def make_desc(reduce, dtype, relu, in_dim, out_dim, has_root=False, need_dx=True
     d.in_dim, d.out_dim = int(in_dim), int(out_dim)
     d.has_root, d.need_dx = int(has_root), int(need_dx)
     d.in_act, d.dy_is_dz = (GT_ACT_RELU if in_relu else GT_ACT_NONE), int(dy_is_dz)
+    d.pad_writable = int(pad_writable)
     return d
 
 

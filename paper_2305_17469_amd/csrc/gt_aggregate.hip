@@ -16,7 +16,7 @@ size_t gt_aggregate_ws_bytes(const gt_graph *g, int64_t F) {
 
 gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce, gt_dtype in_dtype, gt_dtype out_dtype,
                            int64_t F, const void *X, int64_t ldx, void *Y, int64_t ldy, const float *bias, gt_act act,
-                           void *ws, size_t ws_bytes, hipStream_t st, bool traced, const void *mask, int64_t ldmask) {
+                           void *ws, size_t ws_bytes, hipStream_t st, bool traced, const void *mask, int64_t ldmask, bool pad_out) {
     const char *fn = transposed ? "gt_aggregate_bwd" : "gt_aggregate_fwd";
     if (!g) return gt_fail(GT_ERR_INVALID_ARG, "%s: g is null", fn);
     if (F < 0) return gt_fail(GT_ERR_INVALID_ARG, "%s: F < 0", fn);
@@ -58,6 +58,7 @@ gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce,
     }
     a.bias = bias; a.relu = (act == GT_ACT_RELU);
     a.mask = mask; a.ldmask = ldmask;
+    a.pad_out = pad_out ? 1 : 0;
     if (mask && ldmask < F) return gt_fail(GT_ERR_INVALID_ARG, "%s: mask leading dimension smaller than F", fn);
     a.X = X; a.ldx = ldx; a.Y = Y; a.ldy = ldy; a.F = F;
     a.partials = static_cast<float *>(ws); a.ldp = (F + 7) / 8 * 8;

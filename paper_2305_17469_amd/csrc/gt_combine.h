@@ -9,7 +9,7 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
                       const void *A, int64_t lda, const void *B, int64_t ldb, const float *bias, const float *rowscale,
                       gt_act act, const void *Cin, int64_t ldcin, void *C, int64_t ldc, gt_dtype c_dtype, void *ws,
                       size_t ws_bytes, hipStream_t st, const void *mask = nullptr, int64_t ldmask = 0,
-                      float *colsum_b = nullptr);
+                      float *colsum_b = nullptr, bool pad_c = false);
 // colsum_b (transA products with !transB only): also writes the N column sums of op(B) there, a
 // by-product of streaming B (the bias gradient when B is dZ); sums have a fixed order.
 
@@ -43,6 +43,8 @@ struct GemmArgs {
     int vecA, vecB;                // 16-byte loads allowed
     int ntm, ntn;                  // output tiles along M and N (host side; see gemm_tile_of_block)
     int split_xcd;                 // splits % 8 == 0: the output tiles of one k-range run on one XCD
+    int pad_c;                     // rows of C are padded and the padding may be written (zeros): a row's last
+                                   // 16 bytes go out whole instead of in pieces (honoured by the staged epilogues)
 };
 
 // Workgroups are handed to the 8 XCDs round-robin by linear id, and each XCD has its own L2.  The

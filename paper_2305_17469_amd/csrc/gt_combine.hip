@@ -664,7 +664,7 @@ __global__ void __launch_bounds__(256) k_colsum_splits(const float *partial, int
 gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
                       const void *A, int64_t lda, const void *B, int64_t ldb, const float *bias, const float *rowscale,
                       gt_act act, const void *Cin, int64_t ldcin, void *C, int64_t ldc, gt_dtype c_dtype, void *ws,
-                      size_t ws_bytes, hipStream_t st, const void *mask, int64_t ldmask, float *colsum_b) {
+                      size_t ws_bytes, hipStream_t st, const void *mask, int64_t ldmask, float *colsum_b, bool pad_c) {
     if (dtype != GT_F32 && dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown dtype", fn);
     if (mask && ldmask < N) return gt_fail(GT_ERR_INVALID_ARG, "%s: mask leading dimension too small", fn);
     if (c_dtype != GT_F32 && c_dtype != GT_BF16) return gt_fail(GT_ERR_INVALID_ARG, "%s: unknown c_dtype", fn);
@@ -699,6 +699,7 @@ gt_status gt_gemm_run(const char *fn, gt_dtype dtype, int transA, int transB, in
     g.bias = bias; g.rowscale = rowscale; g.relu = (act == GT_ACT_RELU); g.c_bf16 = (c_dtype == GT_BF16);
     g.Cin = Cin; g.ldcin = ldcin;
     g.mask = mask; g.ldmask = ldmask;
+    g.pad_c = pad_c ? 1 : 0;
     g.colsum = colsum_b ? reinterpret_cast<float *>(static_cast<char *>(ws) + need_part) : nullptr;
     if (mask && p.splits > 1) return gt_fail(GT_ERR_INTERNAL, "%s: an output mask on a split reduction", fn);
     if (p.splits > 1) { g.C = ws; g.ldc = N; } else { g.C = C; g.ldc = ldc; }

@@ -170,7 +170,10 @@ __device__ inline void ws_epilogue_rows_f32(const GemmArgs &g, floatx16 (&acc)[N
 // per row, 16 bytes per lane: whole 128-byte lines again.
 // LATE: the mask vectors are requested when they are needed instead of before the round is staged (the
 // instances with two wavefronts per SIMD have no 16 registers to hold them meanwhile).
-template <bool EX, bool MK, bool LATE, int NB>
+// RAGGED: N need not fill the column slice: a lane whose eight columns straddle N stores the ones inside
+// one by one, a lane past N stores nothing (config 3's 256 -> 47: storing from registers wrote every
+// 96-byte row as twelve 8-byte pieces spread over six instructions).
+template <bool EX, bool MK, bool LATE, bool RAGGED, int NB>
 __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[NB], int64_t row0, int64_t n0, int lane,
                                              uint32_t *stage) {
     static_assert(NB % 2 == 0, "column groups are staged in pairs");
@@ -184,8 +187,9 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
             for (int it = 0; it < 4; ++it) {
                 int64_t row = row0 + it * 8 + (lane >> 3);
                 if (row >= g.M) row = g.M - 1;
-                mkv[it] = *reinterpret_cast<const uint4 *>(static_cast<const gemm_bf16_t *>(g.mask) + row * g.ldmask + n0 +
-                                                          bp * 64 + (lane & 7) * 8);
+                const int64_t cm = n0 + bp * 64 + (lane & 7) * 8;
+                mkv[it] = *reinterpret_cast<const uint4 *>(static_cast<const gemm_bf16_t *>(g.mask) + row * g.ldmask +
+                                                          ((!RAGGED || cm < g.N) ? cm : 0));
             }
         }
         __asm__ volatile("" ::: "memory");
@@ -211,14 +215,30 @@ __device__ inline void ws_epilogue_rows_bf16(const GemmArgs &g, floatx16 (&acc)[
             uint4 v = *reinterpret_cast<const uint4 *>(stage + rr * SSTR + (lane & 7) * 4);
             int64_t row = row0 + rr;
             if (row >= g.M) row = g.M - 1;
+            const int64_t c0 = n0 + bp * 64 + (lane & 7) * 8;
             if constexpr (MK) {
                 const uint4 mk = LATE ? *reinterpret_cast<const uint4 *>(static_cast<const gemm_bf16_t *>(g.mask) + row * g.ldmask +
-                                                                         n0 + bp * 64 + (lane & 7) * 8)
+                                                                         ((!RAGGED || c0 < g.N) ? c0 : 0))
                                       : mkv[it];
                 v.x = ws_mask_pair(v.x, mk.x); v.y = ws_mask_pair(v.y, mk.y);
                 v.z = ws_mask_pair(v.z, mk.z); v.w = ws_mask_pair(v.w, mk.w);
             }
-            *reinterpret_cast<uint4 *>(static_cast<gemm_bf16_t *>(g.C) + row * g.ldc + n0 + bp * 64 + (lane & 7) * 8) = v;
+            gemm_bf16_t *dst = static_cast<gemm_bf16_t *>(g.C) + row * g.ldc + c0;
+            if constexpr (!RAGGED) {
+                *reinterpret_cast<uint4 *>(dst) = v;
+            } else {
+                const int64_t left = g.N - c0;
+                if (left >= 8 || (g.pad_c && left > 0 && c0 + 8 <= g.ldc)) {   // (columns past N hold zeros)
+                    *reinterpret_cast<uint4 *>(dst) = v;
+                } else if (left > 0) {
+                    // 1..7 columns as an 8-, a 4- and a 2-byte piece
+                    if (left & 4) *reinterpret_cast<uint2 *>(dst) = make_uint2(v.x, v.y);
+                    const uint32_t w2 = (left & 4) ? v.z : v.x, w3 = (left & 4) ? v.w : v.y;
+                    gemm_bf16_t *d2 = dst + (left & 4);
+                    if (left & 2) *reinterpret_cast<uint32_t *>(d2) = w2;
+                    if (left & 1) d2[left & 2] = (gemm_bf16_t)(((left & 2) ? w3 : w2) & 0xffffu);
+                }
+            }
         }
     }
     __asm__ volatile("" ::: "memory");
@@ -257,7 +277,7 @@ constexpr int ws_per_cu() { return ws_lds_bytes<T, NB, NS, 4>() <= 80 * 1024 ? 2
 // wait at the head of the row loop does not include the previous block's stores.
 // HALF (one-slice instances): K is at most half a slice, the MFMA steps of the empty half are left out
 // (2^20 x 16 -> 1024 fp32 spent 0.44 of its 1.0 ms multiplying zeros).
-template <typename T, int NB, int NS, bool EX, bool FAST, bool MK, bool HALF>
+template <typename T, int NB, int NS, bool EX, bool FAST, bool MK, bool HALF, bool RG>
 __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB, NS>())) k_gemm_ws(const GemmArgs g, const int transB) {
     constexpr int NW = ws_waves<T, NB, NS>(), NT = NW * 64;
     static_assert(!HALF || NS == 1, "HALF is a form of the one-slice instances");
@@ -430,7 +450,7 @@ __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB
         }
         const int64_t row = rb * 32 + l32;
         if constexpr (FAST && sizeof(T) == 4) ws_epilogue_rows_f32<EX, MK, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<float *>(As));
-        else if constexpr (FAST) ws_epilogue_rows_bf16<EX, MK, (NW > 4), NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<uint32_t *>(As));
+        else if constexpr (FAST) ws_epilogue_rows_bf16<EX, MK, (NW > 4), RG, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<uint32_t *>(As));
         else if (row < g.M) ws_epilogue<sizeof(T) == 2, EX, false, NB>(g, acc, row, n0, h, out_vec);
     }
 }
@@ -828,7 +848,7 @@ gt_status ws_x3_launch(const GemmArgs &g, int transB, hipStream_t st) {
                   : ws_x3_launch_ex<NB, NS, false, false>(g, transB, st);
 }
 
-template <typename T, int NB, int NS, bool EX, bool FAST, bool MK = false, bool HALF = false>
+template <typename T, int NB, int NS, bool EX, bool FAST, bool MK = false, bool HALF = false, bool RG = false>
 gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     constexpr int NW = ws_waves<T, NB, NS>();
     constexpr size_t lds = ws_lds_bytes<T, NB, NS, NW>();
@@ -836,7 +856,7 @@ gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     // it (a host-side setting, no stream operation), so the first launch of an instance behaves
     // like any other, also under stream capture.
     if (lds > 64 * 1024) {
-        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX, FAST, MK, HALF>),
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws<T, NB, NS, EX, FAST, MK, HALF, RG>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     }
     const int64_t nrb = (g.M + 31) / 32;
@@ -844,7 +864,7 @@ gt_status ws_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     int64_t gx = (nrb + NW - 1) / NW;
     if (gx > 256 * per_cu) gx = 256 * per_cu;
     dim3 grid((unsigned)gx, (unsigned)((g.N + NB * 32 - 1) / (NB * 32)), 1);
-    k_gemm_ws<T, NB, NS, EX, FAST, MK, HALF><<<grid, NW * 64, lds, st>>>(g, transB);
+    k_gemm_ws<T, NB, NS, EX, FAST, MK, HALF, RG><<<grid, NW * 64, lds, st>>>(g, transB);
     GT_LAUNCH_CHECK("k_gemm_ws");
     return GT_OK;
 }
@@ -866,6 +886,14 @@ gt_status ws_launch(const GemmArgs &g, int transB, hipStream_t st) {
             return g.mask ? ws_launch_ex<T, NB, NS, true, true, true>(g, transB, st)
                  : extras ? ws_launch_ex<T, NB, NS, true, true>(g, transB, st)
                           : ws_launch_ex<T, NB, NS, false, true>(g, transB, st);
+    }
+    if constexpr (NB == 2 && sizeof(T) == 2) {   // at most 64 bf16 columns, any N: the staged, row-major epilogue with a ragged end
+        const bool rows = g.ldc % 8 == 0 && (((uintptr_t)g.C & 15) == 0) &&
+                          (!g.mask || (g.ldmask % 8 == 0 && ((uintptr_t)g.mask & 15) == 0));
+        if (rows)
+            return g.mask ? ws_launch_ex<T, NB, NS, true, true, true, false, true>(g, transB, st)
+                 : extras ? ws_launch_ex<T, NB, NS, true, true, false, false, true>(g, transB, st)
+                          : ws_launch_ex<T, NB, NS, false, true, false, false, true>(g, transB, st);
     }
     return extras ? ws_launch_ex<T, NB, NS, true, false>(g, transB, st)
                   : ws_launch_ex<T, NB, NS, false, false>(g, transB, st);

@@ -99,7 +99,8 @@ static inline size_t gt_dtype_size(gt_dtype t) { return t == GT_BF16 ? 2 : 4; }
 gt_status gt_aggregate_run(const gt_graph *g, bool transposed, gt_reduce reduce, gt_dtype in_dtype,
                            gt_dtype out_dtype, int64_t F, const void *X, int64_t ldx, void *Y, int64_t ldy,
                            const float *bias, gt_act act, void *ws, size_t ws_bytes, hipStream_t stream,
-                           bool traced = true, const void *mask = nullptr, int64_t ldmask = 0);
+                           bool traced = true, const void *mask = nullptr, int64_t ldmask = 0, bool pad_out = false);
+// pad_out: the output rows are padded and the padding is the library's to write (see gt_layer_desc.pad_writable)
 
 size_t gt_aggregate_ws_bytes(const gt_graph *g, int64_t F);
 

@@ -464,6 +464,7 @@ extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_
     const int64_t fi = d->in_dim, fo = d->out_dim;
 
     void *gws = at(scratch, L.gemm_ws);
+    const bool pad_user = d->pad_writable != 0;   // the caller's Y has padded rows whose padding may be written
     if (order == GT_AGG_FIRST) {
         // forward only (no `saved`): A X is a temporary, or is never written at all where the fused
         // kernel applies and is the faster of the two
@@ -473,11 +474,11 @@ extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_
         void *M = saved ? saved : at(scratch, L.dM);
         // M = A X (kept for the weight gradient), then the combination on n_dst rows
         s = gt_aggregate_run(g, false, d->reduce, t, t, fi, X, ldx, M, L.ldi, nullptr, GT_ACT_NONE,
-                             at(scratch, L.agg_ws), L.agg_ws_bytes, st);
+                             at(scratch, L.agg_ws), L.agg_ws_bytes, st, true, nullptr, 0, /*pad_out (own buffer)*/ true);
         if (s != GT_OK) return s;
         if (!d->has_root)
             return gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, M, L.ldi, W, fo, b, nullptr, d->act, nullptr, 0, Y, ldy,
-                               t, gws, L.gemm_ws_bytes, st);
+                               t, gws, L.gemm_ws_bytes, st, nullptr, 0, nullptr, pad_user);
         s = gt_gemm_run(fn, t, 0, 0, g->n_dst, fo, fi, M, L.ldi, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, Y,
                         ldy, t, gws, L.gemm_ws_bytes, st);
         if (s != GT_OK) return s;
@@ -486,11 +487,12 @@ extern "C" gt_status gt_layer_fwd(const gt_graph *g, const gt_layer_desc *d, gt_
         // applied as the row is written
         void *T = at(scratch, L.T);
         s = gt_gemm_run(fn, t, 0, 0, g->n_src, fo, fi, X, ldx, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, T, L.ldo,
-                        t, gws, L.gemm_ws_bytes, st);
+                        t, gws, L.gemm_ws_bytes, st, nullptr, 0, nullptr, /*pad_c (own buffer)*/ true);
         if (s != GT_OK) return s;
         const bool fuse = !d->has_root;
         s = gt_aggregate_run(g, false, d->reduce, t, t, fo, T, L.ldo, Y, ldy, fuse ? b : nullptr,
-                             fuse ? d->act : GT_ACT_NONE, at(scratch, L.agg_ws), L.agg_ws_bytes, st);
+                             fuse ? d->act : GT_ACT_NONE, at(scratch, L.agg_ws), L.agg_ws_bytes, st, true, nullptr, 0,
+                             pad_user);
         if (s != GT_OK || fuse) return s;
     }
     // root term: Y = act(Y + X[0:n_dst] W_root + b)
@@ -591,7 +593,8 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
     void *S = at(scratch, L.S);
     if (need_S) {
         // S = A^T dZ: the aggregation's derivative, outputs on the source vertices, width out_dim
-        s = gt_aggregate_run(g, true, d->reduce, t, t, fo, dZ, lddz, S, L.ldo, nullptr, GT_ACT_NONE, aws, L.agg_ws_bytes, st);
+        s = gt_aggregate_run(g, true, d->reduce, t, t, fo, dZ, lddz, S, L.ldo, nullptr, GT_ACT_NONE, aws, L.agg_ws_bytes, st,
+                             true, nullptr, 0, /*pad_out (own buffer)*/ true);
         if (s != GT_OK) return s;
     }
     if (fwd_used == GT_COMB_FIRST) {
@@ -609,15 +612,15 @@ extern "C" gt_status gt_layer_bwd(const gt_graph *g, const gt_layer_desc *d, gt_
     if (order == GT_COMB_FIRST) {
         // dX = (A^T dZ) W^T
         s = gt_gemm_run(fn, t, 0, 1, g->n_src, fi, fo, S, L.ldo, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dX, lddx,
-                        t, gws, L.gemm_ws_bytes, st, mk, ldx);
+                        t, gws, L.gemm_ws_bytes, st, mk, ldx, nullptr, d->pad_writable != 0);
     } else {
         // dM = dZ W^T (the combination's derivative uses the transposed weight), dX = A^T dM
         void *dM = at(scratch, L.dM);
         s = gt_gemm_run(fn, t, 0, 1, g->n_dst, fi, fo, dZ, lddz, W, fo, nullptr, nullptr, GT_ACT_NONE, nullptr, 0, dM, L.ldi,
-                        t, gws, L.gemm_ws_bytes, st);
+                        t, gws, L.gemm_ws_bytes, st, nullptr, 0, nullptr, /*pad_c (own buffer)*/ true);
         if (s != GT_OK) return s;
         s = gt_aggregate_run(g, true, d->reduce, t, t, fi, dM, L.ldi, dX, lddx, nullptr, GT_ACT_NONE, aws, L.agg_ws_bytes, st,
-                             true, mk, ldx);
+                             true, mk, ldx, d->pad_writable != 0);
     }
     if (s != GT_OK) return s;
     if (d->has_root) {

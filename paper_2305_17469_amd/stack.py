@@ -56,7 +56,8 @@ class LayerStack:
             # hidden layers end in a ReLU: the layer above folds its derivative into the gradient it
             # hands down (in_relu), and the layer itself then takes that gradient as dZ (dy_is_dz)
             d = B.make_desc(reduce, dtype, l < self.L - 1, dims[l], dims[l + 1], has_root=self.W_root[l] is not None,
-                            need_dx=l > 0, in_relu=fold_relu_grad and l > 0, dy_is_dz=fold_relu_grad and l < self.L - 1)
+                            need_dx=l > 0, in_relu=fold_relu_grad and l > 0, dy_is_dz=fold_relu_grad and l < self.L - 1,
+                            pad_writable=pad)   # H and dH below are this class's own padded buffers
             self.descs.append(d)
             self.bufs.append(B.LayerBuffers(g, d))
             feat_shapes += [(g.n_dst, ld(dims[l + 1])), (g.n_src if l > 0 else 0, ld(dims[l]))]

@@ -6,8 +6,8 @@ import pytest
 import torch
 
 import oracle
-from gt_inputs import configs
-from gpu_util import announce, down, max_rel_err, pad_to, relu_rounding_sets, tol_for, up_feat, up_i32
+from gt_inputs import configs, graphs, tensors
+from gpu_util import announce, down, empty_feat, max_rel_err, pad_to, relu_rounding_sets, tol_for, up_feat, up_i32
 
 pytestmark = pytest.mark.gpu
 
@@ -250,3 +250,49 @@ def test_layer_calls_check_buffer_sizes_and_overlap_before_launching():
     assert bool((Y == 7.0).all()) and bool((dX == 7.0).all())
     assert fwd(need_saved, need_scratch) == 0 and bwd(need_saved, need_scratch) == 0
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype,in_dim,out_dim", [("bf16", 64, 47), ("bf16", 47, 100), ("f32", 64, 41), ("f32", 41, 18)])
+def test_pad_writable_touches_only_the_rest_of_a_rows_last_vector(dtype, in_dim, out_dim):
+    """gt_layer_desc.pad_writable: the logical outputs are bit for bit what they are without it, the
+    padding columns up to the next multiple of 16 bytes hold zeros afterwards or are untouched, every
+    column beyond that (and, without the flag, all padding) is left as it was.  16,384 vertices, so that the
+    tall-product kernels with the staged epilogues run."""
+    from paper_2305_17469_amd import binding as B
+    rp, ci = graphs.rmat_csr(14, 8, seed=77)
+    n = rp.size - 1
+    g = B.Graph(up_i32(rp), up_i32(ci), n)
+    v = 8 if dtype == "bf16" else 4
+    X = tensors.normal((n, in_dim), seed=1)
+    W = tensors.glorot(in_dim, out_dim, seed=2)
+    dY = tensors.normal((n, out_dim), seed=3)
+    if dtype == "bf16":
+        X, W, dY = tensors.bf16_values(X), tensors.bf16_values(W), tensors.bf16_values(dY)
+    bias = torch.from_numpy(tensors.normal((out_dim,), seed=4)).cuda()
+    Xd, Wd, dYd = up_feat(X, dtype, pad_to(in_dim, dtype)), up_feat(W, dtype), up_feat(dY, dtype, pad_to(out_dim, dtype))
+    ldy, ldx = pad_to(out_dim, dtype) + 2 * v, pad_to(in_dim, dtype) + 2 * v
+    for order in ("agg_first", "comb_first"):
+        res = {}
+        for flag in (False, True):
+            announce("pad_writable", dtype, in_dim, out_dim, order, flag)
+            d = B.make_desc("sum", dtype, True, in_dim, out_dim, in_relu=True, pad_writable=flag)
+            bufs = B.LayerBuffers(g, d)
+            Y = empty_feat(n, out_dim, dtype, ldy)
+            dX = empty_feat(n, in_dim, dtype, ldx)
+            _, used = B.gt_layer_fwd(g, d, Xd, Wd, bias, bufs, order, out=Y)
+            r = B.gt_layer_bwd(g, d, used, dYd, Xd, Wd, Y, bufs, order, out_dX=dX)
+            torch.cuda.synchronize()
+            res[flag] = (Y.clone(), dX.clone(), r["dW"].clone(), r["db"].clone())
+            for T, F, ld in ((Y, out_dim, ldy), (dX, in_dim, ldx)):
+                full = T.as_strided((n, ld), (ld, 1), T.storage_offset()).float()
+                edge = pad_to(F, dtype) if flag else F
+                assert not torch.isnan(full[:, :F]).any()
+                rest = full[:, F:edge]                               # the rest of the row's last vector: zeros, or untouched
+                assert bool(((rest == 0) | torch.isnan(rest)).all())
+                assert bool(torch.isnan(full[:, edge:]).all())       # nothing beyond it was written
+                # the aggregation kernel writes these two (Y of a combination-first forward, dX of an
+                # aggregation-first backward) and does store the zeros
+                if flag and ((T is Y and order == "comb_first") or (T is dX and order == "agg_first")):
+                    assert bool((rest == 0).all())
+        for a, b in zip(res[False], res[True]):
+            assert torch.equal(a, b)
