@@ -116,7 +116,9 @@ __device__ inline void gemm_epilogue(const GemmArgs &g, floatx16 (&acc)[TM][TN],
     const int64_t ldc = partial ? g.N : g.ldc;
     if (partial) out_f += (int64_t)split * g.M * g.N;
     const bool as_bf16 = !partial && g.c_bf16;
-    const bool vec_ok = (ldc % 4 == 0) && (((uintptr_t)g.C & 15) == 0) && (col + 4 <= g.N);
+    // whole vectors: inside N, or (padded rows whose padding may be written) the row's last one, zeros past N
+    const bool vec_ok = (ldc % 4 == 0) && (((uintptr_t)g.C & 15) == 0) &&
+                        (col + 4 <= g.N || (g.pad_c && !partial && col < g.N && col + 4 <= ldc));
     float bia[4] = {0.f, 0.f, 0.f, 0.f};
     if (!partial && g.bias) {
 #pragma unroll
@@ -156,7 +158,7 @@ __device__ inline void gemm_epilogue(const GemmArgs &g, floatx16 (&acc)[TM][TN],
                                                   : static_cast<const float *>(g.mask)[row * g.ldmask + col + i];
                         x = mk > 0.0f ? x : 0.0f;
                     }
-                    v[i] = x;
+                    v[i] = (col + i < g.N) ? x : 0.0f;
                 }
             }
             if (as_bf16) {
