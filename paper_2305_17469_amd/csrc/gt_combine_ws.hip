@@ -130,7 +130,8 @@ __device__ inline void ws_epilogue(const GemmArgs &g, floatx16 (&acc)[NB], int64
 // been read) and is written row-major, eight lanes per row, so a store instruction covers whole
 // 128-byte lines of 8 rows instead of 32-byte pieces of 32 rows.  Rows past M hold the last row's
 // values (their loads were clamped to it) and are written onto the last row.
-template <bool EX, bool MK, int NB>
+// RAGGED: N need not fill the column slice (see ws_epilogue_rows_bf16).
+template <bool EX, bool MK, bool RAGGED, int NB>
 __device__ inline void ws_epilogue_rows_f32(const GemmArgs &g, floatx16 (&acc)[NB], int64_t row0, int64_t n0, int lane,
                                             float *stage) {
     constexpr int SSTR = 36;   // 32 columns + 4: the stage holds 32 x 36 floats
@@ -154,12 +155,26 @@ __device__ inline void ws_epilogue_rows_f32(const GemmArgs &g, floatx16 (&acc)[N
             float4 v = *reinterpret_cast<const float4 *>(stage + rr * SSTR + c4);
             int64_t row = row0 + rr;
             if (row >= g.M) row = g.M - 1;
+            const int64_t c0 = n0 + b * 32 + c4;
             if constexpr (MK) {   // the host passes a mask here only when its rows allow 16-byte loads
-                const float4 mk = *reinterpret_cast<const float4 *>(static_cast<const float *>(g.mask) + row * g.ldmask + n0 + b * 32 + c4);
+                const float4 mk = *reinterpret_cast<const float4 *>(static_cast<const float *>(g.mask) + row * g.ldmask +
+                                                                    ((!RAGGED || c0 < g.N) ? c0 : 0));
                 v.x = mk.x > 0.0f ? v.x : 0.0f; v.y = mk.y > 0.0f ? v.y : 0.0f;
                 v.z = mk.z > 0.0f ? v.z : 0.0f; v.w = mk.w > 0.0f ? v.w : 0.0f;
             }
-            *reinterpret_cast<float4 *>(static_cast<float *>(g.C) + row * g.ldc + n0 + b * 32 + c4) = v;
+            float *dst = static_cast<float *>(g.C) + row * g.ldc + c0;
+            if constexpr (!RAGGED) {
+                *reinterpret_cast<float4 *>(dst) = v;
+            } else {
+                const int64_t left = g.N - c0;
+                if (left >= 4 || (g.pad_c && left > 0 && c0 + 4 <= g.ldc)) {   // (columns past N hold zeros)
+                    *reinterpret_cast<float4 *>(dst) = v;
+                } else if (left > 0) {
+                    dst[0] = v.x;
+                    if (left > 1) dst[1] = v.y;
+                    if (left > 2) dst[2] = v.z;
+                }
+            }
         }
     }
     __asm__ volatile("" ::: "memory");
@@ -449,7 +464,7 @@ __global__ void __launch_bounds__((ws_waves<T, NB, NS>() * 64), (ws_per_cu<T, NB
             }
         }
         const int64_t row = rb * 32 + l32;
-        if constexpr (FAST && sizeof(T) == 4) ws_epilogue_rows_f32<EX, MK, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<float *>(As));
+        if constexpr (FAST && sizeof(T) == 4) ws_epilogue_rows_f32<EX, MK, RG, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<float *>(As));
         else if constexpr (FAST) ws_epilogue_rows_bf16<EX, MK, (NW > 4), RG, NB>(g, acc, rb * 32, n0, lane, reinterpret_cast<uint32_t *>(As));
         else if (row < g.M) ws_epilogue<sizeof(T) == 2, EX, false, NB>(g, acc, row, n0, h, out_vec);
     }
@@ -480,7 +495,7 @@ constexpr size_t ws_x3_lds_bytes() {
 template <int NB, int NS>
 constexpr int ws_x3_per_cu() { return ws_x3_lds_bytes<NB, NS>() <= 80 * 1024 ? 2 : 1; }
 
-template <int NB, int NS, bool EX, bool FAST, bool MK>
+template <int NB, int NS, bool EX, bool FAST, bool MK, bool RG>
 __global__ void __launch_bounds__(256, (ws_x3_per_cu<NB, NS>())) k_gemm_ws_x3(const GemmArgs g, const int transB) {
     constexpr int SK = 32;                      // k per slice (128 bytes of fp32)
     constexpr int KP = NS * SK;                 // K capacity of this instance
@@ -629,7 +644,7 @@ __global__ void __launch_bounds__(256, (ws_x3_per_cu<NB, NS>())) k_gemm_ws_x3(co
             }
         }
         const int64_t row = rb * 32 + l32;
-        if constexpr (FAST) ws_epilogue_rows_f32<EX, MK, NB>(g, acc, rb * 32, n0, lane, As);
+        if constexpr (FAST) ws_epilogue_rows_f32<EX, MK, RG, NB>(g, acc, rb * 32, n0, lane, As);
         else if (row < g.M) ws_epilogue<false, EX, false, NB>(g, acc, row, n0, h, out_vec);
     }
 }
@@ -816,11 +831,11 @@ static gt_status ws_stream_launch(const GemmArgs &g, int transB, hipStream_t st)
     return ws_stream_launch_n<32>(g, transB, NR, st);
 }
 
-template <int NB, int NS, bool EX, bool FAST, bool MK = false>
+template <int NB, int NS, bool EX, bool FAST, bool MK = false, bool RG = false>
 gt_status ws_x3_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     constexpr size_t lds = ws_x3_lds_bytes<NB, NS>();
     if (lds > 64 * 1024) {
-        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws_x3<NB, NS, EX, FAST, MK>),
+        GT_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_ws_x3<NB, NS, EX, FAST, MK, RG>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     }
     const int64_t nrb = (g.M + 31) / 32;
@@ -828,7 +843,7 @@ gt_status ws_x3_launch_ex(const GemmArgs &g, int transB, hipStream_t st) {
     int64_t gx = (nrb + 3) / 4;
     if (gx > 256 * per_cu) gx = 256 * per_cu;
     dim3 grid((unsigned)gx, (unsigned)((g.N + NB * 32 - 1) / (NB * 32)), 1);
-    k_gemm_ws_x3<NB, NS, EX, FAST, MK><<<grid, 256, lds, st>>>(g, transB);
+    k_gemm_ws_x3<NB, NS, EX, FAST, MK, RG><<<grid, 256, lds, st>>>(g, transB);
     GT_LAUNCH_CHECK("k_gemm_ws_x3");
     return GT_OK;
 }
@@ -843,6 +858,14 @@ gt_status ws_x3_launch(const GemmArgs &g, int transB, hipStream_t st) {
             return g.mask ? ws_x3_launch_ex<NB, NS, true, true, true>(g, transB, st)
                  : extras ? ws_x3_launch_ex<NB, NS, true, true>(g, transB, st)
                           : ws_x3_launch_ex<NB, NS, false, true>(g, transB, st);
+    }
+    if constexpr (NB == 2) {   // at most 64 fp32 columns, any N: the staged, row-major epilogue with a ragged end
+        const bool rows = g.ldc % 4 == 0 && (((uintptr_t)g.C & 15) == 0) &&
+                          (!g.mask || (g.ldmask % 8 == 0 && ((uintptr_t)g.mask & 15) == 0));
+        if (rows)
+            return g.mask ? ws_x3_launch_ex<NB, NS, true, true, true, true>(g, transB, st)
+                 : extras ? ws_x3_launch_ex<NB, NS, true, true, false, true>(g, transB, st)
+                          : ws_x3_launch_ex<NB, NS, false, true, false, true>(g, transB, st);
     }
     return extras ? ws_x3_launch_ex<NB, NS, true, false>(g, transB, st)
                   : ws_x3_launch_ex<NB, NS, false, false>(g, transB, st);
